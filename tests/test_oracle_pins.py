@@ -1,0 +1,270 @@
+"""Pins for the fp64 CPU oracle: each test checks it against something other than itself --
+closed forms, library routines, brute force, algebraic identities the paper states.  A dropped
+term, a wrong sign or index, or a transposed operand in the oracle fails at least one of them.
+"""
+import math
+
+import numpy as np
+import pytest
+import scipy.linalg
+import torch
+
+import oracle
+from oracle import methods, metrics
+import synth_inputs as si
+
+
+def ones_strict(C):
+    return np.tril(np.ones((C, C)), -1)
+
+
+# ---------------------------------------------------------------- closed forms (P1-P3)
+@pytest.mark.parametrize("C", [2, 4, 16, 64, 128])
+def test_difference_operator(C):
+    # inverse of the cumulative-sum matrix is the first-difference matrix
+    T = oracle.tri_inv(ones_strict(C)[None])[0]
+    expect = np.eye(C) - np.eye(C, k=-1)
+    assert np.array_equal(T, expect)
+
+
+@pytest.mark.parametrize("C,beta", [(8, 0.25), (64, 0.7), (128, 0.95)])
+def test_geometric_rows(C, beta):
+    # A = beta * ones_strict  =>  T_ij = -beta (1 - beta)^(i-j-1) for i > j
+    T = oracle.tri_inv((beta * ones_strict(C))[None])[0]
+    i, j = np.indices((C, C))
+    expect = np.where(i > j, -beta * (1.0 - beta) ** np.clip(i - j - 1, 0, None), (i == j).astype(float))
+    assert np.allclose(T, expect, rtol=1e-13, atol=1e-300)
+
+
+@pytest.mark.parametrize("C", [4, 64, 128])
+def test_powers_of_two(C):
+    # A = -ones_strict  =>  T_ij = 2^(i-j-1), exact in fp64 up to 2^126
+    T = oracle.tri_inv((-ones_strict(C))[None])[0]
+    i, j = np.indices((C, C))
+    expect = np.where(i > j, np.ldexp(1.0, np.clip(i - j - 1, 0, None)), (i == j).astype(float))
+    assert np.array_equal(T, expect)
+
+
+# ---------------------------------------------------------------- P4 binomial powers (Sec. 3.2)
+@pytest.mark.parametrize("C", [16, 64])
+def test_binomial_powers_pin_neumann_helper(C):
+    # (ones_strict^k)_ij = binom(i-j-1, k-1): pins the repeated-squaring Y of Alg. 5
+    L = ones_strict(C)
+    for iters in range(0, int(math.log2(C // 2)) + 1):
+        _, Y = methods.mch(L, iters=iters, return_Y=True)
+        k = 2 ** iters
+        for (i, j) in [(C - 1, 0), (C // 2, 0), (C - 1, C // 4), (k, 0), (k - 1, 0)]:
+            want = math.comb(i - j - 1, k - 1) if i - j >= k else 0
+            assert Y[i, j] == pytest.approx(want, rel=1e-12), (iters, i, j)
+    # corner of L^(n/2) grows like 2^n / sqrt(n): overflows fp16 long before n = 64
+    assert math.comb(C - 2, C // 2 - 1) > (65504 if C >= 32 else 0)
+
+
+# ---------------------------------------------------------------- library routines (P11), brute force (P12)
+def _cofactor_inverse(M):
+    n = M.shape[0]
+
+    def det(X):
+        if X.shape[0] == 1:
+            return X[0, 0]
+        return sum((-1) ** c * X[0, c] * det(np.delete(np.delete(X, 0, 0), c, 1)) for c in range(X.shape[0]))
+
+    d = det(M)
+    inv = np.empty_like(M)
+    for r in range(n):
+        for c in range(n):
+            minor = np.delete(np.delete(M, r, 0), c, 1)
+            inv[c, r] = (-1) ** (r + c) * (det(minor) if n > 1 else 1.0) / d
+    return inv
+
+
+@pytest.mark.parametrize("C", [2, 4, 6])
+def test_brute_force_cofactor(C):
+    rng = np.random.default_rng(C)
+    A = np.tril(rng.normal(size=(3, C, C)), -1)
+    T = oracle.tri_inv(A)
+    for m in range(3):
+        assert np.allclose(T[m], _cofactor_inverse(np.eye(C) + A[m]), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("C", [8, 64, 128])
+def test_library_inverse_and_triangular_solve(C):
+    rng = np.random.default_rng(100 + C)
+    A = np.tril(rng.normal(size=(4, C, C)) * (0.5 / math.sqrt(C)), -1)
+    T = oracle.tri_inv(A)
+    for m in range(4):
+        M = np.eye(C) + A[m]
+        assert np.allclose(T[m], np.linalg.inv(M), rtol=1e-10, atol=1e-12)
+        ts = scipy.linalg.solve_triangular(M, np.eye(C), lower=True, unit_diagonal=True)
+        assert np.allclose(T[m], ts, rtol=1e-12, atol=1e-14)
+
+
+def test_upper_triangle_and_diagonal_are_ignored():
+    A = si.random_strict_lower(3, 64, 0.1, seed=1, garbage_upper=True)
+    clean = torch.tril(torch.nan_to_num(A, nan=0.0), -1)
+    assert np.array_equal(oracle.tri_inv(A), oracle.tri_inv(clean))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16, torch.bfloat16])
+def test_stored_values_are_widened_exactly(dtype):
+    A = si.random_strict_lower(2, 64, 0.1, seed=2, garbage_upper=False).to(dtype)
+    ref = oracle.tri_inv(A.to(torch.float64).numpy())
+    assert np.array_equal(oracle.tri_inv(A), ref)
+    if dtype == torch.float16:  # subnormal fp16 values survive the widening
+        tiny = torch.zeros(1, 4, 4, dtype=torch.float16)
+        tiny[0, 1, 0] = 6e-8
+        assert oracle.tri_inv(tiny)[0, 1, 0] == -float(tiny[0, 1, 0])
+
+
+# ---------------------------------------------------------------- P5-P8 on the workload generators
+def _small(idx, **kw):
+    return si.make_inputs(si.workload(idx, **kw))
+
+
+@pytest.mark.parametrize("idx,kw", [(0, {}), (1, dict(Tlen=256, H=2)), (2, dict(B=1, Tlen=256, H=2)),
+                                    (3, dict(B=1, Tlen=128, H=2)), (4, dict(Tlen=512, H=2))])
+def test_structure_residual_nilpotency_entry_bound(idx, kw):
+    inp = _small(idx, **kw)
+    w = inp["workload"]
+    A = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    T = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    assert A.shape == (w.n_mat, w.C, w.C)
+    assert metrics.structure_ok(T)                                        # unit lower triangular
+    assert np.array_equal(A, np.tril(A, -1))
+    assert np.array_equal(T, oracle.tri_inv(A))                           # fused == build then invert
+    res = metrics.residual(A, T)
+    assert res["normalised"].max() < w.C * 2.0 ** -52                     # (I + A) T = I
+    assert np.abs(T).max() <= 1.0 + 1e-12                                 # entries of the inverse in [-1, 1]
+    M = np.eye(w.C)[None] + A
+    cond = np.linalg.cond(M[: min(8, w.n_mat)])
+    assert cond.max() <= w.C ** 2                                         # Cor. 2.1
+    # nilpotency: A^C = 0 and the finite Neumann sum is the inverse (benign inputs only)
+    if idx != 4:
+        for m in range(min(4, w.n_mat)):
+            assert np.array_equal(np.linalg.matrix_power(A[m], w.C), np.zeros((w.C, w.C)))
+            assert np.allclose(methods.neumann_sum(A[m]), T[m], rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- build_A: independent einsum, P9, P13
+def test_build_A_matches_independent_einsum_scalar_gate():
+    inp = _small(1, Tlen=128, H=3)
+    w = inp["workload"]
+    K = inp["K"].to(torch.float64)
+    B, Tlen, H, d = K.shape
+    Kc = K.reshape(B, Tlen // w.C, w.C, H, d)
+    S = torch.einsum("bnihd,bnjhd->bnhij", Kc, Kc)
+    g = inp["g"].to(torch.float64).reshape(B, Tlen // w.C, w.C, H).permute(0, 1, 3, 2)
+    beta = inp["beta"].to(torch.float64).reshape(B, Tlen // w.C, w.C, H).permute(0, 1, 3, 2)
+    A = beta[..., :, None] * torch.exp(g[..., :, None] - g[..., None, :]) * S
+    A = torch.tril(A, -1).reshape(-1, w.C, w.C).numpy()
+    got = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    assert np.allclose(got, A, rtol=1e-12, atol=1e-15)
+
+
+def test_build_A_per_channel_matches_factored_form():
+    # (K * Gamma)(K / Gamma)^T with Gamma = exp(g) -- the KDA row of Table 1 -- equals the
+    # difference form the oracle evaluates
+    inp = _small(3, B=1, Tlen=128, H=2)
+    w = inp["workload"]
+    K = inp["K"].to(torch.float64)
+    g = inp["g"].to(torch.float64)
+    B, Tlen, H, d = K.shape
+    Kp = (K * torch.exp(g)).reshape(B, Tlen // w.C, w.C, H, d)
+    Km = (K * torch.exp(-g)).reshape(B, Tlen // w.C, w.C, H, d)
+    S = torch.einsum("bnihd,bnjhd->bnhij", Kp, Km)
+    beta = inp["beta"].to(torch.float64).reshape(B, Tlen // w.C, w.C, H).permute(0, 1, 3, 2)
+    A = torch.tril(beta[..., :, None] * S, -1).reshape(-1, w.C, w.C).numpy()
+    got = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    assert np.allclose(got, A, rtol=1e-11, atol=1e-15)
+
+
+def test_matrix_index_order_and_selection():
+    inp = _small(1, B=2, Tlen=192, H=3)
+    w = inp["workload"]
+    A = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    # m = (b * n_chunk + chunk) * H + h
+    b, chunk, h = 1, 2, 1
+    m = (b * (w.Tlen // w.C) + chunk) * w.H + h
+    Kc = inp["K"][b, chunk * w.C:(chunk + 1) * w.C, h].to(torch.float64).numpy()
+    gc = inp["g"][b, chunk * w.C:(chunk + 1) * w.C, h].to(torch.float64).numpy()
+    bc = inp["beta"][b, chunk * w.C:(chunk + 1) * w.C, h].to(torch.float64).numpy()
+    want = np.tril(bc[:, None] * np.exp(gc[:, None] - gc[None, :]) * (Kc @ Kc.T), -1)
+    assert np.allclose(A[m], want, rtol=1e-12, atol=1e-15)
+    sel = [m, 0, 5]
+    assert np.array_equal(oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C, sel=sel), A[sel])
+    T = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    assert np.array_equal(oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C, sel=sel), T[sel])
+
+
+def test_scalar_gate_similarity():
+    # A_gated = Gamma A Gamma^-1  =>  T_gated[i,j] = T_ungated[i,j] * exp(g_i - g_j)
+    inp = _small(2, B=1, Tlen=128, H=2)
+    w = inp["workload"]
+    T_g = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], si.GATE_SCALAR, w.C)
+    T_0 = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], None, si.GATE_NONE, w.C)
+    g = inp["g"].to(torch.float64).reshape(w.B, w.Tlen // w.C, w.C, w.H).permute(0, 1, 3, 2).reshape(-1, w.C).numpy()
+    scale = np.exp(g[:, :, None] - g[:, None, :])
+    assert np.allclose(T_g, T_0 * scale, rtol=1e-12, atol=1e-15)
+
+
+def test_per_channel_gate_reduces_to_scalar_gate_and_to_deltanet():
+    inp = _small(2, B=1, Tlen=128, H=2)
+    w = inp["workload"]
+    g_bcast = inp["g"][..., None].expand(-1, -1, -1, w.d_k).contiguous()
+    A_s = oracle.build_A(inp["K"], inp["beta"], inp["g"], si.GATE_SCALAR, w.C)
+    A_c = oracle.build_A(inp["K"], inp["beta"], g_bcast, si.GATE_PER_CHANNEL, w.C)
+    assert np.allclose(A_s, A_c, rtol=1e-12, atol=1e-16)
+    A_0 = oracle.build_A(inp["K"], inp["beta"], None, si.GATE_NONE, w.C)
+    A_z = oracle.build_A(inp["K"], inp["beta"], torch.zeros_like(inp["g"]), si.GATE_SCALAR, w.C)
+    assert np.array_equal(A_0, A_z)
+
+
+# ---------------------------------------------------------------- paper algorithms in exact arithmetic
+@pytest.mark.parametrize("C", [16, 64, 128])
+def test_paper_algorithms_reach_the_oracle_in_fp64(C):
+    rng = np.random.default_rng(C)
+    Kn = rng.normal(size=(C, 32))
+    Kn /= np.linalg.norm(Kn, axis=1, keepdims=True)
+    L = np.tril(Kn @ Kn.T * rng.uniform(0.2, 1.0, size=(C, 1)), -1)
+    T = oracle.tri_inv(L[None])[0]
+    assert np.allclose(methods.mch(L), T, atol=1e-11)
+    assert np.allclose(methods.mbh(L), T, atol=1e-12)
+    assert np.allclose(methods.mxr(L, b0=16), T, atol=1e-12)
+    assert np.allclose(methods.mxr(L, b0=16, r=1), T, atol=1e-12)
+    assert np.allclose(methods.ir(T + 1e-4 * np.tril(rng.normal(size=(C, C))), L), T, atol=1e-6)
+    assert np.allclose(methods.ns(L, m=4 * int(math.log2(C))), T, atol=1e-10)
+    assert np.allclose(methods.forward_substitution(L), T, atol=1e-13)
+
+
+def test_mch_partial_sums():
+    # after k iterations of Alg. 5, X = sum_{i < 2^(k+1)} (-L)^i
+    rng = np.random.default_rng(5)
+    L = np.tril(rng.normal(size=(32, 32)) * 0.2, -1)
+    for k in range(0, 5):
+        want = sum(np.linalg.matrix_power(-L, i) for i in range(2 ** (k + 1)))
+        assert np.allclose(methods.mch(L, iters=k), want, atol=1e-12)
+
+
+@pytest.mark.parametrize("C", [16, 64])
+def test_mbh_block_invariant(C):
+    # after the level with block size b, every 2b x 2b diagonal block of X is the inverse of the
+    # same block of I + L (Lemma C.1 induction)
+    rng = np.random.default_rng(C + 1)
+    L = np.tril(rng.normal(size=(C, C)) * 0.3, -1)
+    levels = []
+    methods.mbh(L, levels_out=levels)
+    assert [b for b, _ in levels] == [2 ** k for k in range(int(math.log2(C)))]
+    for b, X in levels:
+        for t in range(C // (2 * b)):
+            s = slice(2 * b * t, 2 * b * (t + 1))
+            want = oracle.tri_inv(L[s, s][None])[0]
+            assert np.allclose(X[s, s], want, atol=1e-10), (b, t)
+
+
+def test_matmul_counts_table2():
+    # Table 2: MCH 2*ceil(log2(n/2)) -> 10 at 64, 12 at 128 ; MBH (b0=1) 2*log2(n) -> 12, 14
+    for n, mch_cnt, mbh_cnt in [(64, 10, 12), (128, 12, 14)]:
+        assert 2 * math.ceil(math.log2(n / 2)) == mch_cnt
+        levels = []
+        methods.mbh(np.zeros((n, n)), levels_out=levels)
+        assert 2 * len(levels) == mbh_cnt
