@@ -1,0 +1,143 @@
+/*
+ * triinv -- batched inversion T = (I + A)^{-1} of small strictly-lower-triangular chunk
+ * matrices for delta-rule linear attention, on one AMD MI355X (gfx950).
+ *
+ * The operation (paper Sec. 1, Eq. 3 and Table 1): a sequence of Tlen tokens is cut into
+ * chunks of C tokens; for every (batch, chunk, head) the C x C matrix
+ *      A_ij = beta_i * exp(g_i - g_j) * <k_i, k_j>              (scalar gate, GDN)
+ *      A_ij = beta_i * sum_c k_ic k_jc exp(g_ic - g_jc)         (per-channel gate, KDA)
+ *      A_ij = beta_i * <k_i, k_j>                               (no gate, DeltaNet)
+ * for i > j, and 0 for i <= j, is strictly lower triangular, and the layer needs the
+ * unit-lower-triangular inverse T = (I + A)^{-1}.  The matrices are independent.
+ *
+ * Conventions shared by every entry point
+ *   - every pointer is a DEVICE pointer (hipMalloc / torch .data_ptr()), 16-byte aligned;
+ *     the caller owns all buffers; nothing is allocated, freed or synchronised here;
+ *   - work is enqueued on the given HIP stream (NULL = the default stream) and the call
+ *     returns at once; the return value reports argument / launch errors only;
+ *   - the return value is TRIINV_OK (0) or a negative triinv_status; argument errors are
+ *     detected on the host before anything is launched, so a failing call does no GPU work;
+ *   - T is always fp32, dense row-major [n_mat][C][C], completely overwritten: exact 0.0f
+ *     above the diagonal and exact 1.0f on it;
+ *   - non-finite input values are not errors; they propagate inside their own matrix only.
+ */
+#ifndef TRIINV_H
+#define TRIINV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element types: of a stored input (in_dtype, k_dtype) or of the matrix-core operands
+ * (op_dtype; products always accumulate in fp32, paper Sec. 4.1). */
+typedef enum { TRIINV_F32 = 0, TRIINV_F16 = 1, TRIINV_BF16 = 2 } triinv_dtype;
+
+/* Inversion methods. */
+typedef enum {
+    /* Row-wise forward substitution in fp32 vector arithmetic; the direct, matmul-free, stable
+     * baseline (the role of the vectorised column sweep, paper Sec. 3.1).  Ignores op_dtype. */
+    TRIINV_FWD_SUBST = 0,
+    /* Blocked 2x2 recursion (paper Alg. 4, Sec. 3.3, Eq. 7 in its lower-triangular reading):
+     * X <- D_e + D_o - D_o A D_e for block sizes 1, 2, ..., C/2.  Log-stable. */
+    TRIINV_BLOCK_RECURSIVE = 1,
+    /* Neumann product prod_k (I + (-A)^(2^k)) by repeated squaring (paper Alg. 5, Sec. 3.2):
+     * X <- I - A, Y <- A, then log2(C/2) times Y <- Y Y, X <- X + X Y.  Unstable: intermediate
+     * powers may overflow / cancel; the result is returned as computed. */
+    TRIINV_NEUMANN = 2,
+    /* Mixed recursion (paper Alg. 2, Sec. 3.4): Neumann product on the 16 x 16 diagonal blocks,
+     * then the blocked recursion from block size 16.  Log-stable. */
+    TRIINV_MIXED = 3
+} triinv_method;
+
+/* Gate kinds of the fused entry point. */
+typedef enum {
+    TRIINV_GATE_SCALAR = 0,      /* g is [B, Tlen, H]      */
+    TRIINV_GATE_PER_CHANNEL = 1, /* g is [B, Tlen, H, d_k] */
+    TRIINV_GATE_NONE = 2         /* g is ignored (may be NULL) */
+} triinv_gate;
+
+typedef enum {
+    TRIINV_OK = 0,
+    TRIINV_ERR_NULL = -1,        /* a required pointer is NULL while there is work to do */
+    TRIINV_ERR_BAD_C = -2,       /* C is not 64 or 128 */
+    TRIINV_ERR_BAD_DTYPE = -3,   /* unknown in_dtype / k_dtype / op_dtype */
+    TRIINV_ERR_BAD_METHOD = -4,  /* unknown method or gate kind */
+    TRIINV_ERR_BAD_SHAPE = -5,   /* n_mat < 0; B, H, d_k <= 0; Tlen < 0; Tlen % C != 0; d_k % 32 != 0; d_k > 256 */
+    TRIINV_ERR_ALIGN = -6,       /* a pointer is not 16-byte aligned */
+    TRIINV_ERR_ALIAS = -7,       /* T overlaps an input buffer */
+    TRIINV_ERR_LAUNCH = -8,      /* the HIP runtime refused the launch */
+    TRIINV_ERR_UNSUPPORTED = -9  /* valid arguments, but this combination is not built */
+} triinv_status;
+
+/* Bits of `flags` (0 = none). */
+#define TRIINV_FLAG_REFINE1 0x1u /* one iterative-refinement step X <- X + (I - X(I+A))X after the
+                                    method (paper Alg. 6, Eq. 9); matrix-product methods only */
+
+/*
+ * tri_inv: invert n_mat precomputed matrices (paper Sec. 1 Eq. 3 with A given; App. D.1: the
+ * input is a tensor of many small independent chunks).
+ *   A        device, [n_mat][C][C] row-major, elements of type in_dtype.  Only entries with
+ *            i > j are read into the arithmetic; entries with i <= j are ignored, so garbage or
+ *            NaN there does not change the result (the mask of Eq. 3 is applied on load).
+ *   T        device, [n_mat][C][C] fp32, output; must not overlap A.
+ *   n_mat    number of matrices, >= 0; 0 is a successful no-op (pointers may then be NULL).
+ *   C        64 or 128.
+ *   in_dtype triinv_dtype of A.
+ *   method   triinv_method.
+ * Short form: op_dtype = in_dtype, default stream, flags 0.
+ */
+int tri_inv(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int method);
+
+/*
+ * tri_inv_ex: as tri_inv, with
+ *   op_dtype   type the matrix-core operands are rounded to (round-to-nearest-even) at every
+ *              product; accumulators and all additions stay fp32.  Ignored by TRIINV_FWD_SUBST.
+ *   hip_stream a hipStream_t (e.g. torch.cuda.current_stream().cuda_stream), or NULL.
+ *   flags      TRIINV_FLAG_* bits.
+ */
+int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int method,
+               int op_dtype, void* hip_stream, uint32_t flags);
+
+/*
+ * gdn_chunk_tri_inv: fused "build A from the keys, then invert" (paper Sec. 1 Eq. 3 with the
+ * GDN row of Table 1), never writing A to memory.
+ *   K     device, [B][Tlen][H][d_k] contiguous (token-major, heads interleaved), bf16.
+ *   beta  device, [B][Tlen][H] fp32.
+ *   g     device, [B][Tlen][H] fp32: the chunk-local cumulative log-decay (the running sum
+ *         restarts at every chunk boundary).
+ *   T     device, [n_mat][C][C] fp32 with n_mat = B * (Tlen / C) * H and matrix index
+ *         m = (b * (Tlen / C) + chunk) * H + h; must not overlap an input.
+ *   Tlen must be a multiple of C (a shorter last chunk is rejected), d_k a multiple of 32, <= 256.
+ * Short form: k_dtype = BF16, scalar gate, method = TRIINV_BLOCK_RECURSIVE, op_dtype = BF16,
+ * default stream, flags 0.
+ */
+int gdn_chunk_tri_inv(const void* K, const float* beta, const float* g, float* T,
+                      int B, int64_t Tlen, int H, int d_k, int C);
+
+/*
+ * gdn_chunk_tri_inv_ex: as gdn_chunk_tri_inv, with
+ *   k_dtype    triinv_dtype of K.  The Gram products <k_i, k_j> use the stored key values as
+ *              matrix-core operands (exact products, fp32 accumulation) for the scalar and
+ *              no-gate kinds.  For the per-channel gate the gated keys k*exp(+-(g - g_mid)) are
+ *              rounded to op_dtype (g_mid = the chunk's middle row), so the in-chunk range of g
+ *              must stay below ~80 (fp32, bf16 operands) or ~10 (fp16 operands).
+ *   gate_kind  triinv_gate (KDA row of Table 1 for TRIINV_GATE_PER_CHANNEL).
+ *   method, op_dtype, hip_stream, flags: as in tri_inv_ex.
+ */
+int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float* T,
+                         int B, int64_t Tlen, int H, int d_k, int C,
+                         int k_dtype, int gate_kind, int method, int op_dtype,
+                         void* hip_stream, uint32_t flags);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* triinv_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int triinv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRIINV_H */

@@ -1,0 +1,9 @@
+"""Batched triangular inversion T = (I + A)^{-1} for delta-rule linear attention on MI355X.
+
+Thin binding over the hand-written HIP library `libtriinv.so` (C-ABI in include/triinv.h).
+"""
+from .binding import (  # noqa: F401
+    BF16, BLOCK_RECURSIVE, F16, F32, FWD_SUBST, GATE_NONE, GATE_PER_CHANNEL, GATE_SCALAR, MIXED, NEUMANN,
+    DTYPE_NAMES, EXPORTS, METHOD_NAMES, TriInvError,
+    gdn_chunk_tri_inv, gdn_chunk_tri_inv_ex, lib, status_string, tri_inv, tri_inv_ex, version,
+)

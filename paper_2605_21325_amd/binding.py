@@ -1,0 +1,150 @@
+"""ctypes binding of libtriinv.so -- argument marshalling only.
+
+Every step of the path (Gram products, gating, masking, inversion, store) runs in the HIP
+kernels behind the C-ABI declared in include/triinv.h; PyTorch is used here for device memory
+and for the current stream, nothing else.  There is no CPU fallback: if the shared library is
+missing or cannot be loaded, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # imported before the library is opened so that its HIP runtime is the one in use
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtriinv.so")
+
+# enums of include/triinv.h
+F32, F16, BF16 = 0, 1, 2
+FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED = 0, 1, 2, 3
+GATE_SCALAR, GATE_PER_CHANNEL, GATE_NONE = 0, 1, 2
+OK = 0
+
+METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUMANN: "neumann", MIXED: "mixed"}
+DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
+
+EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "triinv_status_string", "triinv_version")
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class TriInvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library (raw ctypes handle).  Built by `paper_2605_21325_amd.build`."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_21325_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint32
+        L.tri_inv.argtypes = [vp, vp, i64, i32, i32, i32]
+        L.tri_inv.restype = i32
+        L.tri_inv_ex.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, u32]
+        L.tri_inv_ex.restype = i32
+        L.gdn_chunk_tri_inv.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32]
+        L.gdn_chunk_tri_inv.restype = i32
+        L.gdn_chunk_tri_inv_ex.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, i32, vp, u32]
+        L.gdn_chunk_tri_inv_ex.restype = i32
+        L.triinv_status_string.argtypes = [i32]
+        L.triinv_status_string.restype = ctypes.c_char_p
+        L.triinv_version.argtypes = []
+        L.triinv_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().triinv_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().triinv_version())
+
+
+def dtype_code(dt: torch.dtype) -> int:
+    try:
+        return {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}[dt]
+    except KeyError:
+        raise TypeError(f"unsupported element type {dt}") from None
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) or None
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def tri_inv(A: torch.Tensor, T: Optional[torch.Tensor] = None, method: int = BLOCK_RECURSIVE) -> torch.Tensor:
+    """T = (I + strict_lower(A))^{-1};  A [n_mat, C, C] fp32/fp16/bf16 on the GPU.  Short form of
+    the C-ABI: operands in A's own type, default stream."""
+    n_mat, C, _ = A.shape
+    if T is None:
+        T = torch.empty((n_mat, C, C), dtype=torch.float32, device=A.device)
+    st = lib().tri_inv(_dev(A, "A"), _dev(T, "T"), n_mat, C, dtype_code(A.dtype), method)
+    if st != OK:
+        raise TriInvError(st, "tri_inv")
+    return T
+
+
+def tri_inv_ex(A: torch.Tensor, T: Optional[torch.Tensor] = None, method: int = BLOCK_RECURSIVE,
+               op_dtype: Optional[int] = None, stream=None, flags: int = 0) -> torch.Tensor:
+    n_mat, C, _ = A.shape
+    if T is None:
+        T = torch.empty((n_mat, C, C), dtype=torch.float32, device=A.device)
+    in_dt = dtype_code(A.dtype)
+    st = lib().tri_inv_ex(_dev(A, "A"), _dev(T, "T"), n_mat, C, in_dt, method,
+                          in_dt if op_dtype is None else op_dtype, _stream_ptr(stream), flags)
+    if st != OK:
+        raise TriInvError(st, "tri_inv_ex")
+    return T
+
+
+def _n_mat(K: torch.Tensor, C: int) -> int:
+    B, Tlen, H, _ = K.shape
+    return B * (Tlen // C) * H
+
+
+def gdn_chunk_tri_inv(K: torch.Tensor, beta: torch.Tensor, g: torch.Tensor, C: int,
+                      T: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Fused build + invert, short form: bf16 keys [B, Tlen, H, d_k], scalar gate, blocked
+    recursion with bf16 operands, default stream."""
+    B, Tlen, H, d_k = K.shape
+    if K.dtype != torch.bfloat16:
+        raise TypeError("the short form takes bf16 keys; use gdn_chunk_tri_inv_ex")
+    if T is None:
+        T = torch.empty((_n_mat(K, C), C, C), dtype=torch.float32, device=K.device)
+    st = lib().gdn_chunk_tri_inv(_dev(K, "K"), _dev(beta, "beta"), _dev(g, "g"), _dev(T, "T"), B, Tlen, H, d_k, C)
+    if st != OK:
+        raise TriInvError(st, "gdn_chunk_tri_inv")
+    return T
+
+
+def gdn_chunk_tri_inv_ex(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], C: int,
+                         T: Optional[torch.Tensor] = None, gate_kind: int = GATE_SCALAR,
+                         method: int = BLOCK_RECURSIVE, op_dtype: int = BF16, stream=None, flags: int = 0) -> torch.Tensor:
+    B, Tlen, H, d_k = K.shape
+    if T is None:
+        T = torch.empty((_n_mat(K, C), C, C), dtype=torch.float32, device=K.device)
+    gp = None if g is None else _dev(g, "g")
+    st = lib().gdn_chunk_tri_inv_ex(_dev(K, "K"), _dev(beta, "beta"), gp, _dev(T, "T"), B, Tlen, H, d_k, C,
+                                    dtype_code(K.dtype), gate_kind, method, op_dtype, _stream_ptr(stream), flags)
+    if st != OK:
+        raise TriInvError(st, "gdn_chunk_tri_inv_ex")
+    return T

@@ -1,0 +1,57 @@
+"""Build libtriinv.so (hand-written HIP for gfx950) in-tree with hipcc.
+
+One translation unit per (C, operand type) pair plus the C-ABI file, compiled in parallel and
+linked into paper_2605_21325_amd/libtriinv.so.  Packed-fp32 code generation is switched off
+for every device compile.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libtriinv.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-pass-failed", "-Wno-unused-command-line-argument",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+UNITS = [("api", "api.hip", [])] + [
+    (f"inst_nb{nb}_op{op}", "inst.hip", [f"-DTRIINV_INST_NB={nb}", f"-DTRIINV_INST_OP={op}"])
+    for nb in (4, 8) for op in (0, 1, 2)
+]
+
+
+def _sources_mtime() -> float:
+    return max(os.path.getmtime(os.path.join(CSRC, f)) for f in os.listdir(CSRC))
+
+
+def _compile(unit) -> str:
+    name, src, defs = unit
+    out = os.path.join(OBJ, name + ".o")
+    cmd = [HIPCC, *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {name}:\n{r.stderr[-4000:]}")
+    return out
+
+
+def build(force: bool = False, jobs: int = 0) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= _sources_mtime():
+        return LIB
+    os.makedirs(OBJ, exist_ok=True)
+    jobs = jobs or min(len(UNITS), os.cpu_count() or 4, 16)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(_compile, UNITS))
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stderr[-4000:]}")
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv))

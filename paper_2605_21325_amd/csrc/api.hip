@@ -1,0 +1,119 @@
+// C-ABI of the library (see include/triinv.h): argument validation on the host, then dispatch
+// to the kernel instantiation for (C, operand type, method).  No allocation, no synchronisation.
+#include "../../include/triinv.h"
+#include "dispatch.hpp"
+
+namespace {
+
+using namespace triinv;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlap(const void* a, uint64_t na, const void* b, uint64_t nb)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_BF16; }
+bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_MIXED; }
+uint64_t esize(int d) { return d == TRIINV_F32 ? 4 : 2; }
+
+int finish(int not_built)
+{
+    if (not_built) return TRIINV_ERR_UNSUPPORTED;
+    return hipGetLastError() == hipSuccess ? TRIINV_OK : TRIINV_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int method, int op_dtype, void* hip_stream,
+               uint32_t flags)
+{
+    if (C != 64 && C != 128) return TRIINV_ERR_BAD_C;
+    if (!dtype_ok(in_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
+    if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
+    if (n_mat < 0 || n_mat > 0x7fffffffLL) return TRIINV_ERR_BAD_SHAPE;
+    if (n_mat == 0) return TRIINV_OK;
+    if (!A || !T) return TRIINV_ERR_NULL;
+    if (!aligned16(A) || !aligned16(T)) return TRIINV_ERR_ALIGN;
+    const uint64_t n_el = (uint64_t)n_mat * C * C;
+    if (overlap(A, n_el * esize(in_dtype), T, n_el * 4)) return TRIINV_ERR_ALIAS;
+    if (flags != 0) return TRIINV_ERR_UNSUPPORTED;
+    if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
+
+    TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream)};
+    int nb = 1;
+    if (C == 64) {
+        nb = op_dtype == TRIINV_F32 ? launch_tri_inv_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb4_op1(a) : launch_tri_inv_nb4_op2(a);
+    } else {
+        nb = op_dtype == TRIINV_F32 ? launch_tri_inv_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb8_op1(a) : launch_tri_inv_nb8_op2(a);
+    }
+    return finish(nb);
+}
+
+int tri_inv(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int method)
+{
+    return tri_inv_ex(A, T, n_mat, C, in_dtype, method, in_dtype, nullptr, 0);
+}
+
+int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float* T, int B, int64_t Tlen, int H, int d_k,
+                         int C, int k_dtype, int gate_kind, int method, int op_dtype, void* hip_stream, uint32_t flags)
+{
+    if (C != 64 && C != 128) return TRIINV_ERR_BAD_C;
+    if (!dtype_ok(k_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
+    if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
+    if (gate_kind < TRIINV_GATE_SCALAR || gate_kind > TRIINV_GATE_NONE) return TRIINV_ERR_BAD_METHOD;
+    if (B <= 0 || H <= 0 || d_k <= 0 || Tlen < 0 || Tlen % C != 0 || d_k % 32 != 0 || d_k > 256) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t n_chunk = (int64_t)B * (Tlen / C);
+    const int64_t n_mat = n_chunk * H;
+    if (n_mat > 0x7fffffffLL) return TRIINV_ERR_BAD_SHAPE;
+    if (n_mat == 0) return TRIINV_OK;
+    const bool need_g = gate_kind != TRIINV_GATE_NONE;
+    if (!K || !beta || !T || (need_g && !g)) return TRIINV_ERR_NULL;
+    if (!aligned16(K) || !aligned16(beta) || !aligned16(T) || (need_g && !aligned16(g))) return TRIINV_ERR_ALIGN;
+    const uint64_t n_tok = (uint64_t)B * Tlen * H;
+    const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4;
+    if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
+    if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
+    if (flags != 0) return TRIINV_ERR_UNSUPPORTED;
+    if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
+
+    GdnArgs a{K, beta, need_g ? g : nullptr, T, n_mat, n_chunk, H, d_k, k_dtype, gate_kind, method, static_cast<hipStream_t>(hip_stream)};
+    int nb = 1;
+    if (C == 64) {
+        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1(a) : launch_gdn_nb4_op2(a);
+    } else {
+        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1(a) : launch_gdn_nb8_op2(a);
+    }
+    return finish(nb);
+}
+
+int gdn_chunk_tri_inv(const void* K, const float* beta, const float* g, float* T, int B, int64_t Tlen, int H, int d_k, int C)
+{
+    return gdn_chunk_tri_inv_ex(K, beta, g, T, B, Tlen, H, d_k, C, TRIINV_BF16, TRIINV_GATE_SCALAR, TRIINV_BLOCK_RECURSIVE,
+                                TRIINV_BF16, nullptr, 0);
+}
+
+const char* triinv_status_string(int status)
+{
+    switch (status) {
+    case TRIINV_OK: return "ok";
+    case TRIINV_ERR_NULL: return "null pointer";
+    case TRIINV_ERR_BAD_C: return "C must be 64 or 128";
+    case TRIINV_ERR_BAD_DTYPE: return "unknown element type";
+    case TRIINV_ERR_BAD_METHOD: return "unknown method or gate kind";
+    case TRIINV_ERR_BAD_SHAPE: return "bad shape";
+    case TRIINV_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case TRIINV_ERR_ALIAS: return "output overlaps an input";
+    case TRIINV_ERR_LAUNCH: return "kernel launch failed";
+    case TRIINV_ERR_UNSUPPORTED: return "combination not built";
+    default: return "unknown status";
+    }
+}
+
+int triinv_version(void) { return 100; }
+
+}  // extern "C"

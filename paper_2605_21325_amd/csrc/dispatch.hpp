@@ -1,0 +1,45 @@
+// Host-side launch table: one launcher per (C, operand type) pair, each compiled in its own
+// translation unit (inst.hip with TRIINV_INST_NB / TRIINV_INST_OP set) so the build parallelises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace triinv {
+
+struct TriInvArgs {
+    const void* A;
+    float* T;
+    int64_t n_mat;
+    int in_dt;
+    int method;
+    hipStream_t stream;
+};
+
+struct GdnArgs {
+    const void* K;
+    const float* beta;
+    const float* g;  // null for the no-gate kind
+    float* T;
+    int64_t n_mat;
+    int64_t n_chunk;  // B * Tlen / C
+    int H;
+    int d_k;
+    int k_dt;
+    int gate;
+    int method;
+    hipStream_t stream;
+};
+
+// Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.
+#define TRIINV_DECL(NB, OP)                                  \
+    int launch_tri_inv_nb##NB##_op##OP(const TriInvArgs& a); \
+    int launch_gdn_nb##NB##_op##OP(const GdnArgs& a);
+TRIINV_DECL(4, 0)
+TRIINV_DECL(4, 1)
+TRIINV_DECL(4, 2)
+TRIINV_DECL(8, 0)
+TRIINV_DECL(8, 1)
+TRIINV_DECL(8, 2)
+#undef TRIINV_DECL
+
+}  // namespace triinv

@@ -1,0 +1,76 @@
+// Kernel instantiations for one (C = 16 * TRIINV_INST_NB, operand type TRIINV_INST_OP) pair.
+#include "dispatch.hpp"
+#include "kernels.hpp"
+
+#ifndef TRIINV_INST_NB
+#error "compile with -DTRIINV_INST_NB=4|8 -DTRIINV_INST_OP=0|1|2"
+#endif
+
+namespace triinv {
+
+#define CAT_(a, b, c, d) a##b##c##d
+#define CAT(a, b, c, d) CAT_(a, b, c, d)
+
+constexpr int NB = TRIINV_INST_NB;
+constexpr int OP = TRIINV_INST_OP;
+
+template <int METHOD> static int go_tri(const TriInvArgs& a)
+{
+    hipLaunchKernelGGL((k_tri_inv<OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
+    return 0;
+}
+
+int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const TriInvArgs& a)
+{
+    switch (a.method) {
+#if TRIINV_INST_OP == 0
+    case M_FWD: return go_tri<M_FWD>(a);
+#endif
+    case M_BLOCK: return go_tri<M_BLOCK>(a);
+    case M_MIXED: return go_tri<M_MIXED>(a);
+#if TRIINV_INST_NB == 4
+    case M_NEUMANN: return go_tri<M_NEUMANN>(a);
+#endif
+    default: return 1;
+    }
+}
+
+template <int KD, int METHOD, int DKS> static int go_gdn(const GdnArgs& a)
+{
+    hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
+                       a.g, a.T, a.n_chunk, a.H, a.d_k);
+    return 0;
+}
+
+template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
+{
+    switch (a.method) {
+#if TRIINV_INST_OP == 0
+    case M_FWD: return go_gdn<KD, M_FWD, DKS>(a);
+#endif
+    case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
+    case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
+#if TRIINV_INST_NB == 4
+    case M_NEUMANN: return go_gdn<KD, M_NEUMANN, DKS>(a);
+#endif
+    default: return 1;
+    }
+}
+
+int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const GdnArgs& a)
+{
+    if (a.gate == G_CHANNEL) return 1;
+    if (a.k_dt == OP_F32) {
+        if (a.d_k == 64) return gdn_method<OP_F32, 4>(a);
+        if (a.d_k == 128) return gdn_method<OP_F32, 8>(a);
+    } else if (a.k_dt == OP_BF16) {
+        if (a.d_k == 64) return gdn_method<OP_BF16, 2>(a);
+        if (a.d_k == 128) return gdn_method<OP_BF16, 4>(a);
+    } else {
+        if (a.d_k == 64) return gdn_method<OP_F16, 2>(a);
+        if (a.d_k == 128) return gdn_method<OP_F16, 4>(a);
+    }
+    return 1;
+}
+
+}  // namespace triinv

@@ -1,0 +1,284 @@
+// Inversion cores on register tiles: one 64-lane wavefront inverts one C x C matrix, C = 16 * NB.
+//
+// All functions take the strictly-lower chunk matrix A through a "tile source" object
+//     template <bool TR> v4f get(int i, int j) const;      // 16x16 tile (i, j), i >= j
+// returning the tile in N orientation (TR = false: registers hold A_ij) or in T orientation
+// (TR = true: registers hold A_ij^T).  Diagonal tiles come back already masked to their
+// strictly-lower part.  See tile_ops.hpp for the register layout and the tn primitive.
+#pragma once
+#include "tile_ops.hpp"
+
+namespace triinv {
+
+// ---------------------------------------------------------------------------------------------
+// 16 x 16 leaves.  Both return the leaf inverse in both orientations (XN = X, XT = X^T).
+// ---------------------------------------------------------------------------------------------
+
+// Blocked recursion inside the leaf (paper Alg. 4 with b0 = 1, Lemma C.1): block sizes 1, 2, 4, 8.
+// The level b = 1 starts from X = I, so D_o A D_e only picks the entries A[i][i-1], i odd.
+// Each later level applies X <- X - [D_o A D_e restricted to the 2b-block diagonal]; the
+// restriction drops the entries the unrolled product creates outside the 2b x 2b blocks, which
+// the paper's next level discards when it re-selects diagonal blocks.
+template <int OP>
+__device__ __forceinline__ void leaf_block_recursive(v4f LN, v4f LT, v4f& XN, v4f& XT, Lane ln)
+{
+    const Opnd<OP> LNo = pack<OP>(LN), LTo = pack<OP>(LT);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int a = 4 * ln.q + r, b = ln.n;  // XN[r] = X[a][b], XT[r] = X[b][a]
+        XN[r] = (a == b) ? 1.f : (((a & 1) && b == a - 1) ? -LN[r] : 0.f);
+        XT[r] = (a == b) ? 1.f : (((b & 1) && a == b - 1) ? -LT[r] : 0.f);
+    }
+#pragma unroll
+    for (int lb = 1; lb < 4; ++lb) {  // block size b = 2^lb
+        v4f eN, oT;
+        bool keep[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int a = 4 * ln.q + r, b = ln.n;
+            const bool same_b = (a >> lb) == (b >> lb);
+            const bool even = ((a >> lb) & 1) == 0;
+            eN[r] = (same_b && even) ? XN[r] : 0.f;   // D_e        (N)
+            oT[r] = (same_b && !even) ? XT[r] : 0.f;  // D_o^T      (T)
+            keep[r] = (a >> (lb + 1)) == (b >> (lb + 1));
+        }
+        const Opnd<OP> eNo = pack<OP>(eN), oTo = pack<OP>(oT);
+        const v4f P1 = tn<OP>(LTo, eNo, zero4());             // A D_e
+        const v4f P2 = tn<OP>(LNo, oTo, zero4());             // A^T D_o^T = (D_o A)^T
+        const v4f Q1 = tn<OP>(oTo, pack<OP>(P1), zero4());    // D_o A D_e
+        const v4f Q2 = tn<OP>(eNo, pack<OP>(P2), zero4());    // (D_o A D_e)^T
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            XN[r] -= keep[r] ? Q1[r] : 0.f;
+            XT[r] -= keep[r] ? Q2[r] : 0.f;
+        }
+    }
+}
+
+// Neumann product on the leaf (paper Alg. 5 with n = 16: three squarings), both orientations.
+template <int OP>
+__device__ __forceinline__ void leaf_neumann(v4f LN, v4f LT, v4f& XN, v4f& XT, Lane ln)
+{
+    v4f YN = LN, YT = LT;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float id = (4 * ln.q + r == ln.n) ? 1.f : 0.f;
+        XN[r] = id - LN[r];
+        XT[r] = id - LT[r];
+    }
+#pragma unroll
+    for (int it = 0; it < 3; ++it) {
+        const Opnd<OP> YNo = pack<OP>(YN), YTo = pack<OP>(YT);
+        YN = tn<OP>(YTo, YNo, zero4());                        // Y <- Y Y
+        if (it < 2) YT = tn<OP>(YNo, YTo, zero4());            // (Y Y)^T
+        const Opnd<OP> Yn = pack<OP>(YN), XTo = pack<OP>(XT);
+        const v4f XNn = tn<OP>(XTo, Yn, XN);                   // X + X Y
+        XT = tn<OP>(Yn, XTo, XT);                              // (X + X Y)^T
+        XN = XNn;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tile transpose through a wave-private LDS patch of 16 x 20 floats.
+// ---------------------------------------------------------------------------------------------
+constexpr int XPOSE_LD = 20;
+constexpr int XPOSE_FLOATS = 16 * XPOSE_LD;
+
+__device__ __forceinline__ v4f transpose_tile(v4f t, float* patch, Lane ln)
+{
+#pragma unroll
+    for (int r = 0; r < 4; ++r) patch[(4 * ln.q + r) * XPOSE_LD + ln.n] = t[r];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    v4f o = *reinterpret_cast<const v4f*>(&patch[ln.n * XPOSE_LD + 4 * ln.q]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return o;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Blocked 2x2 recursion above the leaves (paper Sec. 3.3, Eq. 7, lower-triangular reading):
+//   inv [[A11, 0], [A21, A22]] = [[T11, 0], [-T22 A21 T11, T22]].
+// Levels are unrolled over tile-block sizes h = 1, 2, ..., NB/2; at each level the pairs are
+// independent.  A pair's left factor T22 is held in T orientation and its right factor T11 in
+// N orientation, so both products are tn() calls on registers.  A block that will be the odd
+// (left-factor) child of its parent is produced in T orientation, an even child in N.
+//
+// Result: Tt[tix(i, j)] for the lower tiles; final orientation given by result_is_T().
+// ---------------------------------------------------------------------------------------------
+template <int NB, bool ROOT_T>
+__host__ __device__ constexpr bool result_is_T(int i, int j)
+{
+    return (NB == 1) ? false : ((j >= NB / 2) ? true : ((i < NB / 2) ? false : ROOT_T));
+}
+
+enum : int { LEAF_BLOCK_RECURSIVE = 0, LEAF_NEUMANN = 1 };
+
+template <int OP, int NB, bool ROOT_T, int LEAF, class ASrc>
+__device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln)
+{
+    v4f leafN[NB], leafT[NB];
+#pragma unroll
+    for (int d = 0; d < NB; ++d) {
+        const v4f LN = A.template get<false>(d, d), LT = A.template get<true>(d, d);
+        if (LEAF == LEAF_BLOCK_RECURSIVE)
+            leaf_block_recursive<OP>(LN, LT, leafN[d], leafT[d], ln);
+        else
+            leaf_neumann<OP>(LN, LT, leafN[d], leafT[d], ln);
+    }
+
+#pragma unroll
+    for (int h = 1; h < NB; h *= 2) {
+#pragma unroll
+        for (int p = 0; p < NB / (2 * h); ++p) {
+            const int lo = 2 * h * p, mid = lo + h, hi = lo + 2 * h;
+            const bool blockT = (2 * h == NB) ? ROOT_T : ((p & 1) != 0);
+            // packed operands of the two children
+            constexpr int NH = (NB / 2) * (NB / 2 + 1) / 2 > 0 ? (NB / 2) * (NB / 2 + 1) / 2 : 1;
+            Opnd<OP> t11[NH], t22[NH];
+#pragma unroll
+            for (int d = 0; d < h; ++d)
+#pragma unroll
+                for (int c = 0; c <= d; ++c) {
+                    t11[tix(d, c)] = pack<OP>(d == c ? leafN[lo + d] : Tt[tix(lo + d, lo + c)]);
+                    t22[tix(d, c)] = pack<OP>(d == c ? leafT[mid + d] : Tt[tix(mid + d, mid + c)]);
+                }
+            // off-diagonal tiles of A, fetched once: T orientation for an N block, N for a T block
+            Opnd<OP> a21[(NB / 2) * (NB / 2) > 0 ? (NB / 2) * (NB / 2) : 1];
+#pragma unroll
+            for (int b = 0; b < h; ++b)
+#pragma unroll
+                for (int d = 0; d < h; ++d)
+                    a21[b * h + d] = blockT ? pack<OP>(A.template get<false>(mid + b, lo + d))
+                                            : pack<OP>(A.template get<true>(mid + b, lo + d));
+            if (!blockT) {
+                // W = -T22 (A21 T11), N orientation
+#pragma unroll
+                for (int c = 0; c < h; ++c) {
+                    Opnd<OP> P[NB / 2 > 0 ? NB / 2 : 1];
+#pragma unroll
+                    for (int b = 0; b < h; ++b) {
+                        v4f acc = zero4();
+#pragma unroll
+                        for (int d = c; d < h; ++d) acc = tn<OP>(a21[b * h + d], t11[tix(d, c)], acc);
+                        P[b] = pack<OP>(acc);
+                    }
+#pragma unroll
+                    for (int a = 0; a < h; ++a) {
+                        v4f acc = zero4();
+#pragma unroll
+                        for (int b = 0; b <= a; ++b) acc = tn<OP>(t22[tix(a, b)], P[b], acc);
+                        Tt[tix(mid + a, lo + c)] = -acc;
+                    }
+                }
+            } else {
+                // W^T = -T11^T (A21^T T22^T), T orientation
+#pragma unroll
+                for (int a = 0; a < h; ++a) {
+                    Opnd<OP> Q[NB / 2 > 0 ? NB / 2 : 1];
+#pragma unroll
+                    for (int d = 0; d < h; ++d) {
+                        v4f acc = zero4();
+#pragma unroll
+                        for (int b = 0; b <= a; ++b) acc = tn<OP>(a21[b * h + d], t22[tix(a, b)], acc);
+                        Q[d] = pack<OP>(acc);
+                    }
+#pragma unroll
+                    for (int c = 0; c < h; ++c) {
+                        v4f acc = zero4();
+#pragma unroll
+                        for (int d = c; d < h; ++d) acc = tn<OP>(t11[tix(d, c)], Q[d], acc);
+                        Tt[tix(mid + a, lo + c)] = -acc;
+                    }
+                }
+            }
+            // bring the children to this block's orientation (leaves have both already)
+            if (2 * h != NB) {
+                const int clo = blockT ? lo : mid;  // child to convert: even child if T, odd child if N
+#pragma unroll
+                for (int d = 1; d < h; ++d)
+#pragma unroll
+                    for (int c = 0; c < d; ++c)
+                        Tt[tix(clo + d, clo + c)] = transpose_tile(Tt[tix(clo + d, clo + c)], patch, ln);
+            }
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < NB; ++d) Tt[tix(d, d)] = result_is_T<NB, ROOT_T>(d, d) ? leafT[d] : leafN[d];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Neumann product on the whole matrix (paper Alg. 5, Sec. 3.2):
+//   X <- I - A, Y <- A;  log2(C/2) times:  Y <- Y Y;  X <- X + X Y.
+// State: Y in both orientations, X in T orientation (X^T <- X^T + Y^T X^T is the literal update
+// transposed).  The running power Y = A^p is structurally zero in tiles with 16 (i-j) + 15 < p;
+// those tiles and the products through them are skipped.
+// Result: Xt[tix(i, j)], every tile in T orientation.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ constexpr bool power_tile_nonzero(int d, int p) { return 16 * d + 15 >= p; }
+__host__ __device__ constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
+template <int OP, int NB, class ASrc>
+__device__ __forceinline__ void neumann(const ASrc& A, v4f (&Xt)[NB * (NB + 1) / 2], Lane ln)
+{
+    constexpr int NT = NB * (NB + 1) / 2;
+    Opnd<OP> Yn[NT], Yt[NT];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            const v4f an = A.template get<false>(i, j), at = A.template get<true>(i, j);
+            Yn[tix(i, j)] = pack<OP>(an);
+            Yt[tix(i, j)] = pack<OP>(at);
+            v4f x;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = ((i == j && 4 * ln.q + r == ln.n) ? 1.f : 0.f) - at[r];
+            Xt[tix(i, j)] = x;
+        }
+    constexpr int iters = ilog2(16 * NB / 2);  // log2(C / 2)
+#pragma unroll
+    for (int it = 0; it < iters; ++it) {
+        const int p = 1 << it, pn = 2 << it;  // Y = A^p becomes A^pn
+        const bool last = (it == iters - 1);
+        v4f Nn[NT], Nt[NT];
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                v4f accn = zero4(), acct = zero4();
+                if (power_tile_nonzero(i - j, pn)) {
+#pragma unroll
+                    for (int k = j; k <= i; ++k)
+                        if (power_tile_nonzero(i - k, p) && power_tile_nonzero(k - j, p)) {
+                            accn = tn<OP>(Yt[tix(i, k)], Yn[tix(k, j)], accn);
+                            if (!last) acct = tn<OP>(Yn[tix(k, j)], Yt[tix(i, k)], acct);
+                        }
+                }
+                Nn[tix(i, j)] = accn;
+                Nt[tix(i, j)] = acct;
+            }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            Yn[t] = pack<OP>(Nn[t]);
+            Yt[t] = pack<OP>(Nt[t]);
+        }
+        // X^T(i,j) += sum_k Y(k,j)^T X(i,k)^T ; ascending j keeps the old X(i,k), k >= j, intact
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            Opnd<OP> xo[NB];
+#pragma unroll
+            for (int k = 0; k <= i; ++k) xo[k] = pack<OP>(Xt[tix(i, k)]);
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                v4f acc = Xt[tix(i, j)];
+#pragma unroll
+                for (int k = j; k <= i; ++k)
+                    if (power_tile_nonzero(k - j, pn)) acc = tn<OP>(Yn[tix(k, j)], xo[k], acc);
+                Xt[tix(i, j)] = acc;
+            }
+        }
+    }
+}
+
+}  // namespace triinv

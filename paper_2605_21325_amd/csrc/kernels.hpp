@@ -1,0 +1,329 @@
+// Kernels: one 64-lane wavefront (= one workgroup) per chunk matrix.
+//   k_tri_inv      A given in global memory          -> T
+//   k_gdn_tri_inv  K, beta, g -> Gram on MFMA, gate  -> T      (A never leaves the registers)
+// Methods: forward substitution (fp32 VALU, A broadcast through LDS), blocked recursion,
+// Neumann product, mixed recursion (MFMA, see inv_core.hpp).
+#pragma once
+#include "inv_core.hpp"
+
+namespace triinv {
+
+enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3 };
+enum : int { G_SCALAR = 0, G_CHANNEL = 1, G_NONE = 2 };
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tile source 1: A in global memory (row-major C x C, element type chosen at run time).
+// ---------------------------------------------------------------------------------------------
+template <int NB> struct GlobalA {
+    static constexpr int C = 16 * NB;
+    const void* base;  // first element of this matrix
+    int dt;            // OP_F32 / OP_F16 / OP_BF16 storage
+    Lane ln;
+
+    __device__ __forceinline__ float elem16(uint16_t u) const { return dt == OP_F16 ? f16_to_f32(u) : bf16_to_f32(u); }
+
+    template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const
+    {
+        v4f v;
+        if (!TR) {  // v[r] = A[16i + 4q + r][16j + n]
+            const int64_t off = (int64_t)(16 * i + 4 * ln.q) * C + 16 * j + ln.n;
+            if (dt == OP_F32) {
+                const float* p = static_cast<const float*>(base) + off;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = p[r * C];
+            } else {
+                const uint16_t* p = static_cast<const uint16_t*>(base) + off;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = elem16(p[r * C]);
+            }
+            if (i == j) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = (4 * ln.q + r > ln.n) ? v[r] : 0.f;
+            }
+        } else {  // v[r] = A[16i + n][16j + 4q + r]
+            const int64_t off = (int64_t)(16 * i + ln.n) * C + 16 * j + 4 * ln.q;
+            if (dt == OP_F32) {
+                v = *reinterpret_cast<const v4f*>(static_cast<const float*>(base) + off);
+            } else {
+                const uint2 u = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + off);
+                v[0] = elem16((uint16_t)(u.x & 0xffff));
+                v[1] = elem16((uint16_t)(u.x >> 16));
+                v[2] = elem16((uint16_t)(u.y & 0xffff));
+                v[3] = elem16((uint16_t)(u.y >> 16));
+            }
+            if (i == j) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = (ln.n > 4 * ln.q + r) ? v[r] : 0.f;
+            }
+        }
+        return v;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Tile source 2: A built from the keys.  S = K_c K_c^T on the matrix cores with the stored key
+// values as operands (16x16x32 for 16-bit keys, 16x16x4 for fp32 keys), then
+// A_ij = beta_i exp(g_i - g_j) S_ij in fp32 (paper Table 1, GDN / DeltaNet rows).
+// KD: storage type of K.  DKS: number of k-steps (32 channels each for 16-bit keys, 16 for fp32).
+// ---------------------------------------------------------------------------------------------
+template <int KD> struct KeyVec;
+template <> struct KeyVec<OP_F32> { typedef v4f type; };
+template <> struct KeyVec<OP_F16> { typedef v8h type; };
+template <> struct KeyVec<OP_BF16> { typedef v8bf type; };
+
+template <int KD> __device__ __forceinline__ v4f gram_step(typename KeyVec<KD>::type a, typename KeyVec<KD>::type b, v4f acc);
+template <> __device__ __forceinline__ v4f gram_step<OP_F32>(v4f a, v4f b, v4f acc)
+{
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r], b[r], acc, 0, 0, 0);
+    return acc;
+}
+template <> __device__ __forceinline__ v4f gram_step<OP_F16>(v8h a, v8h b, v4f acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ v4f gram_step<OP_BF16>(v8bf a, v8bf b, v4f acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+}
+
+template <int KD, int NB, int DKS> struct GramA {
+    typedef typename KeyVec<KD>::type kvec;
+    static constexpr int C = 16 * NB;
+    static constexpr int KSTEP = (KD == OP_F32) ? 16 : 32;  // channels per k-step
+    kvec k[NB][DKS];
+    // gate vectors: *_n indexed by the lane's column n, *_q by its row group (4q + r)
+    float beta_n[NB], g_n[NB];
+    v4f beta_q[NB], g_q[NB];
+    bool gated;
+    Lane ln;
+
+    // Kc: first key element of (chunk row 0, this head); row_stride in elements.
+    __device__ __forceinline__ void load_keys(const void* Kc, int64_t row_stride)
+    {
+        constexpr int per_lane = (KD == OP_F32) ? 4 : 8;
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int s = 0; s < DKS; ++s) {
+                const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + KSTEP * s + per_lane * ln.q;
+                if (KD == OP_F32)
+                    k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const float*>(Kc) + off);
+                else
+                    k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const uint16_t*>(Kc) + off);
+            }
+    }
+
+    // beta / g of the chunk's tokens through a wave-private LDS patch of 2*C floats.
+    // bc, gc: first element of (chunk row 0, this head); tok_stride in elements; gc may be null.
+    __device__ __forceinline__ void load_gate(const float* bc, const float* gc, int64_t tok_stride, float* lds)
+    {
+        const int l = 16 * ln.q + ln.n;
+        gated = (gc != nullptr);
+#pragma unroll
+        for (int t = l; t < C; t += 64) {
+            lds[t] = bc[t * tok_stride];
+            lds[C + t] = gated ? gc[t * tok_stride] : 0.f;
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            beta_n[i] = lds[16 * i + ln.n];
+            g_n[i] = lds[C + 16 * i + ln.n];
+            beta_q[i] = *reinterpret_cast<const v4f*>(&lds[16 * i + 4 * ln.q]);
+            g_q[i] = *reinterpret_cast<const v4f*>(&lds[C + 16 * i + 4 * ln.q]);
+        }
+        wave_lds_sync();
+    }
+
+    template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const
+    {
+        v4f s = zero4();
+#pragma unroll
+        for (int t = 0; t < DKS; ++t) s = TR ? gram_step<KD>(k[j][t], k[i][t], s) : gram_step<KD>(k[i][t], k[j][t], s);
+        v4f a;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            // N: element (row 16i + 4q + r, col 16j + n);  T: element (row 16i + n, col 16j + 4q + r)
+            const float b = TR ? beta_n[i] : beta_q[i][r];
+            float w = b;
+            if (gated) {
+                const float d = TR ? (g_n[i] - g_q[j][r]) : (g_q[i][r] - g_n[j]);
+                w = b * __builtin_amdgcn_exp2f(d * 1.44269504088896340736f);  // exp(d) = exp2(d log2 e)
+            }
+            const bool low = (i != j) || (TR ? (ln.n > 4 * ln.q + r) : (4 * ln.q + r > ln.n));
+            a[r] = low ? w * s[r] : 0.f;
+        }
+        return a;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Result store.  Tm: first element of this matrix's T.  Tile (i, j) is in T orientation when
+// IS_T(i, j): one 16-byte store per lane; otherwise four 4-byte stores.  Diagonal tiles get an
+// exact unit diagonal and exact zeros above it; tiles above the diagonal are zero-filled.
+// ---------------------------------------------------------------------------------------------
+template <int NB, class IsT>
+__device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, Lane ln)
+{
+    constexpr int C = 16 * NB;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (j > i) {
+                *reinterpret_cast<v4f*>(Tm + (int64_t)(16 * i + ln.n) * C + 16 * j + 4 * ln.q) = zero4();
+                continue;
+            }
+            v4f v = Tt[tix(i, j)];
+            if (is_t(i, j)) {
+                if (i == j) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = ln.n, col = 4 * ln.q + r;
+                        v[r] = (row == col) ? 1.f : ((row > col) ? v[r] : 0.f);
+                    }
+                }
+                *reinterpret_cast<v4f*>(Tm + (int64_t)(16 * i + ln.n) * C + 16 * j + 4 * ln.q) = v;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = 4 * ln.q + r, col = ln.n;
+                    float x = v[r];
+                    if (i == j) x = (row == col) ? 1.f : ((row > col) ? x : 0.f);
+                    Tm[(int64_t)(16 * i + row) * C + 16 * j + col] = x;
+                }
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward substitution, row by row, in fp32 vector arithmetic.  Lane = one column c of T:
+//   T[i][c] = [i == c] - sum_{j < i} A[i][j] T[j][c]
+// so every lane needs the same A[i][j]: the rows of A are staged through LDS, 16 rows at a
+// time (double-buffered), and read back with wave-uniform addresses (LDS broadcast).
+// C = 128 runs two passes of 64 columns; pass p only involves rows and columns >= 64 p.
+// lds: wave-private, 2 * 16 * (C + 4) floats.
+// ---------------------------------------------------------------------------------------------
+template <int NB> constexpr int fwd_lds_floats() { return 2 * 16 * (16 * NB + 4); }
+
+template <int NB, class ASrc>
+__device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, float* lds, Lane ln)
+{
+    constexpr int C = 16 * NB;
+    constexpr int LD = C + 4;
+    const int lane = 16 * ln.q + ln.n;
+#pragma unroll
+    for (int p = 0; p < C / 64; ++p) {
+        const int c = 64 * p + lane;  // this lane's column
+        float Tc[C];                  // Tc[k] = T[64p + k][c]
+        if (p > 0) {
+            // rows above this pass's diagonal block: columns >= 64p are zero there
+#pragma unroll 8
+            for (int i = 0; i < 64 * p; ++i) Tm[(int64_t)i * C + c] = 0.f;
+        }
+        v4f stage[NB];  // tiles (s, 4p..s) of the strip being staged, T orientation = row-major pieces
+        stage[4 * p] = A.template get<true>(4 * p, 4 * p);
+#pragma unroll
+        for (int s = 4 * p; s < NB; ++s) {
+            float* buf = lds + (s & 1) * 16 * LD;
+#pragma unroll
+            for (int j = 4 * p; j <= s; ++j) *reinterpret_cast<v4f*>(&buf[ln.n * LD + 16 * j + 4 * ln.q]) = stage[j];
+            wave_lds_sync();
+            if (s + 1 < NB) {
+#pragma unroll
+                for (int j = 4 * p; j <= s + 1; ++j) stage[j] = A.template get<true>(s + 1, j);
+            }
+#pragma unroll
+            for (int ii = 0; ii < 16; ++ii) {
+                const int i = 16 * s + ii;
+                float acc = 0.f;
+#pragma unroll
+                for (int j4 = 64 * p; j4 < i; j4 += 4) {
+                    const v4f a = *reinterpret_cast<const v4f*>(&buf[ii * LD + j4]);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (j4 + r < i) acc += a[r] * Tc[j4 + r - 64 * p];
+                }
+                const float t = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
+                Tc[i - 64 * p] = t;
+                Tm[(int64_t)i * C + c] = t;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernels
+// ---------------------------------------------------------------------------------------------
+template <int NB> constexpr int gate_lds_floats() { return 2 * 16 * NB; }
+
+template <int OP, int NB, int METHOD, class ASrc>
+__device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, float* lds, Lane ln)
+{
+    constexpr int NT = NB * (NB + 1) / 2;
+    if (METHOD == M_FWD) {
+        forward_substitution<NB>(src, Tm, lds, ln);
+    } else if (METHOD == M_NEUMANN) {
+        v4f Xt[NT];
+        neumann<OP, NB>(src, Xt, ln);
+        store_result<NB>(Tm, Xt, [](int, int) { return true; }, ln);
+    } else {
+        constexpr bool ROOT_T = true;
+        v4f Tt[NT];
+        block_recursive<OP, NB, ROOT_T, (METHOD == M_MIXED) ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE>(src, Tt, lds, ln);
+        store_result<NB>(Tm, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, ln);
+    }
+}
+
+template <int NB, int METHOD> constexpr int core_lds_floats()
+{
+    return METHOD == M_FWD ? fwd_lds_floats<NB>() : XPOSE_FLOATS;
+}
+
+template <int OP, int NB, int METHOD>
+__global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt)
+{
+    constexpr int C = 16 * NB;
+    __shared__ __attribute__((aligned(16))) float lds[core_lds_floats<NB, METHOD>()];
+    const int64_t m = blockIdx.x;
+    if (m >= n_mat) return;
+    const Lane ln = lane_id();
+    GlobalA<NB> src;
+    src.base = static_cast<const char*>(A) + m * C * C * (in_dt == OP_F32 ? 4 : 2);
+    src.dt = in_dt;
+    src.ln = ln;
+    invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
+}
+
+template <int KD, int OP, int NB, int METHOD, int DKS>
+__global__ __launch_bounds__(64) void k_gdn_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
+                                                    const float* __restrict__ g, float* __restrict__ T, int64_t n_chunk,
+                                                    int H, int d_k)
+{
+    constexpr int C = 16 * NB;
+    constexpr int CORE = core_lds_floats<NB, METHOD>();
+    constexpr int GATE = gate_lds_floats<NB>();
+    __shared__ __attribute__((aligned(16))) float lds[CORE > GATE ? CORE : GATE];
+    const int64_t m = blockIdx.x;       // (b * n_chunk + chunk) * H + h
+    const int h = (int)(m % H);
+    const int64_t bc = m / H;           // b * n_chunk + chunk  (Tlen = n_chunk * C, so token0 = bc * C)
+    const int64_t tok0 = bc * C;
+    const Lane ln = lane_id();
+    GramA<KD, NB, DKS> src;
+    src.ln = ln;
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
+    src.load_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, lds);
+    (void)n_chunk;
+    invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
+}
+
+}  // namespace triinv

@@ -1,0 +1,101 @@
+// 16 x 16 register tiles and the one matrix-core primitive everything is built from (gfx950).
+//
+// A logical 16 x 16 fp32 matrix M lives in 4 VGPRs of one 64-lane wavefront in the accumulator
+// layout of the 16x16 MFMA instructions: lane l = 16*q + n (q = l / 16, n = l % 16) holds
+//     v[r] = M[4*q + r][n],  r = 0..3.
+// The same four registers, narrowed to the operand type, are a valid B operand of M (contraction
+// over M's ROW index) and a valid A operand of M^T.  Hence the single primitive
+//     tn(X, Y) = X^T * Y          (X, Y, result all in the layout above)
+// needs no cross-lane movement between dependent products.  A matrix that must act as a LEFT
+// factor is therefore kept transposed ("T orientation": the tile registers hold M^T), a RIGHT
+// factor as is ("N orientation").
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace triinv {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+enum : int { OP_F32 = 0, OP_F16 = 1, OP_BF16 = 2 };
+
+struct Lane {
+    int q;  // lane / 16 : row group (rows 4q..4q+3 of a tile)
+    int n;  // lane % 16 : column of a tile
+};
+
+__device__ __forceinline__ Lane lane_id()
+{
+    int l = __lane_id();
+    return Lane{l >> 4, l & 15};
+}
+
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ short bf16_bits(float f)
+{
+    __bf16 b = (__bf16)f;
+    return __builtin_bit_cast(short, b);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b)
+{
+    return __builtin_bit_cast(float, ((uint32_t)b) << 16);
+}
+
+__device__ __forceinline__ float f16_to_f32(uint16_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+
+// Packed matrix-core operand of one tile.
+template <int OP> struct Opnd;
+template <> struct Opnd<OP_F32> { v4f x; };
+template <> struct Opnd<OP_F16> { v4h x; };
+template <> struct Opnd<OP_BF16> { v4s x; };
+
+template <int OP> __device__ __forceinline__ Opnd<OP> pack(v4f t);
+template <> __device__ __forceinline__ Opnd<OP_F32> pack<OP_F32>(v4f t) { return {t}; }
+template <> __device__ __forceinline__ Opnd<OP_F16> pack<OP_F16>(v4f t)
+{
+    v4h h;
+    h[0] = (_Float16)t[0]; h[1] = (_Float16)t[1]; h[2] = (_Float16)t[2]; h[3] = (_Float16)t[3];
+    return {h};
+}
+template <> __device__ __forceinline__ Opnd<OP_BF16> pack<OP_BF16>(v4f t)
+{
+    v4s s;
+    s[0] = bf16_bits(t[0]); s[1] = bf16_bits(t[1]); s[2] = bf16_bits(t[2]); s[3] = bf16_bits(t[3]);
+    return {s};
+}
+
+// acc + X^T * Y   (x packed from X, y packed from Y)
+template <int OP> __device__ __forceinline__ v4f tn(Opnd<OP> x, Opnd<OP> y, v4f acc);
+template <> __device__ __forceinline__ v4f tn<OP_F32>(Opnd<OP_F32> x, Opnd<OP_F32> y, v4f acc)
+{
+    // 16x16x4 fp32: k slot q of step r stands for contraction index 4q + r on both operands
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x[0], y.x[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x[1], y.x[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x[2], y.x[2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x[3], y.x[3], acc, 0, 0, 0);
+    return acc;
+}
+template <> __device__ __forceinline__ v4f tn<OP_F16>(Opnd<OP_F16> x, Opnd<OP_F16> y, v4f acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(x.x, y.x, acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ v4f tn<OP_BF16>(Opnd<OP_BF16> x, Opnd<OP_BF16> y, v4f acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(x.x, y.x, acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ v4f zero4() { return v4f{0.f, 0.f, 0.f, 0.f}; }
+
+// Index of lower tile (i, j), i >= j, in a packed array of NB*(NB+1)/2 tiles.
+__host__ __device__ constexpr int tix(int i, int j) { return i * (i + 1) / 2 + j; }
+
+}  // namespace triinv
