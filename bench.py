@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched triangular-inversion hot path on one MI355X.
+
+A "step" is one pass of the whole hot path -- load keys/beta/g, Gram on the matrix cores,
+gate + mask, inversion, store of T -- over one batch of synthetic input, i.e. one call of the
+fused C-ABI entry point `gdn_chunk_tri_inv_ex` on workload 2 (B=8, T=8192, H=16, d_k=128, C=64:
+16 384 chunk matrices, bf16 keys, scalar gate).  Inputs are resident in HBM before the timed
+region.  The timed steps rotate over several distinct input/output buffer sets so that no step
+finds its data in the 256 MB last-level cache left by the previous one.
+
+Prints ONE JSON line: the contract fields plus
+  roofline      achieved algorithmic GB/s of the kernel (HIP events on the launch stream) vs 8 TB/s
+  cpu_baseline  the fp64 oracle timed on the host cores on the same batch
+  parity        sampled outputs of the timed configuration checked against the oracle
+  methods       (with --table) matrices/s for every method / operand type, standalone and fused
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+METRIC = "64x64 tri-inversions/sec + effective TFLOP/s & GB/s vs roofline; rel error"
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
+# keyed by (workload index, method, op_dtype).  None = not measured for that configuration.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes_per_matrix(w, fused: bool, in_bytes: int = 4) -> int:
+    C, d = w.C, w.d_k
+    out = 4 * C * C
+    if not fused:
+        return in_bytes * C * (C - 1) // 2 + out          # strictly-lower A in, dense fp32 T out
+    kb = 2 if w.k_dtype == "bf16" else 4
+    n = C * d * kb + 4 * C + out                          # K, beta, T
+    if w.gate_kind == 0:
+        n += 4 * C
+    elif w.gate_kind == 1:
+        n += 4 * C * d
+    return n
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", type=int, default=2)
+    ap.add_argument("--method", type=int, default=1, help="0 fwd, 1 block recursive, 2 neumann, 3 mixed")
+    ap.add_argument("--op", type=int, default=2, help="operand type: 0 f32, 1 f16, 2 bf16")
+    ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
+    ap.add_argument("--table", action="store_true", help="also time every method / operand type")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the chunk matrices are independent; sharding is "
+              "a plain split of the batch with no exchange). Re-run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth_inputs as si
+    import paper_2605_21325_amd as tri
+    from paper_2605_21325_amd import build as tri_build
+
+    if not os.path.exists(tri.binding.LIB_PATH):
+        tri_build.build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = si.WORKLOADS[args.workload]
+    inp = si.make_inputs(w)
+    n_mat, C = w.n_mat, w.C
+    sets = []
+    for _ in range(max(1, args.nbuf)):
+        K = inp["K"].to(dev)
+        beta = inp["beta"].to(dev)
+        g = None if inp["g"] is None else inp["g"].to(dev)
+        T = torch.empty((n_mat, C, C), dtype=torch.float32, device=dev)
+        sets.append((K, beta, g, T))
+    torch.cuda.synchronize()
+
+    def step(i: int, method: int, op: int):
+        K, beta, g, T = sets[i % len(sets)]
+        tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=T, gate_kind=w.gate_kind, method=method, op_dtype=op)
+
+    def timed(method: int, op: int, steps: int, warmup: int):
+        for i in range(warmup):
+            step(i, method, op)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            evs[i][0].record()
+            step(i, method, op)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kern_ms = [a.elapsed_time(b) for a, b in evs]
+        return wall, kern_ms
+
+    wall, kern_ms = timed(args.method, args.op, args.steps, args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    value = n_mat * args.steps / wall
+    avg_kernel_ms = float(np.mean(kern_ms))
+    bytes_per_launch = algorithmic_bytes_per_matrix(w, fused=True) * n_mat
+    achieved = bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
+    flops_inv = C ** 3 / 3.0
+    flops_gram = C * C * w.d_k
+
+    # ---- parity of the timed configuration on sampled outputs ------------------------------
+    import oracle
+    from oracle import metrics
+
+    rng = np.random.default_rng(12345)
+    sel = np.unique(np.concatenate([[0, n_mat - 1], rng.integers(0, n_mat, size=62)])).tolist()
+    T_ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, C, sel=sel)
+    T_gpu = sets[(args.steps - 1) % len(sets)][3][sel].cpu().numpy().astype(np.float64)
+    err = metrics.forward_errors(T_ref, T_gpu)["rel_fro"]
+    A_ref = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, C, sel=sel)
+    res = metrics.residual(A_ref, T_gpu)["normalised"]
+    tol = 1e-5 if (args.op == 0 or args.method == 0) else 2e-2
+    parity = {"sampled_matrices": len(sel), "rel_fro_max": float(np.max(err)), "residual_max": float(np.max(res)),
+              "tolerance": tol, "ok": bool(np.max(err) <= tol and metrics.structure_ok(T_gpu))}
+
+    # ---- the oracle timed on the host cores -----------------------------------------------
+    cpu_baseline = None
+    if not args.no_cpu:
+        cores = oracle.hw_threads()
+        t0 = time.perf_counter()
+        oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, C, n_threads=cores)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": n_mat / dt, "unit": "matrices/s", "cores": cores, "kind": "oracle",
+                        "sample": f"the whole batch ({n_mat} matrices, fused build + fp64 forward substitution), "
+                                  f"{dt:.2f} s wall on {cores} threads"}
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "matrices/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": {0: "f32", 1: "f16", 2: "bf16"}[args.op] + "-operands/f32-accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{w.index}] {w.name}: B={w.B} T={w.Tlen} H={w.H} d_k={w.d_k} C={w.C} "
+                               f"-> {n_mat} matrices, fused gdn_chunk_tri_inv_ex",
+                   "method": tri.METHOD_NAMES[args.method], "op_dtype": tri.DTYPE_NAMES[args.op],
+                   "k_dtype": w.k_dtype, "buffer_sets": len(sets)},
+        "effective": {"GBps": achieved, "TFLOPs_inversion": flops_inv * n_mat / (avg_kernel_ms * 1e-3) / 1e12,
+                      "TFLOPs_with_gram": (flops_inv + flops_gram) * n_mat / (avg_kernel_ms * 1e-3) / 1e12,
+                      "kernel_ms_avg": avg_kernel_ms, "kernel_ms_min": float(np.min(kern_ms))},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get((w.index, args.method, args.op))},
+        "cpu_baseline": cpu_baseline,
+        "parity": parity,
+    }
+
+    if args.table:
+        table = []
+        A32 = None
+        if w.gate_kind != 1:
+            # input of the standalone entry point: the same chunk matrices, formed once with
+            # torch ops on the GPU outside any timed region (input preparation, not the product)
+            K, beta, g, _ = sets[0]
+            Kc = K.float().reshape(w.B, w.Tlen // C, C, w.H, w.d_k).permute(0, 1, 3, 2, 4)
+            S = Kc @ Kc.transpose(-1, -2)
+            bb = beta.reshape(w.B, w.Tlen // C, C, w.H).permute(0, 1, 3, 2)
+            S = S * bb[..., None]
+            if g is not None:
+                gg = g.reshape(w.B, w.Tlen // C, C, w.H).permute(0, 1, 3, 2)
+                S = S * torch.exp(gg[..., :, None] - gg[..., None, :])
+            A32 = torch.tril(S, -1).reshape(n_mat, C, C).contiguous()
+            del S, Kc
+        for method in (0, 1, 3, 2):
+            for op in (0, 1, 2):
+                if method == 0 and op != 0:
+                    continue
+                row = {"method": tri.METHOD_NAMES[method], "op": tri.DTYPE_NAMES[op]}
+                try:
+                    _, km = timed(method, op, 10, 3)
+                    row["fused_matrices_per_s"] = n_mat / (np.mean(km) * 1e-3)
+                    row["fused_GBps"] = algorithmic_bytes_per_matrix(w, True) * n_mat / (np.mean(km) * 1e-3) / 1e9
+                except tri.TriInvError as e:
+                    row["fused_error"] = str(e)
+                if A32 is not None:
+                    try:
+                        Ts = [s[3] for s in sets]
+                        for i in range(3):
+                            tri.tri_inv_ex(A32, T=Ts[i % len(Ts)], method=method, op_dtype=op)
+                        torch.cuda.synchronize()
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        for i in range(10):
+                            tri.tri_inv_ex(A32, T=Ts[i % len(Ts)], method=method, op_dtype=op)
+                        e1.record()
+                        torch.cuda.synchronize()
+                        ms = e0.elapsed_time(e1) / 10
+                        row["standalone_matrices_per_s"] = n_mat / (ms * 1e-3)
+                        row["standalone_GBps"] = algorithmic_bytes_per_matrix(w, False) * n_mat / (ms * 1e-3) / 1e9
+                    except tri.TriInvError as e:
+                        row["standalone_error"] = str(e)
+                table.append(row)
+        out["methods"] = table
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,127 @@
+"""The C-ABI boundary without a GPU: the library loads, exports everything include/triinv.h
+declares, and every argument error is reported by the host-side checks before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_21325_amd as tri
+from paper_2605_21325_amd import build as tri_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "triinv.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(tri.binding.LIB_PATH):
+        tri_build.build()
+    return tri.lib()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", src, flags=re.M)
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert set(names) == set(tri.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_header_enums_match_binding():
+    src = open(HEADER).read()
+    for name, val in [("TRIINV_F32", tri.F32), ("TRIINV_F16", tri.F16), ("TRIINV_BF16", tri.BF16),
+                      ("TRIINV_FWD_SUBST", tri.FWD_SUBST), ("TRIINV_BLOCK_RECURSIVE", tri.BLOCK_RECURSIVE),
+                      ("TRIINV_NEUMANN", tri.NEUMANN), ("TRIINV_MIXED", tri.MIXED),
+                      ("TRIINV_GATE_SCALAR", tri.GATE_SCALAR), ("TRIINV_GATE_PER_CHANNEL", tri.GATE_PER_CHANNEL),
+                      ("TRIINV_GATE_NONE", tri.GATE_NONE)]:
+        assert re.search(rf"\b{name}\s*=\s*{val}\b", src), name
+
+
+def test_version_and_status_strings(L):
+    assert tri.version() >= 100
+    seen = set()
+    for code in range(0, -10, -1):
+        s = tri.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 10
+    assert tri.status_string(-99) == "unknown status"
+
+
+# fake, never dereferenced device addresses (all checks below fail before any launch)
+P = 0x7F0000000000
+Q = 0x7F1000000000
+
+
+def test_tri_inv_argument_errors(L):
+    ex = L.tri_inv_ex
+    ok_args = dict(A=P, T=Q, n=4, C=64, dt=0, m=1, op=0)
+
+    def call(**kw):
+        a = {**ok_args, **kw}
+        return ex(a["A"], a["T"], a["n"], a["C"], a["dt"], a["m"], a["op"], None, 0)
+
+    assert call(n=0) == 0                       # empty batch: success, nothing launched
+    assert call(n=0, A=None, T=None) == 0
+    assert call(C=32) == -2 and call(C=96) == -2 and call(C=0) == -2
+    assert call(dt=3) == -3 and call(op=-1) == -3
+    assert call(m=4) == -4 and call(m=-1) == -4
+    assert call(n=-1) == -5
+    assert call(A=None) == -1 and call(T=None) == -1
+    assert call(A=P + 4) == -6 and call(T=Q + 8) == -6
+    assert call(T=P) == -7                                  # same buffer
+    assert call(T=P + 64 * 64 * 4 * 4 - 16) == -7           # tail overlap
+    assert L.tri_inv(None, None, 0, 64, 0, 1) == 0
+    assert L.tri_inv(P, Q, 1, 64, 7, 1) == -3
+
+
+def test_adjacent_buffers_do_not_alias(L):
+    # checked through a failing later argument so that nothing is launched: flags != 0 is
+    # rejected after the alias test
+    n = 4
+    assert L.tri_inv_ex(P, P + n * 64 * 64 * 4, n, 64, 0, 1, 0, None, 0x80) == -9
+    assert L.tri_inv_ex(P, P + n * 64 * 64 * 4 - 16, n, 64, 0, 1, 0, None, 0x80) == -7
+    assert L.tri_inv_ex(P, P + n * 64 * 64 * 2, n, 64, 2, 1, 0, None, 0x80) == -9   # bf16 input is half the size
+
+
+def test_gdn_argument_errors(L):
+    ex = L.gdn_chunk_tri_inv_ex
+    base = dict(K=P, beta=Q, g=Q + (1 << 30), T=Q + (2 << 30), B=1, Tlen=128, H=2, d_k=128, C=64, kd=2, gate=0, m=1, op=2)
+
+    def call(**kw):
+        a = {**base, **kw}
+        return ex(a["K"], a["beta"], a["g"], a["T"], a["B"], a["Tlen"], a["H"], a["d_k"], a["C"], a["kd"], a["gate"],
+                  a["m"], a["op"], None, 0)
+
+    assert call(Tlen=0) == 0
+    assert call(C=100) == -2
+    assert call(kd=5) == -3 and call(op=9) == -3
+    assert call(m=17) == -4 and call(gate=3) == -4
+    assert call(B=0) == -5 and call(H=-1) == -5 and call(d_k=0) == -5
+    assert call(Tlen=100) == -5                 # not a multiple of C
+    assert call(d_k=48) == -5 and call(d_k=512) == -5
+    assert call(K=None) == -1 and call(beta=None) == -1 and call(T=None) == -1 and call(g=None) == -1
+    assert call(K=P + 2) == -6 and call(g=Q + (1 << 30) + 4) == -6
+    assert call(T=P) == -7 and call(T=Q) == -7 and call(T=Q + (1 << 30)) == -7
+    assert L.gdn_chunk_tri_inv(P, Q, None, Q + (2 << 30), 1, 128, 2, 128, 64) == -1
+
+
+def test_binding_refuses_host_tensors_and_missing_library(monkeypatch, L):
+    import torch
+
+    A = torch.zeros(1, 64, 64)
+    with pytest.raises(ValueError):
+        tri.tri_inv(A)
+    with pytest.raises(TypeError):
+        tri.binding.dtype_code(torch.float64)
+    # no fallback: a missing shared library is an error, not a silent CPU path
+    monkeypatch.setattr(tri.binding, "_lib", None)
+    monkeypatch.setattr(tri.binding, "LIB_PATH", "/nonexistent/libtriinv.so")
+    with pytest.raises(FileNotFoundError):
+        tri.lib()

@@ -1,0 +1,243 @@
+"""Parity of the HIP path against the fp64 CPU oracle, element by element, on the same seeded
+inputs, through the C-ABI.  Tolerances (relative Frobenius error per matrix, maximum over the
+batch): 1e-5 for the fp32 path (forward substitution, fp32 matrix-core operands), 2e-2 for
+fp16 / bf16 operands.  The Neumann product is held to them on the benign workloads only; on the
+stress workload the paper predicts it breaks, and its error is reported, not asserted."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import metrics
+import synth_inputs as si
+import paper_2605_21325_amd as tri
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL = {tri.F32: 1e-5, tri.F16: 2e-2, tri.BF16: 2e-2}
+MFMA_METHODS = [tri.BLOCK_RECURSIVE, tri.MIXED, tri.NEUMANN]
+ALL = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in MFMA_METHODS for o in (tri.F32, tri.F16, tri.BF16)]
+
+
+def ids(mo):
+    return f"{tri.METHOD_NAMES[mo[0]]}-{tri.DTYPE_NAMES[mo[1]]}"
+
+
+def check(T_gpu: torch.Tensor, T_ref: np.ndarray, tol: float, what: str):
+    torch.cuda.synchronize()
+    Tg = T_gpu.cpu().numpy()
+    assert metrics.structure_ok(Tg), f"{what}: not exactly unit lower triangular"
+    err = metrics.forward_errors(T_ref, Tg.astype(np.float64))["rel_fro"]
+    assert np.isfinite(err).all(), f"{what}: non-finite output"
+    assert err.max() <= tol, f"{what}: rel_fro max {err.max():.3e} > {tol}"
+    return err.max()
+
+
+@pytest.fixture(scope="module")
+def cases():
+    """Small instances of every workload recipe: inputs, fp64 A, fp64 T."""
+    out = {}
+    for idx, kw in [(0, {}), (1, dict(Tlen=1024)), (2, dict(B=2, Tlen=512, H=5)), (4, dict(Tlen=512, H=3))]:
+        inp = si.make_inputs(si.workload(idx, **kw))
+        w = inp["workload"]
+        A = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+        out[idx] = dict(inp=inp, w=w, A=A, T=oracle.tri_inv(A))
+    return out
+
+
+# ------------------------------------------------------------------ standalone tri_inv
+@pytest.mark.parametrize("mo", ALL, ids=ids)
+@pytest.mark.parametrize("idx", [0, 1, 4])
+def test_tri_inv_fp32_input(cases, idx, mo):
+    method, op = mo
+    c = cases[idx]
+    if c["w"].C == 128 and method == tri.NEUMANN:
+        pytest.skip("Neumann product at C = 128 is not built")
+    A32 = torch.from_numpy(c["A"].astype(np.float32))
+    T_ref = oracle.tri_inv(A32)                      # oracle on the values as stored
+    T = tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op)
+    tol = TOL[op]
+    if idx == 4 and method == tri.MIXED and op == tri.BF16:
+        tol = 4e-2  # mixed recursion without refinement loses digits on the stress input (paper Sec. 4.1)
+    check(T, T_ref, tol, f"cfg{idx} {ids(mo)}")
+
+
+@pytest.mark.parametrize("dt", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("method", [tri.FWD_SUBST, tri.BLOCK_RECURSIVE, tri.NEUMANN, tri.MIXED])
+def test_tri_inv_16bit_input_short_form(cases, dt, method):
+    # short form: operands in the input's own type; the oracle widens the stored values exactly
+    A = torch.from_numpy(cases[1]["A"].astype(np.float32)).to(dt)
+    T_ref = oracle.tri_inv(A)
+    T = tri.tri_inv(A.to(DEV), method=method)
+    check(T, T_ref, 1e-5 if method == tri.FWD_SUBST else 2e-2, f"short form {dt} {tri.METHOD_NAMES[method]}")
+    # same stored values, fp32 operands: the fp32 tolerance holds against the same oracle result
+    T = tri.tri_inv_ex(A.to(DEV), method=method, op_dtype=tri.F32)
+    check(T, T_ref, 1e-5, f"{dt} input, f32 operands")
+
+
+@pytest.mark.parametrize("C", [64, 128])
+@pytest.mark.parametrize("mo", [(tri.FWD_SUBST, tri.F32), (tri.BLOCK_RECURSIVE, tri.F32), (tri.BLOCK_RECURSIVE, tri.BF16),
+                                (tri.MIXED, tri.F16), (tri.NEUMANN, tri.F32)], ids=ids)
+def test_entries_on_and_above_the_diagonal_are_ignored(C, mo):
+    method, op = mo
+    if C == 128 and method == tri.NEUMANN:
+        pytest.skip("Neumann product at C = 128 is not built")
+    n = 37  # ragged: not a multiple of anything
+    dirty = si.random_strict_lower(n, C, 0.5 / np.sqrt(C), seed=3, garbage_upper=True)
+    clean = si.random_strict_lower(n, C, 0.5 / np.sqrt(C), seed=3, garbage_upper=False)
+    assert torch.equal(torch.tril(dirty, -1), torch.tril(clean, -1))
+    Td = tri.tri_inv_ex(dirty.to(DEV), method=method, op_dtype=op)
+    Tc = tri.tri_inv_ex(clean.to(DEV), method=method, op_dtype=op)
+    torch.cuda.synchronize()
+    assert torch.equal(Td, Tc)                       # bit-identical: garbage never enters the arithmetic
+    check(Tc, oracle.tri_inv(clean), TOL[op], f"random lower C={C} {ids(mo)}")
+
+
+@pytest.mark.parametrize("n_mat", [0, 1, 3])
+def test_tiny_batches(n_mat):
+    A = si.random_strict_lower(max(n_mat, 1), 64, 0.05, seed=4, garbage_upper=False)[:n_mat].contiguous()
+    guard = torch.full((n_mat + 1, 64, 64), 7.0, device=DEV)
+    T = tri.tri_inv_ex(A.to(DEV), T=guard[:n_mat], method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32)
+    torch.cuda.synchronize()
+    assert (guard[n_mat] == 7.0).all()               # nothing written past the batch
+    if n_mat:
+        check(T, oracle.tri_inv(A), 1e-5, f"n_mat={n_mat}")
+
+
+def test_non_finite_values_stay_in_their_matrix():
+    A = si.random_strict_lower(5, 64, 0.05, seed=5, garbage_upper=False)
+    A[2, 40, 3] = float("nan")
+    A[3, 10, 9] = float("inf")
+    ref = oracle.tri_inv(A)
+    for method, op in [(tri.FWD_SUBST, tri.F32), (tri.BLOCK_RECURSIVE, tri.BF16), (tri.NEUMANN, tri.F32)]:
+        T = tri.tri_inv_ex(A.to(DEV), method=method, op_dtype=op).cpu().numpy()
+        for m in (0, 1, 4):
+            e = metrics.forward_errors(ref[m][None], T[m][None].astype(np.float64))["rel_fro"][0]
+            assert e <= TOL[op]
+        assert not np.isfinite(T[2]).all() and not np.isfinite(T[3]).all()
+
+
+def test_runs_on_the_callers_stream(cases):
+    c = cases[1]
+    A32 = torch.from_numpy(c["A"].astype(np.float32)).to(DEV)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        T = tri.tri_inv_ex(A32, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32)          # picks the current stream
+        T2 = tri.tri_inv_ex(A32, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32, stream=s)
+    s.synchronize()
+    assert torch.equal(T, T2)
+    check(T, oracle.tri_inv(A32.cpu()), 1e-5, "side stream")
+
+
+# ------------------------------------------------------------------ fused gdn_chunk_tri_inv
+@pytest.mark.parametrize("mo", ALL, ids=ids)
+@pytest.mark.parametrize("idx", [0, 1, 2, 4])
+def test_fused_matches_oracle(cases, idx, mo):
+    method, op = mo
+    c = cases[idx]
+    w, inp = c["w"], c["inp"]
+    if w.C == 128 and method == tri.NEUMANN:
+        pytest.skip("Neumann product at C = 128 is not built")
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, w.C, gate_kind=w.gate_kind,
+                                 method=method, op_dtype=op)
+    tol = TOL[op]
+    if idx == 4 and method == tri.MIXED and op == tri.BF16:
+        tol = 4e-2
+    check(T, c["T"], tol, f"fused cfg{idx} {ids(mo)}")
+
+
+def test_fused_short_form_and_f16_keys(cases):
+    c = cases[1]
+    w, inp = c["w"], c["inp"]
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    T = tri.gdn_chunk_tri_inv(K, beta, g, w.C)
+    check(T, c["T"], 2e-2, "short form")
+    T_ex = tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=tri.GATE_SCALAR, method=tri.BLOCK_RECURSIVE, op_dtype=tri.BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(T, T_ex)
+    # fp16 keys: the same recipe stored in fp16
+    K16 = inp["K"].to(torch.float16)
+    ref = oracle.gdn_chunk_tri_inv(K16, inp["beta"], inp["g"], w.gate_kind, w.C)
+    T16 = tri.gdn_chunk_tri_inv_ex(K16.to(DEV), beta, g, w.C, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32)
+    check(T16, ref, 1e-5, "fp16 keys")
+
+
+def test_fused_gate_kinds_agree(cases):
+    # zero log-decay through the scalar-gate path == the no-gate path, bit for bit
+    c = cases[1]
+    w, inp = c["w"], c["inp"]
+    K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+    z = torch.zeros_like(inp["g"]).to(DEV)
+    T0 = tri.gdn_chunk_tri_inv_ex(K, beta, None, w.C, gate_kind=tri.GATE_NONE, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32)
+    Tz = tri.gdn_chunk_tri_inv_ex(K, beta, z, w.C, gate_kind=tri.GATE_SCALAR, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32)
+    torch.cuda.synchronize()
+    assert torch.equal(T0, Tz)
+
+
+def test_unbuilt_combinations_report_unsupported(cases):
+    c = cases[1]
+    w, inp = c["w"], c["inp"]
+    K96 = torch.zeros(1, 64, 2, 96, dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros(1, 64, 2, device=DEV)
+    with pytest.raises(tri.TriInvError) as e:
+        tri.gdn_chunk_tri_inv_ex(K96, b, b, 64)
+    assert e.value.status == -9
+    A = torch.zeros(2, 128, 128, device=DEV)
+    with pytest.raises(tri.TriInvError) as e:
+        tri.tri_inv_ex(A, method=tri.NEUMANN, op_dtype=tri.F32)
+    assert e.value.status == -9
+
+
+# ------------------------------------------------------------------ full-size workloads, sampled
+def _sample(n_mat, k=48, seed=0):
+    rng = np.random.default_rng(seed)
+    return np.unique(np.concatenate([[0, 1, n_mat - 1], rng.integers(0, n_mat, size=k)])).tolist()
+
+
+@pytest.mark.parametrize("idx,mo", [(1, (tri.BLOCK_RECURSIVE, tri.BF16)), (1, (tri.FWD_SUBST, tri.F32)),
+                                    (2, (tri.BLOCK_RECURSIVE, tri.BF16)), (2, (tri.BLOCK_RECURSIVE, tri.F32)),
+                                    (2, (tri.MIXED, tri.F16)), (2, (tri.NEUMANN, tri.BF16)), (2, (tri.FWD_SUBST, tri.F32)),
+                                    (4, (tri.BLOCK_RECURSIVE, tri.F32)), (4, (tri.BLOCK_RECURSIVE, tri.BF16)),
+                                    (4, (tri.FWD_SUBST, tri.F32))],
+                         ids=lambda v: ids(v) if isinstance(v, tuple) else f"cfg{v}")
+def test_full_size_workload_sampled(idx, mo):
+    """The launch configuration the benchmark times, at the workload's full size; the oracle
+    recomputes a sample of the output matrices one by one, and the structural property is
+    checked on every matrix."""
+    method, op = mo
+    w = si.WORKLOADS[idx]
+    inp = si.make_inputs(w)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, w.C, gate_kind=w.gate_kind,
+                                 method=method, op_dtype=op)
+    torch.cuda.synchronize()
+    sel = _sample(w.n_mat)
+    T_ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C, sel=sel)
+    check(T[sel], T_ref, TOL[op], f"full cfg{idx} {ids(mo)}")
+    # every matrix: exact unit lower triangle, entries bounded by one (Cor. 2.1 and its source)
+    diag = torch.diagonal(T, dim1=1, dim2=2)
+    assert bool((diag == 1).all())
+    assert bool((torch.triu(T, 1) == 0).all())
+    assert float(T.abs().max()) <= 1.0 + (1e-4 if op == tri.F32 else 5e-2)
+
+
+def test_neumann_on_the_stress_input_is_reported_not_asserted(cases, capsys):
+    """C = 64 sub-blocks of the stress recipe: large ||A||, the repeated squaring overflows or
+    cancels (paper Sec. 3.2, Sec. 4.1).  The library must return whatever the algorithm yields."""
+    inp = si.make_inputs(si.workload(4, Tlen=512, H=3, C=64))
+    w = inp["workload"]
+    A = oracle.build_A(inp["K"], inp["beta"], None, si.GATE_NONE, 64)
+    T_ref = oracle.tri_inv(A)
+    A32 = torch.from_numpy(A.astype(np.float32)).to(DEV)
+    lines = []
+    for op in (tri.F32, tri.F16, tri.BF16):
+        T = tri.tri_inv_ex(A32, method=tri.NEUMANN, op_dtype=op).cpu().numpy().astype(np.float64)
+        e = metrics.forward_errors(T_ref, T)["rel_fro"]
+        lines.append(f"neumann {tri.DTYPE_NAMES[op]} on stress C=64: rel_fro max {np.nanmax(e):.3e}, "
+                     f"non-finite matrices {int((~np.isfinite(e)).sum())}/{len(e)}")
+        Tb = tri.tri_inv_ex(A32, method=tri.BLOCK_RECURSIVE, op_dtype=op)
+        check(Tb, T_ref, TOL[op], "blocked recursion on the same input")
+    with capsys.disabled():
+        print("\n" + "\n".join(lines))
