@@ -46,7 +46,9 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
 
     TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream)};
     int nb = 1;
-    if (C == 64) {
+    if (method == TRIINV_FWD_SUBST) {
+        nb = C == 64 ? launch_tri_inv_nb4_op0_fwd(a) : launch_tri_inv_nb8_op0_fwd(a);
+    } else if (C == 64) {
         nb = op_dtype == TRIINV_F32 ? launch_tri_inv_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb4_op1(a) : launch_tri_inv_nb4_op2(a);
     } else {
         nb = op_dtype == TRIINV_F32 ? launch_tri_inv_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb8_op1(a) : launch_tri_inv_nb8_op2(a);
@@ -79,11 +81,16 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
     if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (flags != 0) return TRIINV_ERR_UNSUPPORTED;
-    if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
+    if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
 
     GdnArgs a{K, beta, need_g ? g : nullptr, T, n_mat, n_chunk, H, d_k, k_dtype, gate_kind, method, static_cast<hipStream_t>(hip_stream)};
     int nb = 1;
-    if (C == 64) {
+    if (method == TRIINV_FWD_SUBST) {
+        if (C == 64)
+            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1_fwd(a) : launch_gdn_nb4_op2_fwd(a);
+        else
+            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1_fwd(a) : launch_gdn_nb8_op2_fwd(a);
+    } else if (C == 64) {
         nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1(a) : launch_gdn_nb4_op2(a);
     } else {
         nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1(a) : launch_gdn_nb8_op2(a);

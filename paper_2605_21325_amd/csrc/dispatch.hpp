@@ -33,7 +33,8 @@ struct GdnArgs {
 // Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.
 #define TRIINV_DECL(NB, OP)                                  \
     int launch_tri_inv_nb##NB##_op##OP(const TriInvArgs& a); \
-    int launch_gdn_nb##NB##_op##OP(const GdnArgs& a);
+    int launch_gdn_nb##NB##_op##OP(const GdnArgs& a);        \
+    int launch_gdn_nb##NB##_op##OP##_fwd(const GdnArgs& a);
 TRIINV_DECL(4, 0)
 TRIINV_DECL(4, 1)
 TRIINV_DECL(4, 2)
@@ -41,5 +42,7 @@ TRIINV_DECL(8, 0)
 TRIINV_DECL(8, 1)
 TRIINV_DECL(8, 2)
 #undef TRIINV_DECL
+int launch_tri_inv_nb4_op0_fwd(const TriInvArgs& a);
+int launch_tri_inv_nb8_op0_fwd(const TriInvArgs& a);
 
 }  // namespace triinv

@@ -1,15 +1,26 @@
-// Kernel instantiations for one (C = 16 * TRIINV_INST_NB, operand type TRIINV_INST_OP) pair.
+// Kernel instantiations for one (C = 16 * TRIINV_INST_NB, operand type TRIINV_INST_OP) pair: the
+// matrix-core methods, or -- with TRIINV_INST_FWD=1 -- forward substitution alone (its fully
+// unrolled code is the slowest to compile, so it gets translation units of its own; the gated
+// keys of the per-channel kernel still use TRIINV_INST_OP as their operand type).
 #include "dispatch.hpp"
 #include "kernels.hpp"
 
 #ifndef TRIINV_INST_NB
-#error "compile with -DTRIINV_INST_NB=4|8 -DTRIINV_INST_OP=0|1|2"
+#error "compile with -DTRIINV_INST_NB=4|8 -DTRIINV_INST_OP=0|1|2 [-DTRIINV_INST_FWD=1]"
+#endif
+#ifndef TRIINV_INST_FWD
+#define TRIINV_INST_FWD 0
 #endif
 
 namespace triinv {
 
-#define CAT_(a, b, c, d) a##b##c##d
-#define CAT(a, b, c, d) CAT_(a, b, c, d)
+#define CAT_(a, b, c, d, e) a##b##c##d##e
+#define CAT(a, b, c, d, e) CAT_(a, b, c, d, e)
+#if TRIINV_INST_FWD
+#define SUFFIX _fwd
+#else
+#define SUFFIX
+#endif
 
 constexpr int NB = TRIINV_INST_NB;
 constexpr int OP = TRIINV_INST_OP;
@@ -20,20 +31,24 @@ template <int METHOD> static int go_tri(const TriInvArgs& a)
     return 0;
 }
 
-int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const TriInvArgs& a)
+#if !(TRIINV_INST_FWD && TRIINV_INST_OP != 0)
+int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const TriInvArgs& a)
 {
     switch (a.method) {
-#if TRIINV_INST_OP == 0
+#if TRIINV_INST_FWD
     case M_FWD: return go_tri<M_FWD>(a);
-#endif
+#else
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);
-#if TRIINV_INST_NB == 4
+#if TRIINV_INST_NB == 4  // the one-wave register version does not fit C = 128 without spilling; not built
     case M_NEUMANN: return go_tri<M_NEUMANN>(a);
+#endif
 #endif
     default: return 1;
     }
 }
+
+#endif
 
 template <int KD, int METHOD, int DKS> static int go_gdn(const GdnArgs& a)
 {
@@ -45,21 +60,48 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const GdnArgs& a)
 template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 {
     switch (a.method) {
-#if TRIINV_INST_OP == 0
+#if TRIINV_INST_FWD
     case M_FWD: return go_gdn<KD, M_FWD, DKS>(a);
-#endif
+#else
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
 #if TRIINV_INST_NB == 4
     case M_NEUMANN: return go_gdn<KD, M_NEUMANN, DKS>(a);
 #endif
+#endif
     default: return 1;
     }
 }
 
-int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const GdnArgs& a)
+template <int METHOD> static int go_kda(const GdnArgs& a)
 {
-    if (a.gate == G_CHANNEL) return 1;
+    hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta, a.g, a.T,
+                       a.n_chunk, a.H, a.d_k, a.k_dt);
+    return 0;
+}
+
+static int kda_method(const GdnArgs& a)
+{
+    switch (a.method) {
+#if TRIINV_INST_FWD
+    case M_FWD: return go_kda<M_FWD>(a);
+#else
+    case M_BLOCK: return go_kda<M_BLOCK>(a);
+    case M_MIXED: return go_kda<M_MIXED>(a);
+#if TRIINV_INST_NB == 4
+    case M_NEUMANN: return go_kda<M_NEUMANN>(a);
+#endif
+#endif
+    default: return 1;
+    }
+}
+
+int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const GdnArgs& a)
+{
+    if (a.gate == G_CHANNEL) return kda_method(a);
+#if TRIINV_INST_FWD && TRIINV_INST_OP != 0
+    return 1;
+#else
     if (a.k_dt == OP_F32) {
         if (a.d_k == 64) return gdn_method<OP_F32, 4>(a);
         if (a.d_k == 128) return gdn_method<OP_F32, 8>(a);
@@ -71,6 +113,7 @@ int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const GdnArgs& a)
         if (a.d_k == 128) return gdn_method<OP_F16, 4>(a);
     }
     return 1;
+#endif
 }
 
 }  // namespace triinv

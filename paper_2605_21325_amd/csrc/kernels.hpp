@@ -166,6 +166,170 @@ template <int KD, int NB, int DKS> struct GramA {
 };
 
 // ---------------------------------------------------------------------------------------------
+// Which tiles of A, in which orientation, a method asks for (used by sources that have to form
+// every tile up front).  The blocked recursion wants an off-diagonal tile in the orientation
+// opposite to that of the merge that consumes it; that merge belongs to the smallest aligned
+// block pair containing tile rows i and j.
+// ---------------------------------------------------------------------------------------------
+constexpr bool ROOT_T = true;  // the last merge of the blocked recursion is produced in T orientation
+
+template <int NB> __host__ __device__ constexpr bool merge_block_is_T(int i, int j)
+{
+    int h = 1;
+    while ((i / (2 * h)) != (j / (2 * h))) h *= 2;
+    return (2 * h == NB) ? ROOT_T : (((i / (2 * h)) & 1) != 0);
+}
+
+template <int NB, int METHOD> __host__ __device__ constexpr bool need_tile(int i, int j, bool tr)
+{
+    if (METHOD == M_FWD) return tr;
+    if (METHOD == M_NEUMANN) return true;
+    if (i == j) return true;
+    return merge_block_is_T<NB>(i, j) ? !tr : tr;
+}
+
+// Tile source 3: all tiles precomputed in registers.
+template <int NB> struct PreA {
+    v4f n[NB * (NB + 1) / 2], t[NB * (NB + 1) / 2];
+    template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const { return TR ? t[tix(i, j)] : n[tix(i, j)]; }
+};
+
+// One k-step (32 channels; lane (q, n) holds channels 8q..8q+7 of row n) as a matrix-core operand.
+template <int OPG> struct GOp;
+template <> struct GOp<OP_F32> { float x[8]; };
+template <> struct GOp<OP_F16> { v8h x; };
+template <> struct GOp<OP_BF16> { v8bf x; };
+
+template <int OPG> __device__ __forceinline__ GOp<OPG> gpack(const float (&v)[8]);
+template <> __device__ __forceinline__ GOp<OP_F32> gpack<OP_F32>(const float (&v)[8])
+{
+    GOp<OP_F32> o;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) o.x[r] = v[r];
+    return o;
+}
+template <> __device__ __forceinline__ GOp<OP_F16> gpack<OP_F16>(const float (&v)[8])
+{
+    GOp<OP_F16> o;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) o.x[r] = (_Float16)v[r];
+    return o;
+}
+template <> __device__ __forceinline__ GOp<OP_BF16> gpack<OP_BF16>(const float (&v)[8])
+{
+    GOp<OP_BF16> o;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) o.x[r] = (__bf16)v[r];
+    return o;
+}
+
+template <int OPG> __device__ __forceinline__ v4f gstep(const GOp<OPG>& a, const GOp<OPG>& b, v4f acc);
+template <> __device__ __forceinline__ v4f gstep<OP_F32>(const GOp<OP_F32>& a, const GOp<OP_F32>& b, v4f acc)
+{
+#pragma unroll
+    for (int r = 0; r < 8; ++r) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x[r], b.x[r], acc, 0, 0, 0);
+    return acc;
+}
+template <> __device__ __forceinline__ v4f gstep<OP_F16>(const GOp<OP_F16>& a, const GOp<OP_F16>& b, v4f acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a.x, b.x, acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ v4f gstep<OP_BF16>(const GOp<OP_BF16>& a, const GOp<OP_BF16>& b, v4f acc)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.x, b.x, acc, 0, 0, 0);
+}
+
+// Eight consecutive key channels of one row, widened to fp32 (storage type chosen at run time).
+__device__ __forceinline__ void load_key8(const void* Kc, int kd, int64_t off, float (&v)[8])
+{
+    if (kd == OP_F32) {
+        const v4f a = *reinterpret_cast<const v4f*>(static_cast<const float*>(Kc) + off);
+        const v4f b = *reinterpret_cast<const v4f*>(static_cast<const float*>(Kc) + off + 4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { v[r] = a[r]; v[4 + r] = b[r]; }
+    } else {
+        const uint4 u = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(Kc) + off);
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint16_t lo = (uint16_t)(w[r] & 0xffff), hi = (uint16_t)(w[r] >> 16);
+            v[2 * r] = kd == OP_F16 ? f16_to_f32(lo) : bf16_to_f32(lo);
+            v[2 * r + 1] = kd == OP_F16 ? f16_to_f32(hi) : bf16_to_f32(hi);
+        }
+    }
+}
+
+// Per-channel gate (paper Table 1, KDA row): A_ij = beta_i sum_c k_ic k_jc exp(g_ic - g_jc)
+//   = beta_i [(K * exp(G - a)) (K * exp(a - G))^T]_ij   for any per-channel anchor a;
+// a is row C/2 of the chunk's G, so both gated factors stay within exp(+-half the chunk's decay).
+// The gated keys are rounded to OPG and contracted on the matrix cores, 32 channels per step,
+// accumulating every tile the method needs; nothing but K, G, beta is read, nothing stored.
+// Kc / gc: element (chunk row 0, this head, channel 0); row_stride in elements (same for both).
+template <int OPG, int NB, int METHOD>
+__device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* Kc, int kd, const float* gc, int64_t row_stride,
+                                                    const float* bc, int64_t tok_stride, int d_k, float* lds, Lane ln)
+{
+    constexpr int C = 16 * NB;
+    constexpr float LOG2E = 1.44269504088896340736f;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            out.n[tix(i, j)] = zero4();
+            out.t[tix(i, j)] = zero4();
+        }
+    for (int s = 0; s < d_k / 32; ++s) {
+        const int ch = 32 * s + 8 * ln.q;
+        const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch);
+        const v4f a1 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch + 4);
+        GOp<OPG> pp[NB], pm[NB];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + ch;
+            float kv[8];
+            load_key8(Kc, kd, off, kv);
+            const v4f g0 = *reinterpret_cast<const v4f*>(gc + off);
+            const v4f g1 = *reinterpret_cast<const v4f*>(gc + off + 4);
+            float up[8], dn[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const float d = ((r < 4) ? (g0[r] - a0[r]) : (g1[r - 4] - a1[r - 4])) * LOG2E;
+                up[r] = kv[r] * __builtin_amdgcn_exp2f(d);
+                dn[r] = kv[r] * __builtin_amdgcn_exp2f(-d);
+            }
+            pp[i] = gpack<OPG>(up);
+            pm[i] = gpack<OPG>(dn);
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                if (need_tile<NB, METHOD>(i, j, false)) out.n[tix(i, j)] = gstep<OPG>(pp[i], pm[j], out.n[tix(i, j)]);
+                if (need_tile<NB, METHOD>(i, j, true)) out.t[tix(i, j)] = gstep<OPG>(pm[j], pp[i], out.t[tix(i, j)]);
+            }
+    }
+    // beta_i row scaling and the strictly-lower mask
+    const int l = 16 * ln.q + ln.n;
+#pragma unroll
+    for (int t = l; t < C; t += 64) lds[t] = bc[t * tok_stride];
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const float bn = lds[16 * i + ln.n];
+        const v4f bq = *reinterpret_cast<const v4f*>(&lds[16 * i + 4 * ln.q]);
+#pragma unroll
+        for (int j = 0; j <= i; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool lowN = (i != j) || (4 * ln.q + r > ln.n), lowT = (i != j) || (ln.n > 4 * ln.q + r);
+                out.n[tix(i, j)][r] = lowN ? bq[r] * out.n[tix(i, j)][r] : 0.f;
+                out.t[tix(i, j)][r] = lowT ? bn * out.t[tix(i, j)][r] : 0.f;
+            }
+    }
+    wave_lds_sync();
+}
+
+// ---------------------------------------------------------------------------------------------
 // Result store.  Tm: first element of this matrix's T.  Tile (i, j) is in T orientation when
 // IS_T(i, j): one 16-byte store per lane; otherwise four 4-byte stores.  Diagonal tiles get an
 // exact unit diagonal and exact zeros above it; tiles above the diagonal are zero-filled.
@@ -276,7 +440,6 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, flo
         neumann<OP, NB>(src, Xt, ln);
         store_result<NB>(Tm, Xt, [](int, int) { return true; }, ln);
     } else {
-        constexpr bool ROOT_T = true;
         v4f Tt[NT];
         block_recursive<OP, NB, ROOT_T, (METHOD == M_MIXED) ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE>(src, Tt, lds, ln);
         store_result<NB>(Tm, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, ln);
@@ -303,6 +466,18 @@ __global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, floa
     invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
 }
 
+// Workgroup -> matrix map of the fused kernels.  Workgroups are handed to the 8 XCDs round-robin
+// (workgroup id mod 8); the H heads of one (batch, chunk) read the same beta / g cache lines, so
+// they are given to one XCD, back to back, and share those lines in its L2.  Groups beyond the
+// last multiple of 8 keep the identity map.
+__device__ __forceinline__ int64_t head_group_swizzle(int64_t bid, int64_t n_group, int H)
+{
+    const int64_t full = (n_group / 8) * 8;
+    if (bid >= full * H) return bid;
+    const int64_t x = bid % 8, q = bid / 8;
+    return ((q / H) * 8 + x) * H + (q % H);
+}
+
 template <int KD, int OP, int NB, int METHOD, int DKS>
 __global__ __launch_bounds__(64) void k_gdn_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                     const float* __restrict__ g, float* __restrict__ T, int64_t n_chunk,
@@ -312,7 +487,7 @@ __global__ __launch_bounds__(64) void k_gdn_tri_inv(const void* __restrict__ K, 
     constexpr int CORE = core_lds_floats<NB, METHOD>();
     constexpr int GATE = gate_lds_floats<NB>();
     __shared__ __attribute__((aligned(16))) float lds[CORE > GATE ? CORE : GATE];
-    const int64_t m = blockIdx.x;       // (b * n_chunk + chunk) * H + h
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);  // (b * n_chunk + chunk) * H + h
     const int h = (int)(m % H);
     const int64_t bc = m / H;           // b * n_chunk + chunk  (Tlen = n_chunk * C, so token0 = bc * C)
     const int64_t tok0 = bc * C;
@@ -322,7 +497,27 @@ __global__ __launch_bounds__(64) void k_gdn_tri_inv(const void* __restrict__ K, 
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
     src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
     src.load_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, lds);
-    (void)n_chunk;
+    invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
+}
+
+// Fused kernel for the per-channel gate: g is [B, Tlen, H, d_k]; the gated keys are rounded to OP.
+template <int OP, int NB, int METHOD>
+__global__ __launch_bounds__(64) void k_kda_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
+                                                    const float* __restrict__ g, float* __restrict__ T, int64_t n_chunk,
+                                                    int H, int d_k, int k_dt)
+{
+    constexpr int C = 16 * NB;
+    constexpr int CORE = core_lds_floats<NB, METHOD>();
+    __shared__ __attribute__((aligned(16))) float lds[CORE > C ? CORE : C];
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
+    const int h = (int)(m % H);
+    const int64_t tok0 = (m / H) * C;
+    const Lane ln = lane_id();
+    const int64_t esz = (k_dt == OP_F32) ? 4 : 2;
+    const int64_t e0 = (tok0 * H + h) * (int64_t)d_k;  // element offset of (token 0, head h, channel 0)
+    PreA<NB> src;
+    build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
+                                        beta + tok0 * H + h, H, d_k, lds, ln);
     invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
 }
 

@@ -20,6 +20,9 @@ MFMA_METHODS = [tri.BLOCK_RECURSIVE, tri.MIXED, tri.NEUMANN]
 ALL = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in MFMA_METHODS for o in (tri.F32, tri.F16, tri.BF16)]
 
 
+NEUMANN_C128_OFF = ("the one-wave Neumann kernel at C = 128 needs more than 512 registers; a run with the spilling build "
+                    "aborted on the GPU, so the path is switched off (the library reports 'combination not built')")
+
 def ids(mo):
     return f"{tri.METHOD_NAMES[mo[0]]}-{tri.DTYPE_NAMES[mo[1]]}"
 
@@ -38,7 +41,8 @@ def check(T_gpu: torch.Tensor, T_ref: np.ndarray, tol: float, what: str):
 def cases():
     """Small instances of every workload recipe: inputs, fp64 A, fp64 T."""
     out = {}
-    for idx, kw in [(0, {}), (1, dict(Tlen=1024)), (2, dict(B=2, Tlen=512, H=5)), (4, dict(Tlen=512, H=3))]:
+    for idx, kw in [(0, {}), (1, dict(Tlen=1024)), (2, dict(B=2, Tlen=512, H=5)), (3, dict(B=2, Tlen=512, H=3)),
+                    (4, dict(Tlen=512, H=3))]:
         inp = si.make_inputs(si.workload(idx, **kw))
         w = inp["workload"]
         A = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
@@ -52,8 +56,8 @@ def cases():
 def test_tri_inv_fp32_input(cases, idx, mo):
     method, op = mo
     c = cases[idx]
-    if c["w"].C == 128 and method == tri.NEUMANN:
-        pytest.skip("Neumann product at C = 128 is not built")
+    if idx == 4 and method == tri.NEUMANN:
+        pytest.skip("Neumann product on the stress input: reported, not asserted (see the last test)")
     A32 = torch.from_numpy(c["A"].astype(np.float32))
     T_ref = oracle.tri_inv(A32)                      # oracle on the values as stored
     T = tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op)
@@ -82,7 +86,7 @@ def test_tri_inv_16bit_input_short_form(cases, dt, method):
 def test_entries_on_and_above_the_diagonal_are_ignored(C, mo):
     method, op = mo
     if C == 128 and method == tri.NEUMANN:
-        pytest.skip("Neumann product at C = 128 is not built")
+        pytest.skip(NEUMANN_C128_OFF)
     n = 37  # ragged: not a multiple of anything
     dirty = si.random_strict_lower(n, C, 0.5 / np.sqrt(C), seed=3, garbage_upper=True)
     clean = si.random_strict_lower(n, C, 0.5 / np.sqrt(C), seed=3, garbage_upper=False)
@@ -132,13 +136,13 @@ def test_runs_on_the_callers_stream(cases):
 
 # ------------------------------------------------------------------ fused gdn_chunk_tri_inv
 @pytest.mark.parametrize("mo", ALL, ids=ids)
-@pytest.mark.parametrize("idx", [0, 1, 2, 4])
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
 def test_fused_matches_oracle(cases, idx, mo):
     method, op = mo
     c = cases[idx]
     w, inp = c["w"], c["inp"]
-    if w.C == 128 and method == tri.NEUMANN:
-        pytest.skip("Neumann product at C = 128 is not built")
+    if idx == 4 and method == tri.NEUMANN:
+        pytest.skip("Neumann product on the stress input: reported, not asserted (see the last test)")
     g = None if inp["g"] is None else inp["g"].to(DEV)
     T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, w.C, gate_kind=w.gate_kind,
                                  method=method, op_dtype=op)
@@ -176,6 +180,29 @@ def test_fused_gate_kinds_agree(cases):
     assert torch.equal(T0, Tz)
 
 
+def test_per_channel_gate_reduces_to_scalar_gate(cases):
+    # the same log-decay on every channel through the per-channel kernel == the scalar-gate kernel's matrix
+    c = cases[2]
+    w, inp = c["w"], c["inp"]
+    K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+    g4 = inp["g"][..., None].expand(-1, -1, -1, w.d_k).contiguous().to(DEV)
+    for method, op in [(tri.BLOCK_RECURSIVE, tri.F32), (tri.FWD_SUBST, tri.F32), (tri.NEUMANN, tri.F32), (tri.MIXED, tri.BF16)]:
+        T = tri.gdn_chunk_tri_inv_ex(K, beta, g4, w.C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
+        check(T, c["T"], TOL[op], f"per-channel == scalar {ids((method, op))}")
+
+
+def test_per_channel_gate_fp32_and_fp16_keys(cases):
+    c = cases[3]
+    w, inp = c["w"], c["inp"]
+    beta, g = inp["beta"].to(DEV), inp["g"].to(DEV)
+    for dt in (torch.float32, torch.float16):
+        Kd = inp["K"].to(dt)
+        ref = oracle.gdn_chunk_tri_inv(Kd, inp["beta"], inp["g"], w.gate_kind, w.C)
+        T = tri.gdn_chunk_tri_inv_ex(Kd.to(DEV), beta, g, w.C, gate_kind=tri.GATE_PER_CHANNEL,
+                                     method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32)
+        check(T, ref, 1e-5, f"per-channel gate, keys {dt}")
+
+
 def test_unbuilt_combinations_report_unsupported(cases):
     c = cases[1]
     w, inp = c["w"], c["inp"]
@@ -184,9 +211,11 @@ def test_unbuilt_combinations_report_unsupported(cases):
     with pytest.raises(tri.TriInvError) as e:
         tri.gdn_chunk_tri_inv_ex(K96, b, b, 64)
     assert e.value.status == -9
-    A = torch.zeros(2, 128, 128, device=DEV)
     with pytest.raises(tri.TriInvError) as e:
-        tri.tri_inv_ex(A, method=tri.NEUMANN, op_dtype=tri.F32)
+        tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32, flags=1)
+    assert e.value.status == -9
+    with pytest.raises(tri.TriInvError) as e:
+        tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.NEUMANN, op_dtype=tri.F32)
     assert e.value.status == -9
 
 
@@ -199,6 +228,8 @@ def _sample(n_mat, k=48, seed=0):
 @pytest.mark.parametrize("idx,mo", [(1, (tri.BLOCK_RECURSIVE, tri.BF16)), (1, (tri.FWD_SUBST, tri.F32)),
                                     (2, (tri.BLOCK_RECURSIVE, tri.BF16)), (2, (tri.BLOCK_RECURSIVE, tri.F32)),
                                     (2, (tri.MIXED, tri.F16)), (2, (tri.NEUMANN, tri.BF16)), (2, (tri.FWD_SUBST, tri.F32)),
+                                    (3, (tri.BLOCK_RECURSIVE, tri.BF16)), (3, (tri.BLOCK_RECURSIVE, tri.F32)),
+                                    (3, (tri.FWD_SUBST, tri.F32)),
                                     (4, (tri.BLOCK_RECURSIVE, tri.F32)), (4, (tri.BLOCK_RECURSIVE, tri.BF16)),
                                     (4, (tri.FWD_SUBST, tri.F32))],
                          ids=lambda v: ids(v) if isinstance(v, tuple) else f"cfg{v}")
@@ -241,3 +272,38 @@ def test_neumann_on_the_stress_input_is_reported_not_asserted(cases, capsys):
         check(Tb, T_ref, TOL[op], "blocked recursion on the same input")
     with capsys.disabled():
         print("\n" + "\n".join(lines))
+
+
+@pytest.mark.skip(reason=NEUMANN_C128_OFF)
+def test_neumann_c128_on_the_stress_input_is_reported(capsys):
+    lines = []
+    inp = si.make_inputs(si.workload(4, Tlen=512, H=3))
+    A = oracle.build_A(inp["K"], inp["beta"], None, si.GATE_NONE, 128)
+    T_ref = oracle.tri_inv(A)
+    A32 = torch.from_numpy(A.astype(np.float32)).to(DEV)
+    for op in (tri.F32, tri.F16, tri.BF16):
+        T = tri.tri_inv_ex(A32, method=tri.NEUMANN, op_dtype=op).cpu().numpy().astype(np.float64)
+        Tf = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), None, 128, gate_kind=tri.GATE_NONE,
+                                      method=tri.NEUMANN, op_dtype=op).cpu().numpy().astype(np.float64)
+        for tag, X in (("standalone", T), ("fused", Tf)):
+            e = metrics.forward_errors(T_ref, X)["rel_fro"]
+            lines.append(f"neumann {tri.DTYPE_NAMES[op]} on stress C=128 {tag}: rel_fro max {np.nanmax(e):.3e}, "
+                         f"non-finite matrices {int((~np.isfinite(e)).sum())}/{len(e)}")
+    with capsys.disabled():
+        print("\n" + "\n".join(lines))
+
+
+@pytest.mark.skip(reason=NEUMANN_C128_OFF)
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+def test_neumann_c128_on_benign_input(op):
+    """The C = 128 Neumann kernel itself is held to the tolerance where the algorithm is
+    accurate: small ||A|| (gated, strongly decayed keys)."""
+    A = si.random_strict_lower(9, 128, 0.02, seed=11, garbage_upper=True)
+    T = tri.tri_inv_ex(A.to(DEV), method=tri.NEUMANN, op_dtype=op)
+    check(T, oracle.tri_inv(A), TOL[op], f"neumann C=128 benign {tri.DTYPE_NAMES[op]}")
+    inp = si.make_inputs(si.workload(2, B=1, Tlen=256, H=3, C=128))
+    w = inp["workload"]
+    ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, 128)
+    Tf = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), 128, gate_kind=w.gate_kind,
+                                  method=tri.NEUMANN, op_dtype=op)
+    check(Tf, ref, TOL[op], f"neumann C=128 fused benign {tri.DTYPE_NAMES[op]}")
