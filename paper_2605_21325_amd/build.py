@@ -6,7 +6,9 @@ for every device compile.
 """
 from __future__ import annotations
 
+import json
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -15,10 +17,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtriinv.so")
+RESOURCES = os.path.join(HERE, "kernel_resources.json")  # registers / scratch / LDS of every kernel, from the compiler
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-pass-failed", "-Wno-unused-command-line-argument",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # keep MFMA results in ordinary VGPRs: the kernels post-process every accumulator with vector
+         # ALU code, and the accumulator-register form costs one copy instruction per register
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+         "-Rpass-analysis=kernel-resource-usage"]
 
 # slowest units first so the pool stays busy
 UNITS = [
@@ -34,14 +41,29 @@ def _sources_mtime() -> float:
     return max(os.path.getmtime(os.path.join(CSRC, f)) for f in os.listdir(CSRC))
 
 
-def _compile(unit) -> str:
+_REMARK = re.compile(r"remark:\s+(Function Name|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]|"
+                     r"VGPRs Spill|LDS Size \[bytes/block\]): (\S+)")
+
+
+def _parse_resources(stderr: str) -> dict:
+    out, cur = {}, None
+    for key, val in _REMARK.findall(stderr):
+        if key == "Function Name":
+            cur = out.setdefault(val, {})
+        elif cur is not None:
+            cur[{"VGPRs": "vgpr", "AGPRs": "agpr", "ScratchSize [bytes/lane]": "scratch", "Occupancy [waves/SIMD]": "occupancy",
+                 "VGPRs Spill": "vgpr_spill", "LDS Size [bytes/block]": "lds"}[key]] = int(val)
+    return out
+
+
+def _compile(unit):
     name, src, defs = unit
     out = os.path.join(OBJ, name + ".o")
     cmd = [HIPCC, *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", out]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {name}:\n{r.stderr[-4000:]}")
-    return out
+    return out, _parse_resources(r.stderr)
 
 
 def build(force: bool = False, jobs: int = 0) -> str:
@@ -50,7 +72,13 @@ def build(force: bool = False, jobs: int = 0) -> str:
     os.makedirs(OBJ, exist_ok=True)
     jobs = jobs or min(len(UNITS), os.cpu_count() or 4, 16)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, UNITS))
+        results = list(ex.map(_compile, UNITS))
+    objs = [o for o, _ in results]
+    resources = {}
+    for _, res in results:
+        resources.update(res)
+    with open(RESOURCES, "w") as f:
+        json.dump(dict(sorted(resources.items())), f, indent=0)
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr[-4000:]}")

@@ -16,9 +16,9 @@ namespace triinv {
 
 // Blocked recursion inside the leaf (paper Alg. 4 with b0 = 1, Lemma C.1): block sizes 1, 2, 4, 8.
 // The level b = 1 starts from X = I, so D_o A D_e only picks the entries A[i][i-1], i odd.
-// Each later level applies X <- X - [D_o A D_e restricted to the 2b-block diagonal]; the
-// restriction drops the entries the unrolled product creates outside the 2b x 2b blocks, which
-// the paper's next level discards when it re-selects diagonal blocks.
+// Each later level applies X <- X - D_o A_b D_e with A_b = A restricted to its 2b x 2b diagonal
+// blocks; the restriction drops the entries the unrolled product would create outside those
+// blocks, which the paper's next level discards when it re-selects diagonal blocks.
 template <int OP>
 __device__ __forceinline__ void leaf_block_recursive(v4f LN, v4f LT, v4f& XN, v4f& XT, Lane ln)
 {
@@ -31,27 +31,26 @@ __device__ __forceinline__ void leaf_block_recursive(v4f LN, v4f LT, v4f& XN, v4
     }
 #pragma unroll
     for (int lb = 1; lb < 4; ++lb) {  // block size b = 2^lb
-        v4f eN, oT;
-        bool keep[4];
+        bool ke[4], ko[4], ks[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int a = 4 * ln.q + r, b = ln.n;
             const bool same_b = (a >> lb) == (b >> lb);
             const bool even = ((a >> lb) & 1) == 0;
-            eN[r] = (same_b && even) ? XN[r] : 0.f;   // D_e        (N)
-            oT[r] = (same_b && !even) ? XT[r] : 0.f;  // D_o^T      (T)
-            keep[r] = (a >> (lb + 1)) == (b >> (lb + 1));
+            ke[r] = same_b && even;                        // D_e (the same predicate serves D_o^T: it is symmetric)
+            ko[r] = same_b && !even;                       // D_o
+            ks[r] = (a >> (lb + 1)) == (b >> (lb + 1));    // inside one 2b x 2b diagonal block
         }
-        const Opnd<OP> eNo = pack<OP>(eN), oTo = pack<OP>(oT);
-        const v4f P1 = tn<OP>(LTo, eNo, zero4());             // A D_e
-        const v4f P2 = tn<OP>(LNo, oTo, zero4());             // A^T D_o^T = (D_o A)^T
-        const v4f Q1 = tn<OP>(oTo, pack<OP>(P1), zero4());    // D_o A D_e
-        const v4f Q2 = tn<OP>(eNo, pack<OP>(P2), zero4());    // (D_o A D_e)^T
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            XN[r] -= keep[r] ? Q1[r] : 0.f;
-            XT[r] -= keep[r] ? Q2[r] : 0.f;
-        }
+        const Mask<OP> Me = make_mask<OP>(ke[0], ke[1], ke[2], ke[3]);
+        const Mask<OP> Mo = make_mask<OP>(ko[0], ko[1], ko[2], ko[3]);
+        const Mask<OP> Ms = make_mask<OP>(ks[0], ks[1], ks[2], ks[3]);
+        const Opnd<OP> eNo = masked<OP>(pack<OP>(XN), Me);     // D_e        (N)
+        const Opnd<OP> oTo = masked<OP>(pack<OP>(XT), Mo);     // D_o^T      (T)
+        // A restricted to the 2b-block diagonal: D_o A D_e then has no entry outside those blocks
+        const v4f P1 = tn<OP>(masked<OP>(LTo, Ms), eNo, zero4());   // A D_e
+        const v4f P2 = tn<OP>(masked<OP>(LNo, Ms), oTo, zero4());   // A^T D_o^T = (D_o A)^T
+        XN -= tn<OP>(oTo, pack<OP>(P1), zero4());                   // D_o A D_e
+        XT -= tn<OP>(eNo, pack<OP>(P2), zero4());                   // (D_o A D_e)^T
     }
 }
 

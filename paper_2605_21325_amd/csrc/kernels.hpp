@@ -210,17 +210,13 @@ template <> __device__ __forceinline__ GOp<OP_F32> gpack<OP_F32>(const float (&v
 }
 template <> __device__ __forceinline__ GOp<OP_F16> gpack<OP_F16>(const float (&v)[8])
 {
-    GOp<OP_F16> o;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) o.x[r] = (_Float16)v[r];
-    return o;
+    const v4u u = {pack2_f16(v[0], v[1]), pack2_f16(v[2], v[3]), pack2_f16(v[4], v[5]), pack2_f16(v[6], v[7])};
+    return {__builtin_bit_cast(v8h, u)};
 }
 template <> __device__ __forceinline__ GOp<OP_BF16> gpack<OP_BF16>(const float (&v)[8])
 {
-    GOp<OP_BF16> o;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) o.x[r] = (__bf16)v[r];
-    return o;
+    const v4u u = {pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]), pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7])};
+    return {__builtin_bit_cast(v8bf, u)};
 }
 
 template <int OPG> __device__ __forceinline__ v4f gstep(const GOp<OPG>& a, const GOp<OPG>& b, v4f acc);
@@ -239,23 +235,36 @@ template <> __device__ __forceinline__ v4f gstep<OP_BF16>(const GOp<OP_BF16>& a,
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.x, b.x, acc, 0, 0, 0);
 }
 
-// Eight consecutive key channels of one row, widened to fp32 (storage type chosen at run time).
-__device__ __forceinline__ void load_key8(const void* Kc, int kd, int64_t off, float (&v)[8])
+// Eight consecutive key channels of one row as stored (16-bit: one 16-byte load; fp32: two).
+template <bool K16> struct RawKey8;
+template <> struct RawKey8<true> { uint4 u; };
+template <> struct RawKey8<false> { v4f a, b; };
+
+template <bool K16> __device__ __forceinline__ RawKey8<K16> load_key8(const void* Kc, int64_t off)
 {
-    if (kd == OP_F32) {
-        const v4f a = *reinterpret_cast<const v4f*>(static_cast<const float*>(Kc) + off);
-        const v4f b = *reinterpret_cast<const v4f*>(static_cast<const float*>(Kc) + off + 4);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { v[r] = a[r]; v[4 + r] = b[r]; }
+    RawKey8<K16> o;
+    if constexpr (K16) {
+        o.u = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(Kc) + off);
     } else {
-        const uint4 u = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(Kc) + off);
-        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+        o.a = *reinterpret_cast<const v4f*>(static_cast<const float*>(Kc) + off);
+        o.b = *reinterpret_cast<const v4f*>(static_cast<const float*>(Kc) + off + 4);
+    }
+    return o;
+}
+
+template <bool K16> __device__ __forceinline__ void widen_key8(const RawKey8<K16>& k, bool is_f16, float (&v)[8])
+{
+    if constexpr (K16) {
+        const uint32_t w[4] = {k.u.x, k.u.y, k.u.z, k.u.w};
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const uint16_t lo = (uint16_t)(w[r] & 0xffff), hi = (uint16_t)(w[r] >> 16);
-            v[2 * r] = kd == OP_F16 ? f16_to_f32(lo) : bf16_to_f32(lo);
-            v[2 * r + 1] = kd == OP_F16 ? f16_to_f32(hi) : bf16_to_f32(hi);
+            v[2 * r] = is_f16 ? f16_to_f32(lo) : bf16_to_f32(lo);
+            v[2 * r + 1] = is_f16 ? f16_to_f32(hi) : bf16_to_f32(hi);
         }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { v[r] = k.a[r]; v[4 + r] = k.b[r]; }
     }
 }
 
@@ -264,13 +273,64 @@ __device__ __forceinline__ void load_key8(const void* Kc, int kd, int64_t off, f
 // a is row C/2 of the chunk's G, so both gated factors stay within exp(+-half the chunk's decay).
 // The gated keys are rounded to OPG and contracted on the matrix cores, 32 channels per step,
 // accumulating every tile the method needs; nothing but K, G, beta is read, nothing stored.
+// One iteration covers one whole 128-byte line of keys per row (64 channels of 16-bit keys, i.e.
+// two k-steps, or 32 channels of fp32 keys): all of a line's key loads are issued together, so
+// its second half is still cached when needed (requested one k-step apart, lines were found
+// evicted in between and fetched from HBM twice).
 // Kc / gc: element (chunk row 0, this head, channel 0); row_stride in elements (same for both).
+template <int OPG, int NB, int METHOD, bool K16>
+__device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void* Kc, bool is_f16, const float* gc,
+                                                      int64_t row_stride, int d_k, Lane ln)
+{
+    constexpr int C = 16 * NB;
+    constexpr float LOG2E = 1.44269504088896340736f;
+    constexpr int STEPS = (K16 && NB <= 4) ? 2 : 1;  // C = 128 has no registers to spare for the pairing
+    for (int s0 = 0; s0 < d_k / 32; s0 += STEPS) {
+        RawKey8<K16> raw[STEPS][NB];
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (s0 + t < d_k / 32) raw[t][i] = load_key8<K16>(Kc, (int64_t)(16 * i + ln.n) * row_stride + 32 * (s0 + t) + 8 * ln.q);
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            if (s0 + t >= d_k / 32) break;
+            const int ch = 32 * (s0 + t) + 8 * ln.q;
+            const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch);
+            const v4f a1 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch + 4);
+            GOp<OPG> pp[NB], pm[NB];
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + ch;
+                const v4f g0 = *reinterpret_cast<const v4f*>(gc + off);
+                const v4f g1 = *reinterpret_cast<const v4f*>(gc + off + 4);
+                float kv[8], up[8], dn[8];
+                widen_key8<K16>(raw[t][i], is_f16, kv);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const float d = ((r < 4) ? (g0[r] - a0[r]) : (g1[r - 4] - a1[r - 4])) * LOG2E;
+                    up[r] = kv[r] * __builtin_amdgcn_exp2f(d);
+                    dn[r] = kv[r] * __builtin_amdgcn_exp2f(-d);
+                }
+                pp[i] = gpack<OPG>(up);
+                pm[i] = gpack<OPG>(dn);
+            }
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+#pragma unroll
+                for (int j = 0; j <= i; ++j) {
+                    if (need_tile<NB, METHOD>(i, j, false)) out.n[tix(i, j)] = gstep<OPG>(pp[i], pm[j], out.n[tix(i, j)]);
+                    if (need_tile<NB, METHOD>(i, j, true)) out.t[tix(i, j)] = gstep<OPG>(pm[j], pp[i], out.t[tix(i, j)]);
+                }
+        }
+    }
+}
+
 template <int OPG, int NB, int METHOD>
 __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* Kc, int kd, const float* gc, int64_t row_stride,
                                                     const float* bc, int64_t tok_stride, int d_k, float* lds, Lane ln)
 {
     constexpr int C = 16 * NB;
-    constexpr float LOG2E = 1.44269504088896340736f;
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -278,36 +338,10 @@ __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* K
             out.n[tix(i, j)] = zero4();
             out.t[tix(i, j)] = zero4();
         }
-    for (int s = 0; s < d_k / 32; ++s) {
-        const int ch = 32 * s + 8 * ln.q;
-        const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch);
-        const v4f a1 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch + 4);
-        GOp<OPG> pp[NB], pm[NB];
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + ch;
-            float kv[8];
-            load_key8(Kc, kd, off, kv);
-            const v4f g0 = *reinterpret_cast<const v4f*>(gc + off);
-            const v4f g1 = *reinterpret_cast<const v4f*>(gc + off + 4);
-            float up[8], dn[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const float d = ((r < 4) ? (g0[r] - a0[r]) : (g1[r - 4] - a1[r - 4])) * LOG2E;
-                up[r] = kv[r] * __builtin_amdgcn_exp2f(d);
-                dn[r] = kv[r] * __builtin_amdgcn_exp2f(-d);
-            }
-            pp[i] = gpack<OPG>(up);
-            pm[i] = gpack<OPG>(dn);
-        }
-#pragma unroll
-        for (int i = 0; i < NB; ++i)
-#pragma unroll
-            for (int j = 0; j <= i; ++j) {
-                if (need_tile<NB, METHOD>(i, j, false)) out.n[tix(i, j)] = gstep<OPG>(pp[i], pm[j], out.n[tix(i, j)]);
-                if (need_tile<NB, METHOD>(i, j, true)) out.t[tix(i, j)] = gstep<OPG>(pm[j], pp[i], out.t[tix(i, j)]);
-            }
-    }
+    if (kd == OP_F32)
+        accumulate_gated_gram<OPG, NB, METHOD, false>(out, Kc, false, gc, row_stride, d_k, ln);
+    else
+        accumulate_gated_gram<OPG, NB, METHOD, true>(out, Kc, kd == OP_F16, gc, row_stride, d_k, ln);
     // beta_i row scaling and the strictly-lower mask
     const int l = 16 * ln.q + ln.n;
 #pragma unroll
@@ -330,24 +364,28 @@ __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* K
 }
 
 // ---------------------------------------------------------------------------------------------
-// Result store.  Tm: first element of this matrix's T.  Tile (i, j) is in T orientation when
-// IS_T(i, j): one 16-byte store per lane; otherwise four 4-byte stores.  Diagonal tiles get an
-// exact unit diagonal and exact zeros above it; tiles above the diagonal are zero-filled.
+// Result store.  Tm: first element of this matrix's T.  The register tiles (N or T orientation,
+// IS_T(i, j)) of one 16-row strip are transposed through a wave-private LDS patch into plain
+// rows, and the strip leaves as four 1 KB-contiguous non-temporal stores (16 B per lane): whole
+// cache lines written by one instruction stream to HBM markedly faster than the 64-byte pieces
+// a tile-shaped store produces.  Diagonal tiles get an exact unit diagonal and exact zeros above
+// it; columns right of the diagonal tile are zero-filled.
+// lds: STORE_LDS_FLOATS floats.
 // ---------------------------------------------------------------------------------------------
+constexpr int STORE_LD = 16 * 8 + 4;                  // row stride of the patch (fits C = 128), floats
+constexpr int STORE_LDS_FLOATS = 16 * STORE_LD;
+
 template <int NB, class IsT>
-__device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, Lane ln)
+__device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln)
 {
     constexpr int C = 16 * NB;
+    const int lane = 16 * ln.q + ln.n;
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
+    for (int i = 0; i < NB; ++i) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            if (j > i) {
-                *reinterpret_cast<v4f*>(Tm + (int64_t)(16 * i + ln.n) * C + 16 * j + 4 * ln.q) = zero4();
-                continue;
-            }
+        for (int j = 0; j <= i; ++j) {
             v4f v = Tt[tix(i, j)];
-            if (is_t(i, j)) {
+            if (is_t(i, j)) {  // v[r] = T[16i + n][16j + 4q + r]
                 if (i == j) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -355,17 +393,29 @@ __device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB
                         v[r] = (row == col) ? 1.f : ((row > col) ? v[r] : 0.f);
                     }
                 }
-                *reinterpret_cast<v4f*>(Tm + (int64_t)(16 * i + ln.n) * C + 16 * j + 4 * ln.q) = v;
-            } else {
+                *reinterpret_cast<v4f*>(&lds[ln.n * STORE_LD + 16 * j + 4 * ln.q]) = v;
+            } else {           // v[r] = T[16i + 4q + r][16j + n]
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int row = 4 * ln.q + r, col = ln.n;
                     float x = v[r];
                     if (i == j) x = (row == col) ? 1.f : ((row > col) ? x : 0.f);
-                    Tm[(int64_t)(16 * i + row) * C + 16 * j + col] = x;
+                    lds[row * STORE_LD + 16 * j + col] = x;
                 }
             }
         }
+        wave_lds_sync();
+        // rows 16i .. 16i+15, C floats each: C/4 lanes per row, 256/C rows per instruction
+        constexpr int LPR = C / 4, RPI = 64 / LPR;
+#pragma unroll
+        for (int k = 0; k < 16 / RPI; ++k) {
+            const int row = RPI * k + lane / LPR, col = 4 * (lane % LPR);
+            v4f v = zero4();
+            if (col < 16 * (i + 1)) v = *reinterpret_cast<const v4f*>(&lds[row * STORE_LD + col]);
+            __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(Tm + (int64_t)(16 * i + row) * C + col));
+        }
+        wave_lds_sync();
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -391,7 +441,7 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, f
         if (p > 0) {
             // rows above this pass's diagonal block: columns >= 64p are zero there
 #pragma unroll 8
-            for (int i = 0; i < 64 * p; ++i) Tm[(int64_t)i * C + c] = 0.f;
+            for (int i = 0; i < 64 * p; ++i) __builtin_nontemporal_store(0.f, Tm + (int64_t)i * C + c);
         }
         v4f stage[NB];  // tiles (s, 4p..s) of the strip being staged, T orientation = row-major pieces
         stage[4 * p] = A.template get<true>(4 * p, 4 * p);
@@ -418,7 +468,7 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, f
                 }
                 const float t = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
                 Tc[i - 64 * p] = t;
-                Tm[(int64_t)i * C + c] = t;
+                __builtin_nontemporal_store(t, Tm + (int64_t)i * C + c);
             }
         }
     }
@@ -438,17 +488,17 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, flo
     } else if (METHOD == M_NEUMANN) {
         v4f Xt[NT];
         neumann<OP, NB>(src, Xt, ln);
-        store_result<NB>(Tm, Xt, [](int, int) { return true; }, ln);
+        store_result<NB>(Tm, Xt, [](int, int) { return true; }, lds, ln);
     } else {
         v4f Tt[NT];
         block_recursive<OP, NB, ROOT_T, (METHOD == M_MIXED) ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE>(src, Tt, lds, ln);
-        store_result<NB>(Tm, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, ln);
+        store_result<NB>(Tm, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, lds, ln);
     }
 }
 
 template <int NB, int METHOD> constexpr int core_lds_floats()
 {
-    return METHOD == M_FWD ? fwd_lds_floats<NB>() : XPOSE_FLOATS;
+    return METHOD == M_FWD ? fwd_lds_floats<NB>() : (STORE_LDS_FLOATS > XPOSE_FLOATS ? STORE_LDS_FLOATS : XPOSE_FLOATS);
 }
 
 template <int OP, int NB, int METHOD>

@@ -21,6 +21,11 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef short v8s __attribute__((ext_vector_type(8)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 enum : int { OP_F32 = 0, OP_F16 = 1, OP_BF16 = 2 };
 
@@ -35,11 +40,16 @@ __device__ __forceinline__ Lane lane_id()
     return Lane{l >> 4, l & 15};
 }
 
-// fp32 -> bf16 bits, round to nearest even (NaN stays NaN).
-__device__ __forceinline__ short bf16_bits(float f)
+// Two fp32 -> two bf16 / fp16 in one register, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b)
 {
-    __bf16 b = (__bf16)f;
-    return __builtin_bit_cast(short, b);
+    const v2f f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));
+}
+__device__ __forceinline__ uint32_t pack2_f16(float a, float b)
+{
+    const v2f f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2h));
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b)
@@ -62,15 +72,42 @@ template <int OP> __device__ __forceinline__ Opnd<OP> pack(v4f t);
 template <> __device__ __forceinline__ Opnd<OP_F32> pack<OP_F32>(v4f t) { return {t}; }
 template <> __device__ __forceinline__ Opnd<OP_F16> pack<OP_F16>(v4f t)
 {
-    v4h h;
-    h[0] = (_Float16)t[0]; h[1] = (_Float16)t[1]; h[2] = (_Float16)t[2]; h[3] = (_Float16)t[3];
-    return {h};
+    const v2u u = {pack2_f16(t[0], t[1]), pack2_f16(t[2], t[3])};
+    return {__builtin_bit_cast(v4h, u)};
 }
 template <> __device__ __forceinline__ Opnd<OP_BF16> pack<OP_BF16>(v4f t)
 {
-    v4s s;
-    s[0] = bf16_bits(t[0]); s[1] = bf16_bits(t[1]); s[2] = bf16_bits(t[2]); s[3] = bf16_bits(t[3]);
-    return {s};
+    const v2u u = {pack2_bf16(t[0], t[1]), pack2_bf16(t[2], t[3])};
+    return {__builtin_bit_cast(v4s, u)};
+}
+
+// Element masks of one tile as bit patterns on the packed operand: keeping an element is an AND
+// with all ones, dropping it an AND with zero (which also kills NaN / Inf).
+template <int OP> struct Mask;
+template <> struct Mask<OP_F32> { v4u m; };
+template <> struct Mask<OP_F16> { v2u m; };
+template <> struct Mask<OP_BF16> { v2u m; };
+
+template <int OP> __device__ __forceinline__ Mask<OP> make_mask(bool k0, bool k1, bool k2, bool k3)
+{
+    Mask<OP> o;
+    if constexpr (OP == OP_F32) {
+        o.m = v4u{k0 ? ~0u : 0u, k1 ? ~0u : 0u, k2 ? ~0u : 0u, k3 ? ~0u : 0u};
+    } else {
+        o.m = v2u{(k0 ? 0xffffu : 0u) | (k1 ? 0xffff0000u : 0u), (k2 ? 0xffffu : 0u) | (k3 ? 0xffff0000u : 0u)};
+    }
+    return o;
+}
+
+template <int OP> __device__ __forceinline__ Opnd<OP> masked(Opnd<OP> x, Mask<OP> k)
+{
+    if constexpr (OP == OP_F32) {
+        return {__builtin_bit_cast(v4f, __builtin_bit_cast(v4u, x.x) & k.m)};
+    } else {
+        Opnd<OP> o;
+        o.x = __builtin_bit_cast(decltype(o.x), __builtin_bit_cast(v2u, x.x) & k.m);
+        return o;
+    }
 }
 
 // acc + X^T * Y   (x packed from X, y packed from Y)

@@ -125,3 +125,18 @@ def test_binding_refuses_host_tensors_and_missing_library(monkeypatch, L):
     monkeypatch.setattr(tri.binding, "LIB_PATH", "/nonexistent/libtriinv.so")
     with pytest.raises(FileNotFoundError):
         tri.lib()
+
+
+def test_no_kernel_spills_at_the_full_register_budget():
+    """A build whose Neumann kernel for C = 128 spilled registers while using all 512 of them
+    aborted on the GPU; such kernels must not be in the library (that path reports
+    'combination not built' instead)."""
+    import json
+
+    path = os.path.join(os.path.dirname(tri.binding.LIB_PATH), "kernel_resources.json")
+    if not os.path.exists(path):
+        pytest.skip("no compiler resource report beside the library")
+    res = json.load(open(path))
+    assert len(res) > 50
+    bad = [k for k, v in res.items() if v.get("vgpr_spill", 0) > 0 and v.get("vgpr", 0) + v.get("agpr", 0) >= 500]
+    assert not bad, bad
