@@ -40,8 +40,12 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 #else
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);
-#if TRIINV_INST_NB == 4  // the one-wave register version does not fit C = 128 without spilling; not built
-    case M_NEUMANN: return go_tri<M_NEUMANN>(a);
+    case M_NEUMANN:
+#if TRIINV_INST_NB == 4
+        return go_tri<M_NEUMANN>(a);
+#else   // C = 128: the one-wave register version would spill; a workgroup of four waves shares Y in LDS
+        hipLaunchKernelGGL((k_tri_inv_neumann128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
+        return 0;
 #endif
 #endif
     default: return 1;
@@ -65,8 +69,17 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 #else
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
+    case M_NEUMANN:
 #if TRIINV_INST_NB == 4
-    case M_NEUMANN: return go_gdn<KD, M_NEUMANN, DKS>(a);
+        return go_gdn<KD, M_NEUMANN, DKS>(a);
+#else
+        if constexpr (KD == OP_F32 && DKS == 8) {
+            return 1;  // 128 fp32 channels x 128 rows of keys per wave do not fit the register file
+        } else {
+            hipLaunchKernelGGL((k_gdn_tri_inv_neumann128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
+                               a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k);
+            return 0;
+        }
 #endif
 #endif
     default: return 1;

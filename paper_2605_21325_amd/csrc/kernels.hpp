@@ -375,46 +375,57 @@ __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* K
 constexpr int STORE_LD = 16 * 8 + 4;                  // row stride of the patch (fits C = 128), floats
 constexpr int STORE_LDS_FLOATS = 16 * STORE_LD;
 
-template <int NB, class IsT>
-__device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln)
+// One strip: tiles (i, 0..i) in row[0..i], tile j in T orientation when row_is_t(j).
+template <int NB, class RowIsT>
+__device__ __forceinline__ void store_strip(float* Tm, int i, const v4f (&row)[NB], RowIsT row_is_t, float* lds, Lane ln)
 {
     constexpr int C = 16 * NB;
     const int lane = 16 * ln.q + ln.n;
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-#pragma unroll
-        for (int j = 0; j <= i; ++j) {
-            v4f v = Tt[tix(i, j)];
-            if (is_t(i, j)) {  // v[r] = T[16i + n][16j + 4q + r]
-                if (i == j) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int row = ln.n, col = 4 * ln.q + r;
-                        v[r] = (row == col) ? 1.f : ((row > col) ? v[r] : 0.f);
-                    }
-                }
-                *reinterpret_cast<v4f*>(&lds[ln.n * STORE_LD + 16 * j + 4 * ln.q]) = v;
-            } else {           // v[r] = T[16i + 4q + r][16j + n]
+    for (int j = 0; j < NB; ++j) {
+        if (j > i) break;
+        v4f v = row[j];
+        if (row_is_t(j)) {  // v[r] = T[16i + n][16j + 4q + r]
+            if (i == j) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int row = 4 * ln.q + r, col = ln.n;
-                    float x = v[r];
-                    if (i == j) x = (row == col) ? 1.f : ((row > col) ? x : 0.f);
-                    lds[row * STORE_LD + 16 * j + col] = x;
+                    const int rr = ln.n, cc = 4 * ln.q + r;
+                    v[r] = (rr == cc) ? 1.f : ((rr > cc) ? v[r] : 0.f);
                 }
             }
-        }
-        wave_lds_sync();
-        // rows 16i .. 16i+15, C floats each: C/4 lanes per row, 256/C rows per instruction
-        constexpr int LPR = C / 4, RPI = 64 / LPR;
+            *reinterpret_cast<v4f*>(&lds[ln.n * STORE_LD + 16 * j + 4 * ln.q]) = v;
+        } else {            // v[r] = T[16i + 4q + r][16j + n]
 #pragma unroll
-        for (int k = 0; k < 16 / RPI; ++k) {
-            const int row = RPI * k + lane / LPR, col = 4 * (lane % LPR);
-            v4f v = zero4();
-            if (col < 16 * (i + 1)) v = *reinterpret_cast<const v4f*>(&lds[row * STORE_LD + col]);
-            __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(Tm + (int64_t)(16 * i + row) * C + col));
+            for (int r = 0; r < 4; ++r) {
+                const int rr = 4 * ln.q + r, cc = ln.n;
+                float x = v[r];
+                if (i == j) x = (rr == cc) ? 1.f : ((rr > cc) ? x : 0.f);
+                lds[rr * STORE_LD + 16 * j + cc] = x;
+            }
         }
-        wave_lds_sync();
+    }
+    wave_lds_sync();
+    // rows 16i .. 16i+15, C floats each: C/4 lanes per row, 256/C rows per instruction
+    constexpr int LPR = C / 4, RPI = 64 / LPR;
+#pragma unroll
+    for (int k = 0; k < 16 / RPI; ++k) {
+        const int rr = RPI * k + lane / LPR, cc = 4 * (lane % LPR);
+        v4f v = zero4();
+        if (cc < 16 * (i + 1)) v = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc]);
+        __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(Tm + (int64_t)(16 * i + rr) * C + cc));
+    }
+    wave_lds_sync();
+}
+
+template <int NB, class IsT>
+__device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln)
+{
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        v4f row[NB];
+#pragma unroll
+        for (int j = 0; j <= i; ++j) row[j] = Tt[tix(i, j)];
+        store_strip<NB>(Tm, i, row, [&](int j) { return is_t(i, j); }, lds, ln);
     }
 }
 
@@ -569,6 +580,183 @@ __global__ __launch_bounds__(64) void k_kda_tri_inv(const void* __restrict__ K, 
     build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
                                         beta + tok0 * H + h, H, d_k, lds, ln);
     invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Neumann product at C = 128: one workgroup of four wavefronts per matrix.
+// The running power Y = A^(2^k) lives in LDS as 36 fp32 tiles (16 x 20 floats each, N orientation);
+// a tile is read back in either orientation (four 4-byte reads, or one 16-byte read of the
+// transposed tile) and rounded to the operand type at every product, as in the one-wave kernel.
+// Wave w owns tile rows w and 7 - w of both Y and X^T; X^T stays in its registers.  Per iteration:
+// new Y tiles into registers -> barrier -> overwrite LDS -> barrier -> X^T += Y^T X^T.
+// ---------------------------------------------------------------------------------------------
+constexpr int N128_NB = 8;
+constexpr int N128_NT = 36;
+constexpr int N128_LDS_FLOATS = N128_NT * XPOSE_FLOATS;   // 46 080 bytes
+
+__device__ __forceinline__ v4f lds_tile_read_n(const float* t, Lane ln)
+{
+    v4f v;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = t[(4 * ln.q + r) * XPOSE_LD + ln.n];
+    return v;
+}
+__device__ __forceinline__ v4f lds_tile_read_t(const float* t, Lane ln)
+{
+    return *reinterpret_cast<const v4f*>(&t[ln.n * XPOSE_LD + 4 * ln.q]);
+}
+__device__ __forceinline__ void lds_tile_write_n(float* t, v4f v, Lane ln)
+{
+#pragma unroll
+    for (int r = 0; r < 4; ++r) t[(4 * ln.q + r) * XPOSE_LD + ln.n] = v[r];
+}
+
+// slot s of wave W: tile (i, j) with i = W for s <= W, else i = 7 - W
+template <int W> __host__ __device__ constexpr int n128_row(int s) { return s <= W ? W : 7 - W; }
+template <int W> __host__ __device__ constexpr int n128_col(int s) { return s <= W ? s : s - (W + 1); }
+
+template <int OP, int W, class ASrc>
+__device__ __forceinline__ void n128_init(const ASrc& A, v4f (&Xt)[9], float* Y, Lane ln)
+{
+#pragma unroll
+    for (int s = 0; s < 9; ++s) {
+        const int i = n128_row<W>(s), j = n128_col<W>(s);
+        lds_tile_write_n(Y + tix(i, j) * XPOSE_FLOATS, A.template get<false>(i, j), ln);
+        const v4f at = A.template get<true>(i, j);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Xt[s][r] = ((i == j && 4 * ln.q + r == ln.n) ? 1.f : 0.f) - at[r];
+    }
+}
+
+template <int OP, int W>
+__device__ __forceinline__ void n128_square(v4f (&Yn)[9], const float* Y, int p, Lane ln)
+{
+#pragma unroll
+    for (int s = 0; s < 9; ++s) {
+        const int i = n128_row<W>(s), j = n128_col<W>(s);
+        v4f acc = zero4();
+#pragma unroll
+        for (int k = 0; k < N128_NB; ++k) {
+            if (k < j || k > i) continue;
+            // structural zeros of A^p (tile (a, b) vanishes when 16 (a - b) + 15 < p); p is uniform
+            if (16 * (i - k) + 15 < p || 16 * (k - j) + 15 < p) continue;
+            const Opnd<OP> l = pack<OP>(lds_tile_read_t(Y + tix(i, k) * XPOSE_FLOATS, ln));
+            const Opnd<OP> r = pack<OP>(lds_tile_read_n(Y + tix(k, j) * XPOSE_FLOATS, ln));
+            acc = tn<OP>(l, r, acc);
+        }
+        Yn[s] = acc;
+    }
+}
+
+template <int W> __device__ __forceinline__ void n128_publish(const v4f (&Yn)[9], float* Y, Lane ln)
+{
+#pragma unroll
+    for (int s = 0; s < 9; ++s) lds_tile_write_n(Y + tix(n128_row<W>(s), n128_col<W>(s)) * XPOSE_FLOATS, Yn[s], ln);
+}
+
+template <int OP, int W>
+__device__ __forceinline__ void n128_update_x(v4f (&Xt)[9], const float* Y, int pn, Lane ln)
+{
+    // X^T(i,j) += sum_k Y(k,j)^T X(i,k)^T over this wave's two tile rows; the packed old row first
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int i = half == 0 ? W : 7 - W, s0 = half == 0 ? 0 : W + 1;
+        Opnd<OP> xo[N128_NB];
+#pragma unroll
+        for (int k = 0; k < N128_NB; ++k)
+            if (k <= i) xo[k] = pack<OP>(Xt[s0 + k]);
+#pragma unroll
+        for (int j = 0; j < N128_NB; ++j) {
+            if (j > i) continue;
+            v4f acc = Xt[s0 + j];
+#pragma unroll
+            for (int k = 0; k < N128_NB; ++k) {
+                if (k < j || k > i) continue;
+                if (16 * (k - j) + 15 < pn) continue;
+                acc = tn<OP>(pack<OP>(lds_tile_read_n(Y + tix(k, j) * XPOSE_FLOATS, ln)), xo[k], acc);
+            }
+            Xt[s0 + j] = acc;
+        }
+    }
+}
+
+template <int W>
+__device__ __forceinline__ void n128_store(float* Tm, const v4f (&Xt)[9], float* patch, Lane ln)
+{
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int i = half == 0 ? W : 7 - W, s0 = half == 0 ? 0 : W + 1;
+        v4f row[N128_NB];
+#pragma unroll
+        for (int j = 0; j < N128_NB; ++j)
+            if (j <= i) row[j] = Xt[s0 + j];
+        store_strip<N128_NB>(Tm, i, row, [](int) { return true; }, patch, ln);
+    }
+}
+
+#define TRIINV_PER_WAVE(w, CALL) \
+    switch (w) {                 \
+    case 0: { constexpr int W = 0; CALL; } break; \
+    case 1: { constexpr int W = 1; CALL; } break; \
+    case 2: { constexpr int W = 2; CALL; } break; \
+    default: { constexpr int W = 3; CALL; } break; \
+    }
+
+template <int OP, class ASrc>
+__device__ __forceinline__ void neumann_c128_workgroup(const ASrc& A, float* Tm, float* Y, Lane ln, int w)
+{
+    v4f Xt[9];
+    TRIINV_PER_WAVE(w, (n128_init<OP, W>(A, Xt, Y, ln)))
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < 6; ++it) {  // log2(128 / 2)
+        const int p = 1 << it, pn = 2 << it;
+        v4f Yn[9];
+        TRIINV_PER_WAVE(w, (n128_square<OP, W>(Yn, Y, p, ln)))
+        __syncthreads();
+        TRIINV_PER_WAVE(w, (n128_publish<W>(Yn, Y, ln)))
+        __syncthreads();
+        TRIINV_PER_WAVE(w, (n128_update_x<OP, W>(Xt, Y, pn, ln)))
+    }
+    __syncthreads();  // Y is dead: its memory becomes the four store patches
+    TRIINV_PER_WAVE(w, (n128_store<W>(Tm, Xt, Y + w * STORE_LDS_FLOATS, ln)))
+}
+
+template <int OP>
+__global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt)
+{
+    __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
+    const int64_t m = blockIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Lane ln = lane_id();
+    GlobalA<N128_NB> src;
+    src.base = static_cast<const char*>(A) + m * 128 * 128 * (in_dt == OP_F32 ? 4 : 2);
+    src.dt = in_dt;
+    src.ln = ln;
+    (void)n_mat;
+    neumann_c128_workgroup<OP>(src, T + m * 128 * 128, Y, ln, w);
+}
+
+template <int KD, int OP, int DKS>
+__global__ __launch_bounds__(256) void k_gdn_tri_inv_neumann128(const void* __restrict__ K, const float* __restrict__ beta,
+                                                                const float* __restrict__ g, float* __restrict__ T,
+                                                                int64_t n_chunk, int H, int d_k)
+{
+    constexpr int C = 128;
+    __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
+    const int h = (int)(m % H);
+    const int64_t tok0 = (m / H) * C;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Lane ln = lane_id();
+    GramA<KD, N128_NB, DKS> src;
+    src.ln = ln;
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
+    // every wave stages beta / g for itself: a private 2 * C floats inside the (not yet used) Y buffer
+    src.load_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, Y + w * 2 * C);
+    __syncthreads();
+    neumann_c128_workgroup<OP>(src, T + m * C * C, Y, ln, w);
 }
 
 }  // namespace triinv

@@ -20,9 +20,6 @@ MFMA_METHODS = [tri.BLOCK_RECURSIVE, tri.MIXED, tri.NEUMANN]
 ALL = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in MFMA_METHODS for o in (tri.F32, tri.F16, tri.BF16)]
 
 
-NEUMANN_C128_OFF = ("the one-wave Neumann kernel at C = 128 needs more than 512 registers; a run with the spilling build "
-                    "aborted on the GPU, so the path is switched off (the library reports 'combination not built')")
-
 def ids(mo):
     return f"{tri.METHOD_NAMES[mo[0]]}-{tri.DTYPE_NAMES[mo[1]]}"
 
@@ -85,8 +82,6 @@ def test_tri_inv_16bit_input_short_form(cases, dt, method):
                                 (tri.MIXED, tri.F16), (tri.NEUMANN, tri.F32)], ids=ids)
 def test_entries_on_and_above_the_diagonal_are_ignored(C, mo):
     method, op = mo
-    if C == 128 and method == tri.NEUMANN:
-        pytest.skip(NEUMANN_C128_OFF)
     n = 37  # ragged: not a multiple of anything
     dirty = si.random_strict_lower(n, C, 0.5 / np.sqrt(C), seed=3, garbage_upper=True)
     clean = si.random_strict_lower(n, C, 0.5 / np.sqrt(C), seed=3, garbage_upper=False)
@@ -214,8 +209,11 @@ def test_unbuilt_combinations_report_unsupported(cases):
     with pytest.raises(tri.TriInvError) as e:
         tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32, flags=1)
     assert e.value.status == -9
+    # per-channel gate + Neumann product at C = 128 is not built
+    K = torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV)
+    g4 = torch.zeros(1, 128, 2, 128, device=DEV)
     with pytest.raises(tri.TriInvError) as e:
-        tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.NEUMANN, op_dtype=tri.F32)
+        tri.gdn_chunk_tri_inv_ex(K, torch.zeros(1, 128, 2, device=DEV), g4, 128, gate_kind=tri.GATE_PER_CHANNEL, method=tri.NEUMANN)
     assert e.value.status == -9
 
 
@@ -274,7 +272,6 @@ def test_neumann_on_the_stress_input_is_reported_not_asserted(cases, capsys):
         print("\n" + "\n".join(lines))
 
 
-@pytest.mark.skip(reason=NEUMANN_C128_OFF)
 def test_neumann_c128_on_the_stress_input_is_reported(capsys):
     lines = []
     inp = si.make_inputs(si.workload(4, Tlen=512, H=3))
@@ -293,7 +290,6 @@ def test_neumann_c128_on_the_stress_input_is_reported(capsys):
         print("\n" + "\n".join(lines))
 
 
-@pytest.mark.skip(reason=NEUMANN_C128_OFF)
 @pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
 def test_neumann_c128_on_benign_input(op):
     """The C = 128 Neumann kernel itself is held to the tolerance where the algorithm is
