@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", type=int, default=2)
-    ap.add_argument("--method", type=int, default=1, help="0 fwd, 1 block recursive, 2 neumann, 3 mixed")
+    ap.add_argument("--method", type=int, default=1, help="0 fwd, 1 block recursive, 2 neumann, 3 mixed, 4 block direct")
     ap.add_argument("--op", type=int, default=2, help="operand type: 0 f32, 1 f16, 2 bf16")
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
@@ -202,7 +202,7 @@ def main() -> int:
                 S = S * torch.exp(gg[..., :, None] - gg[..., None, :])
             A32 = torch.tril(S, -1).reshape(n_mat, C, C).contiguous()
             del S, Kc
-        for method in (0, 1, 3, 2):
+        for method in (0, 1, 4, 3, 2):
             for op in (0, 1, 2):
                 if method == 0 and op != 0:
                     continue

@@ -48,7 +48,11 @@ typedef enum {
     TRIINV_NEUMANN = 2,
     /* Mixed recursion (paper Alg. 2, Sec. 3.4): Neumann product on the 16 x 16 diagonal blocks,
      * then the blocked recursion from block size 16.  Log-stable. */
-    TRIINV_MIXED = 3
+    TRIINV_MIXED = 3,
+    /* Blocked recursion started at block size 16 (paper Alg. 4 with b0 = 16) from 16 x 16 diagonal
+     * blocks inverted directly by forward substitution in fp32 (the stable direct method of
+     * Sec. 3.1); only the merges -T22 A21 T11 use op_dtype operands. */
+    TRIINV_BLOCK_DIRECT = 4
 } triinv_method;
 
 /* Gate kinds of the fused entry point. */

@@ -16,7 +16,7 @@ bool overlap(const void* a, uint64_t na, const void* b, uint64_t nb)
 }
 
 bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_BF16; }
-bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_MIXED; }
+bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_BLOCK_DIRECT; }
 uint64_t esize(int d) { return d == TRIINV_F32 ? 4 : 2; }
 
 int finish(int not_built)

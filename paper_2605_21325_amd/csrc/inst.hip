@@ -40,6 +40,7 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 #else
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);
+    case M_BLOCK_DIRECT: return go_tri<M_BLOCK_DIRECT>(a);
     case M_NEUMANN:
 #if TRIINV_INST_NB == 4
         return go_tri<M_NEUMANN>(a);
@@ -69,6 +70,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 #else
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
+    case M_BLOCK_DIRECT: return go_gdn<KD, M_BLOCK_DIRECT, DKS>(a);
     case M_NEUMANN:
 #if TRIINV_INST_NB == 4
         return go_gdn<KD, M_NEUMANN, DKS>(a);
@@ -101,6 +103,7 @@ static int kda_method(const GdnArgs& a)
 #else
     case M_BLOCK: return go_kda<M_BLOCK>(a);
     case M_MIXED: return go_kda<M_MIXED>(a);
+    case M_BLOCK_DIRECT: return go_kda<M_BLOCK_DIRECT>(a);
 #if TRIINV_INST_NB == 4
     case M_NEUMANN: return go_kda<M_NEUMANN>(a);
 #endif

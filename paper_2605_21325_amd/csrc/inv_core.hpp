@@ -78,6 +78,65 @@ __device__ __forceinline__ void leaf_neumann(v4f LN, v4f LT, v4f& XN, v4f& XT, L
 }
 
 // ---------------------------------------------------------------------------------------------
+// Leaves by forward substitution in fp32 vector arithmetic (the direct method of paper Sec. 3.1
+// as the start X0 of Alg. 4 at b0 = 16).  Four leaves at a time: lane group q solves leaf q, lane
+// n its column n; the leaf's rows are read back from LDS with one address per lane group (LDS
+// broadcast).  lds: LEAF_FWD_FLOATS floats, wave-private.
+// ---------------------------------------------------------------------------------------------
+constexpr int LEAF_LD = 20;                       // row stride inside a staged leaf
+constexpr int LEAF_STRIDE = 16 * LEAF_LD + 8;     // leaf stride: the four groups' rows fall into different banks
+constexpr int LEAF_FWD_FLOATS = 4 * LEAF_STRIDE;
+
+__device__ __forceinline__ void leaf_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int NB, class ASrc>
+__device__ __forceinline__ void leaves_forward_substitution(const ASrc& A, v4f (&leafN)[NB], v4f (&leafT)[NB], float* lds, Lane ln)
+{
+    constexpr int PER = NB < 4 ? NB : 4;
+#pragma unroll
+    for (int pass = 0; pass < (NB + 3) / 4; ++pass) {
+#pragma unroll
+        for (int d = 0; d < PER; ++d) {  // T orientation = row-major pieces: v[r] = A[16 leaf + n][16 leaf + 4q + r]
+            const v4f v = A.template get<true>(4 * pass + d, 4 * pass + d);
+            *reinterpret_cast<v4f*>(&lds[d * LEAF_STRIDE + ln.n * LEAF_LD + 4 * ln.q]) = v;
+        }
+        leaf_lds_sync();
+        const float* Al = lds + ln.q * LEAF_STRIDE;  // this lane group's leaf
+        const int c = ln.n;
+        float t[16];
+        t[0] = (c == 0) ? 1.f : 0.f;
+#pragma unroll
+        for (int i = 1; i < 16; ++i) {
+            float acc = 0.f;
+#pragma unroll
+            for (int j4 = 0; j4 < i; j4 += 4) {
+                const v4f a = *reinterpret_cast<const v4f*>(&Al[i * LEAF_LD + j4]);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (j4 + r < i) acc += a[r] * t[j4 + r];
+            }
+            t[i] = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
+        }
+        leaf_lds_sync();
+#pragma unroll
+        for (int i = 0; i < 16; ++i) lds[ln.q * LEAF_STRIDE + i * LEAF_LD + c] = t[i];
+        leaf_lds_sync();
+#pragma unroll
+        for (int d = 0; d < PER; ++d) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) leafN[4 * pass + d][r] = lds[d * LEAF_STRIDE + (4 * ln.q + r) * LEAF_LD + ln.n];
+            leafT[4 * pass + d] = *reinterpret_cast<const v4f*>(&lds[d * LEAF_STRIDE + ln.n * LEAF_LD + 4 * ln.q]);
+        }
+        leaf_lds_sync();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Tile transpose through a wave-private LDS patch of 16 x 20 floats.
 // ---------------------------------------------------------------------------------------------
 constexpr int XPOSE_LD = 20;
@@ -112,19 +171,23 @@ __host__ __device__ constexpr bool result_is_T(int i, int j)
     return (NB == 1) ? false : ((j >= NB / 2) ? true : ((i < NB / 2) ? false : ROOT_T));
 }
 
-enum : int { LEAF_BLOCK_RECURSIVE = 0, LEAF_NEUMANN = 1 };
+enum : int { LEAF_BLOCK_RECURSIVE = 0, LEAF_NEUMANN = 1, LEAF_FORWARD = 2 };
 
 template <int OP, int NB, bool ROOT_T, int LEAF, class ASrc>
 __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln)
 {
     v4f leafN[NB], leafT[NB];
+    if constexpr (LEAF == LEAF_FORWARD) {
+        leaves_forward_substitution<NB>(A, leafN, leafT, patch, ln);
+    } else {
 #pragma unroll
-    for (int d = 0; d < NB; ++d) {
-        const v4f LN = A.template get<false>(d, d), LT = A.template get<true>(d, d);
-        if (LEAF == LEAF_BLOCK_RECURSIVE)
-            leaf_block_recursive<OP>(LN, LT, leafN[d], leafT[d], ln);
-        else
-            leaf_neumann<OP>(LN, LT, leafN[d], leafT[d], ln);
+        for (int d = 0; d < NB; ++d) {
+            const v4f LN = A.template get<false>(d, d), LT = A.template get<true>(d, d);
+            if (LEAF == LEAF_BLOCK_RECURSIVE)
+                leaf_block_recursive<OP>(LN, LT, leafN[d], leafT[d], ln);
+            else
+                leaf_neumann<OP>(LN, LT, leafN[d], leafT[d], ln);
+        }
     }
 
 #pragma unroll

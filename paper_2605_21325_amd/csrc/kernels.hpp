@@ -8,7 +8,7 @@
 
 namespace triinv {
 
-enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3 };
+enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3, M_BLOCK_DIRECT = 4 };
 enum : int { G_SCALAR = 0, G_CHANNEL = 1, G_NONE = 2 };
 
 __device__ __forceinline__ void wave_lds_sync()
@@ -184,7 +184,7 @@ template <int NB, int METHOD> __host__ __device__ constexpr bool need_tile(int i
 {
     if (METHOD == M_FWD) return tr;
     if (METHOD == M_NEUMANN) return true;
-    if (i == j) return true;
+    if (i == j) return METHOD == M_BLOCK_DIRECT ? tr : true;
     return merge_block_is_T<NB>(i, j) ? !tr : tr;
 }
 
@@ -502,14 +502,16 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, flo
         store_result<NB>(Tm, Xt, [](int, int) { return true; }, lds, ln);
     } else {
         v4f Tt[NT];
-        block_recursive<OP, NB, ROOT_T, (METHOD == M_MIXED) ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE>(src, Tt, lds, ln);
+        constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : METHOD == M_BLOCK_DIRECT ? LEAF_FORWARD : LEAF_BLOCK_RECURSIVE;
+        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln);
         store_result<NB>(Tm, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, lds, ln);
     }
 }
 
 template <int NB, int METHOD> constexpr int core_lds_floats()
 {
-    return METHOD == M_FWD ? fwd_lds_floats<NB>() : (STORE_LDS_FLOATS > XPOSE_FLOATS ? STORE_LDS_FLOATS : XPOSE_FLOATS);
+    static_assert(STORE_LDS_FLOATS >= XPOSE_FLOATS && STORE_LDS_FLOATS >= LEAF_FWD_FLOATS, "the store patch is the largest user");
+    return METHOD == M_FWD ? fwd_lds_floats<NB>() : STORE_LDS_FLOATS;
 }
 
 template <int OP, int NB, int METHOD>

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
 TOL = {tri.F32: 1e-5, tri.F16: 2e-2, tri.BF16: 2e-2}
-MFMA_METHODS = [tri.BLOCK_RECURSIVE, tri.MIXED, tri.NEUMANN]
+MFMA_METHODS = [tri.BLOCK_RECURSIVE, tri.BLOCK_DIRECT, tri.MIXED, tri.NEUMANN]
 ALL = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in MFMA_METHODS for o in (tri.F32, tri.F16, tri.BF16)]
 
 
@@ -65,7 +65,7 @@ def test_tri_inv_fp32_input(cases, idx, mo):
 
 
 @pytest.mark.parametrize("dt", [torch.float16, torch.bfloat16])
-@pytest.mark.parametrize("method", [tri.FWD_SUBST, tri.BLOCK_RECURSIVE, tri.NEUMANN, tri.MIXED])
+@pytest.mark.parametrize("method", [tri.FWD_SUBST, tri.BLOCK_RECURSIVE, tri.NEUMANN, tri.MIXED, tri.BLOCK_DIRECT])
 def test_tri_inv_16bit_input_short_form(cases, dt, method):
     # short form: operands in the input's own type; the oracle widens the stored values exactly
     A = torch.from_numpy(cases[1]["A"].astype(np.float32)).to(dt)
@@ -79,7 +79,8 @@ def test_tri_inv_16bit_input_short_form(cases, dt, method):
 
 @pytest.mark.parametrize("C", [64, 128])
 @pytest.mark.parametrize("mo", [(tri.FWD_SUBST, tri.F32), (tri.BLOCK_RECURSIVE, tri.F32), (tri.BLOCK_RECURSIVE, tri.BF16),
-                                (tri.MIXED, tri.F16), (tri.NEUMANN, tri.F32)], ids=ids)
+                                (tri.MIXED, tri.F16), (tri.NEUMANN, tri.F32), (tri.BLOCK_DIRECT, tri.F32),
+                                (tri.BLOCK_DIRECT, tri.BF16)], ids=ids)
 def test_entries_on_and_above_the_diagonal_are_ignored(C, mo):
     method, op = mo
     n = 37  # ragged: not a multiple of anything
@@ -109,7 +110,8 @@ def test_non_finite_values_stay_in_their_matrix():
     A[2, 40, 3] = float("nan")
     A[3, 10, 9] = float("inf")
     ref = oracle.tri_inv(A)
-    for method, op in [(tri.FWD_SUBST, tri.F32), (tri.BLOCK_RECURSIVE, tri.BF16), (tri.NEUMANN, tri.F32)]:
+    for method, op in [(tri.FWD_SUBST, tri.F32), (tri.BLOCK_RECURSIVE, tri.BF16), (tri.NEUMANN, tri.F32),
+                       (tri.BLOCK_DIRECT, tri.F32)]:
         T = tri.tri_inv_ex(A.to(DEV), method=method, op_dtype=op).cpu().numpy()
         for m in (0, 1, 4):
             e = metrics.forward_errors(ref[m][None], T[m][None].astype(np.float64))["rel_fro"][0]
@@ -181,7 +183,8 @@ def test_per_channel_gate_reduces_to_scalar_gate(cases):
     w, inp = c["w"], c["inp"]
     K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
     g4 = inp["g"][..., None].expand(-1, -1, -1, w.d_k).contiguous().to(DEV)
-    for method, op in [(tri.BLOCK_RECURSIVE, tri.F32), (tri.FWD_SUBST, tri.F32), (tri.NEUMANN, tri.F32), (tri.MIXED, tri.BF16)]:
+    for method, op in [(tri.BLOCK_RECURSIVE, tri.F32), (tri.FWD_SUBST, tri.F32), (tri.NEUMANN, tri.F32), (tri.MIXED, tri.BF16),
+                       (tri.BLOCK_DIRECT, tri.F32)]:
         T = tri.gdn_chunk_tri_inv_ex(K, beta, g4, w.C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
         check(T, c["T"], TOL[op], f"per-channel == scalar {ids((method, op))}")
 
@@ -226,6 +229,8 @@ def _sample(n_mat, k=48, seed=0):
 @pytest.mark.parametrize("idx,mo", [(1, (tri.BLOCK_RECURSIVE, tri.BF16)), (1, (tri.FWD_SUBST, tri.F32)),
                                     (2, (tri.BLOCK_RECURSIVE, tri.BF16)), (2, (tri.BLOCK_RECURSIVE, tri.F32)),
                                     (2, (tri.MIXED, tri.F16)), (2, (tri.NEUMANN, tri.BF16)), (2, (tri.FWD_SUBST, tri.F32)),
+                                    (2, (tri.BLOCK_DIRECT, tri.F32)), (2, (tri.BLOCK_DIRECT, tri.BF16)),
+                                    (3, (tri.BLOCK_DIRECT, tri.F32)), (4, (tri.BLOCK_DIRECT, tri.F32)),
                                     (3, (tri.BLOCK_RECURSIVE, tri.BF16)), (3, (tri.BLOCK_RECURSIVE, tri.F32)),
                                     (3, (tri.FWD_SUBST, tri.F32)),
                                     (4, (tri.BLOCK_RECURSIVE, tri.F32)), (4, (tri.BLOCK_RECURSIVE, tri.BF16)),
