@@ -77,7 +77,9 @@ typedef enum {
 
 /* Bits of `flags` (0 = none). */
 #define TRIINV_FLAG_REFINE1 0x1u /* one iterative-refinement step X <- X + (I - X(I+A))X after the
-                                    method (paper Alg. 6, Eq. 9); matrix-product methods only */
+                                    method (paper Alg. 6, Eq. 9).  Built for TRIINV_BLOCK_RECURSIVE and
+                                    TRIINV_MIXED at C = 64 (tri_inv and the scalar / no-gate fused
+                                    kinds); anything else returns TRIINV_ERR_UNSUPPORTED */
 
 /*
  * tri_inv: invert n_mat precomputed matrices (paper Sec. 1 Eq. 3 with A given; App. D.1: the

@@ -41,13 +41,13 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     if (!aligned16(A) || !aligned16(T)) return TRIINV_ERR_ALIGN;
     const uint64_t n_el = (uint64_t)n_mat * C * C;
     if (overlap(A, n_el * esize(in_dtype), T, n_el * 4)) return TRIINV_ERR_ALIAS;
-    if (flags != 0) return TRIINV_ERR_UNSUPPORTED;
+    if (flags & ~TRIINV_FLAG_REFINE1) return TRIINV_ERR_UNSUPPORTED;
     if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
 
-    TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream)};
+    TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0};
     int nb = 1;
     if (method == TRIINV_FWD_SUBST) {
-        nb = C == 64 ? launch_tri_inv_nb4_op0_fwd(a) : launch_tri_inv_nb8_op0_fwd(a);
+        nb = a.refine ? 1 : C == 64 ? launch_tri_inv_nb4_op0_fwd(a) : launch_tri_inv_nb8_op0_fwd(a);
     } else if (C == 64) {
         nb = op_dtype == TRIINV_F32 ? launch_tri_inv_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb4_op1(a) : launch_tri_inv_nb4_op2(a);
     } else {
@@ -80,12 +80,15 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
     const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4;
     if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
-    if (flags != 0) return TRIINV_ERR_UNSUPPORTED;
+    if (flags & ~TRIINV_FLAG_REFINE1) return TRIINV_ERR_UNSUPPORTED;
     if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
 
-    GdnArgs a{K, beta, need_g ? g : nullptr, T, n_mat, n_chunk, H, d_k, k_dtype, gate_kind, method, static_cast<hipStream_t>(hip_stream)};
+    GdnArgs a{K, beta, need_g ? g : nullptr, T, n_mat, n_chunk, H, d_k, k_dtype, gate_kind, method, static_cast<hipStream_t>(hip_stream),
+              (flags & TRIINV_FLAG_REFINE1) != 0};
     int nb = 1;
-    if (method == TRIINV_FWD_SUBST) {
+    if (method == TRIINV_FWD_SUBST && a.refine) {
+        nb = 1;
+    } else if (method == TRIINV_FWD_SUBST) {
         if (C == 64)
             nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1_fwd(a) : launch_gdn_nb4_op2_fwd(a);
         else

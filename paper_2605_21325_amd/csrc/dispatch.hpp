@@ -13,6 +13,7 @@ struct TriInvArgs {
     int in_dt;
     int method;
     hipStream_t stream;
+    bool refine;  // one iterative-refinement step after the method
 };
 
 struct GdnArgs {
@@ -28,6 +29,7 @@ struct GdnArgs {
     int gate;
     int method;
     hipStream_t stream;
+    bool refine;
 };
 
 // Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.

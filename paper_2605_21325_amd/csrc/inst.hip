@@ -25,15 +25,26 @@ namespace triinv {
 constexpr int NB = TRIINV_INST_NB;
 constexpr int OP = TRIINV_INST_OP;
 
-template <int METHOD> static int go_tri(const TriInvArgs& a)
+template <int METHOD, bool REFINE = false> static int go_tri(const TriInvArgs& a)
 {
-    hipLaunchKernelGGL((k_tri_inv<OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
+    hipLaunchKernelGGL((k_tri_inv<OP, NB, METHOD, REFINE>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat,
+                       a.in_dt);
     return 0;
 }
+
+// The refinement step is built for the blocked and the mixed recursion at C = 64.
+constexpr bool HAS_REFINE = (TRIINV_INST_NB == 4) && !TRIINV_INST_FWD;
 
 #if !(TRIINV_INST_FWD && TRIINV_INST_OP != 0)
 int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const TriInvArgs& a)
 {
+    if (a.refine) {
+        if constexpr (HAS_REFINE) {
+            if (a.method == M_BLOCK) return go_tri<M_BLOCK, true>(a);
+            if (a.method == M_MIXED) return go_tri<M_MIXED, true>(a);
+        }
+        return 1;
+    }
     switch (a.method) {
 #if TRIINV_INST_FWD
     case M_FWD: return go_tri<M_FWD>(a);
@@ -55,15 +66,22 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 
 #endif
 
-template <int KD, int METHOD, int DKS> static int go_gdn(const GdnArgs& a)
+template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
-    hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
-                       a.g, a.T, a.n_chunk, a.H, a.d_k);
+    hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K,
+                       a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k);
     return 0;
 }
 
 template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 {
+    if (a.refine) {
+        if constexpr (HAS_REFINE) {
+            if (a.method == M_BLOCK) return go_gdn<KD, M_BLOCK, DKS, true>(a);
+            if (a.method == M_MIXED) return go_gdn<KD, M_MIXED, DKS, true>(a);
+        }
+        return 1;
+    }
     switch (a.method) {
 #if TRIINV_INST_FWD
     case M_FWD: return go_gdn<KD, M_FWD, DKS>(a);
@@ -97,6 +115,7 @@ template <int METHOD> static int go_kda(const GdnArgs& a)
 
 static int kda_method(const GdnArgs& a)
 {
+    if (a.refine) return 1;
     switch (a.method) {
 #if TRIINV_INST_FWD
     case M_FWD: return go_kda<M_FWD>(a);

@@ -343,4 +343,57 @@ __device__ __forceinline__ void neumann(const ASrc& A, v4f (&Xt)[NB * (NB + 1) /
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// One step of iterative refinement (paper Alg. 6, Eq. 9, for the matrix I + A):
+//   R <- I - Y (I + A);   X <- Y + R Y.
+// Y comes in as the tiles Tt in the orientations is_t() reports; each tile is brought to both
+// orientations (transpose through the LDS patch), then
+//   R^T(i,j) = [i==j] I - Y^T(i,j) - sum_k A(k,j)^T Y(i,k)^T,     X^T(i,j) = Y^T(i,j) + sum_k Y(k,j)^T R(i,k)^T.
+// Result: X in Tt, every tile in T orientation.  Operands are rounded to OP at each product; R and
+// all sums stay fp32.
+// ---------------------------------------------------------------------------------------------
+template <int OP, int NB, class ASrc, class IsT>
+__device__ __forceinline__ void refine_once(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* patch, Lane ln)
+{
+    constexpr int NT = NB * (NB + 1) / 2;
+    v4f Yt[NT];
+    Opnd<OP> Yn[NT], Yto[NT];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            const v4f other = transpose_tile(Tt[tix(i, j)], patch, ln);
+            const v4f n = is_t(i, j) ? other : Tt[tix(i, j)];
+            Yt[tix(i, j)] = is_t(i, j) ? Tt[tix(i, j)] : other;
+            Yn[tix(i, j)] = pack<OP>(n);
+            Yto[tix(i, j)] = pack<OP>(Yt[tix(i, j)]);
+        }
+    Opnd<OP> An[NT], Rt[NT];
+#pragma unroll
+    for (int k = 0; k < NB; ++k)
+#pragma unroll
+        for (int j = 0; j <= k; ++j) An[tix(k, j)] = pack<OP>(A.template get<false>(k, j));
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            v4f acc = zero4();
+#pragma unroll
+            for (int k = j; k <= i; ++k) acc = tn<OP>(An[tix(k, j)], Yto[tix(i, k)], acc);
+            v4f r;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = ((i == j && 4 * ln.q + e == ln.n) ? 1.f : 0.f) - Yt[tix(i, j)][e] - acc[e];
+            Rt[tix(i, j)] = pack<OP>(r);
+        }
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            v4f acc = Yt[tix(i, j)];
+#pragma unroll
+            for (int k = j; k <= i; ++k) acc = tn<OP>(Yn[tix(k, j)], Rt[tix(i, k)], acc);
+            Tt[tix(i, j)] = acc;
+        }
+}
+
 }  // namespace triinv

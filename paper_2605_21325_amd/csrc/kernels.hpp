@@ -490,7 +490,8 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, f
 // ---------------------------------------------------------------------------------------------
 template <int NB> constexpr int gate_lds_floats() { return 2 * 16 * NB; }
 
-template <int OP, int NB, int METHOD, class ASrc>
+// REFINE: one iterative-refinement step after a matrix-product method (C = 64 only).
+template <int OP, int NB, int METHOD, class ASrc, bool REFINE = false>
 __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, float* lds, Lane ln)
 {
     constexpr int NT = NB * (NB + 1) / 2;
@@ -504,7 +505,12 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, flo
         v4f Tt[NT];
         constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : METHOD == M_BLOCK_DIRECT ? LEAF_FORWARD : LEAF_BLOCK_RECURSIVE;
         block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln);
-        store_result<NB>(Tm, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, lds, ln);
+        if constexpr (REFINE) {
+            refine_once<OP, NB>(src, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, lds, ln);
+            store_result<NB>(Tm, Tt, [](int, int) { return true; }, lds, ln);
+        } else {
+            store_result<NB>(Tm, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, lds, ln);
+        }
     }
 }
 
@@ -514,7 +520,7 @@ template <int NB, int METHOD> constexpr int core_lds_floats()
     return METHOD == M_FWD ? fwd_lds_floats<NB>() : STORE_LDS_FLOATS;
 }
 
-template <int OP, int NB, int METHOD>
+template <int OP, int NB, int METHOD, bool REFINE = false>
 __global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt)
 {
     constexpr int C = 16 * NB;
@@ -526,7 +532,7 @@ __global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, floa
     src.base = static_cast<const char*>(A) + m * C * C * (in_dt == OP_F32 ? 4 : 2);
     src.dt = in_dt;
     src.ln = ln;
-    invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
+    invert_and_store<OP, NB, METHOD, GlobalA<NB>, REFINE>(src, T + m * C * C, lds, ln);
 }
 
 // Workgroup -> matrix map of the fused kernels.  Workgroups are handed to the 8 XCDs round-robin
@@ -541,7 +547,7 @@ __device__ __forceinline__ int64_t head_group_swizzle(int64_t bid, int64_t n_gro
     return ((q / H) * 8 + x) * H + (q % H);
 }
 
-template <int KD, int OP, int NB, int METHOD, int DKS>
+template <int KD, int OP, int NB, int METHOD, int DKS, bool REFINE = false>
 __global__ __launch_bounds__(64) void k_gdn_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                     const float* __restrict__ g, float* __restrict__ T, int64_t n_chunk,
                                                     int H, int d_k)
@@ -560,7 +566,7 @@ __global__ __launch_bounds__(64) void k_gdn_tri_inv(const void* __restrict__ K, 
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
     src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
     src.load_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, lds);
-    invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
+    invert_and_store<OP, NB, METHOD, GramA<KD, NB, DKS>, REFINE>(src, T + m * C * C, lds, ln);
 }
 
 // Fused kernel for the per-channel gate: g is [B, Tlen, H, d_k]; the gated keys are rounded to OP.

@@ -201,6 +201,38 @@ def test_per_channel_gate_fp32_and_fp16_keys(cases):
         check(T, ref, 1e-5, f"per-channel gate, keys {dt}")
 
 
+def test_refinement_step_recovers_digits(cases):
+    """One step of iterative refinement (Alg. 6) after the mixed / blocked recursion.  The residual is
+    formed with operands rounded to op_dtype like every other product, so the step cannot go below
+    that rounding floor: on benign inputs it must stay within the tolerance and within 2.5x of the
+    unrefined error; where the unrefined error is far above the floor (the stress recipe, next test)
+    it must reduce it (paper Sec. 4.1: it brings the mixed recursion back on par)."""
+    for idx in (1, 2):
+        c = cases[idx]
+        w, inp = c["w"], c["inp"]
+        A32 = torch.from_numpy(c["A"].astype(np.float32))
+        T_ref = oracle.tri_inv(A32)
+        K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+        for method in (tri.MIXED, tri.BLOCK_RECURSIVE):
+            for op in (tri.F32, tri.F16, tri.BF16):
+                e0 = check(tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op), T_ref, TOL[op], "unrefined")
+                e1 = check(tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op, flags=1), T_ref, TOL[op], "refined")
+                f1 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=w.gate_kind, method=method, op_dtype=op, flags=1),
+                           c["T"], TOL[op], "refined, fused")
+                assert e1 <= 2.5 * e0 + 1e-7 and f1 <= 2.5 * e0 + 1e-7, (idx, method, op, e0, e1, f1)
+
+
+def test_refinement_on_the_stress_blocks():
+    # C = 64 blocks of the stress recipe: mixed recursion with bf16 operands, before and after one step
+    inp = si.make_inputs(si.workload(4, Tlen=512, H=3, C=64))
+    A = oracle.build_A(inp["K"], inp["beta"], None, si.GATE_NONE, 64)
+    T_ref = oracle.tri_inv(A)
+    A32 = torch.from_numpy(A.astype(np.float32)).to(DEV)
+    e0 = check(tri.tri_inv_ex(A32, method=tri.MIXED, op_dtype=tri.BF16), T_ref, 4e-2, "mixed bf16 stress C=64")
+    e1 = check(tri.tri_inv_ex(A32, method=tri.MIXED, op_dtype=tri.BF16, flags=1), T_ref, 2e-2, "mixed bf16 stress C=64 refined")
+    assert e1 < e0
+
+
 def test_unbuilt_combinations_report_unsupported(cases):
     c = cases[1]
     w, inp = c["w"], c["inp"]
@@ -209,8 +241,12 @@ def test_unbuilt_combinations_report_unsupported(cases):
     with pytest.raises(tri.TriInvError) as e:
         tri.gdn_chunk_tri_inv_ex(K96, b, b, 64)
     assert e.value.status == -9
-    with pytest.raises(tri.TriInvError) as e:
-        tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32, flags=1)
+    for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=2), dict(method=tri.FWD_SUBST, flags=1), dict(method=tri.NEUMANN, flags=1)):
+        with pytest.raises(tri.TriInvError) as e:
+            tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), op_dtype=tri.F32, **kw)
+        assert e.value.status == -9
+    with pytest.raises(tri.TriInvError) as e:   # refinement is not built at C = 128
+        tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.MIXED, op_dtype=tri.F32, flags=1)
     assert e.value.status == -9
     # per-channel gate + Neumann product at C = 128 is not built
     K = torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV)
