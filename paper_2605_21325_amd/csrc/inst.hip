@@ -32,6 +32,9 @@ template <int METHOD, bool REFINE = false> static int go_tri(const TriInvArgs& a
     return 0;
 }
 
+// Fused matrix-core kernels at C = 64 run four matrices (adjacent heads) per workgroup.
+constexpr int WPB = (TRIINV_INST_NB == 4 && !TRIINV_INST_FWD) ? 4 : 1;
+
 // The refinement step is built for the blocked and the mixed recursion at C = 64.
 constexpr bool HAS_REFINE = (TRIINV_INST_NB == 4) && !TRIINV_INST_FWD;
 
@@ -68,8 +71,8 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
-    hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K,
-                       a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k);
+    hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
+                       dim3(64 * WPB), 0, a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k);
     return 0;
 }
 
@@ -108,8 +111,8 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 
 template <int METHOD> static int go_kda(const GdnArgs& a)
 {
-    hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta, a.g, a.T,
-                       a.n_chunk, a.H, a.d_k, a.k_dt);
+    hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
+                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k, a.k_dt);
     return 0;
 }
 
