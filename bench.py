@@ -237,9 +237,11 @@ def main() -> int:
                 S = S * torch.exp(gg[..., :, None] - gg[..., None, :])
             A32 = torch.tril(S, -1).reshape(n_mat, C, C).contiguous()
             del S, Kc
-        for method in (0, 1, 4, 3, 2):
+        for method in (0, 1, 4, 3, 2, 5):
             for op in (0, 1, 2):
                 if method == 0 and op != 0:
+                    continue
+                if method == 5 and C != 64:
                     continue
                 row = {"method": tri.METHOD_NAMES[method], "op": tri.DTYPE_NAMES[op]}
                 try:

@@ -52,7 +52,11 @@ typedef enum {
     /* Blocked recursion started at block size 16 (paper Alg. 4 with b0 = 16) from 16 x 16 diagonal
      * blocks inverted directly by forward substitution in fp32 (the stable direct method of
      * Sec. 3.1); only the merges -T22 A21 T11 use op_dtype operands. */
-    TRIINV_BLOCK_DIRECT = 4
+    TRIINV_BLOCK_DIRECT = 4,
+    /* Newton-Schulz iteration (paper Alg. 3, Eq. 8): X <- I / C, then n times Y <- (I + A) X,
+     * X <- 2X - XY.  n = TRIINV_FLAG_ITERS(n) in flags, default 12 (the count the paper finds
+     * sufficient at C = 64).  Built for C = 64. */
+    TRIINV_NEWTON_SCHULZ = 5
 } triinv_method;
 
 /* Gate kinds of the fused entry point. */
@@ -80,6 +84,8 @@ typedef enum {
                                     method (paper Alg. 6, Eq. 9).  Built for TRIINV_BLOCK_RECURSIVE and
                                     TRIINV_MIXED at C = 64 (tri_inv and the scalar / no-gate fused
                                     kinds); anything else returns TRIINV_ERR_UNSUPPORTED */
+
+#define TRIINV_FLAG_ITERS(n) (((uint32_t)(n) & 0xffu) << 8) /* iteration count of TRIINV_NEWTON_SCHULZ (0 = default) */
 
 /*
  * tri_inv: invert n_mat precomputed matrices (paper Sec. 1 Eq. 3 with A given; App. D.1: the

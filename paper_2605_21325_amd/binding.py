@@ -18,12 +18,19 @@ LIB_PATH = os.path.join(HERE, "libtriinv.so")
 
 # enums of include/triinv.h
 F32, F16, BF16 = 0, 1, 2
-FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED, BLOCK_DIRECT = 0, 1, 2, 3, 4
+FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED, BLOCK_DIRECT, NEWTON_SCHULZ = 0, 1, 2, 3, 4, 5
+FLAG_REFINE1 = 0x1
+
+
+def flag_iters(n: int) -> int:
+    """flags bits carrying the Newton-Schulz iteration count."""
+    return (int(n) & 0xFF) << 8
+
 GATE_SCALAR, GATE_PER_CHANNEL, GATE_NONE = 0, 1, 2
 OK = 0
 
 METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUMANN: "neumann", MIXED: "mixed",
-                BLOCK_DIRECT: "block_direct"}
+                BLOCK_DIRECT: "block_direct", NEWTON_SCHULZ: "newton_schulz"}
 DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
 
 EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "triinv_status_string", "triinv_version")

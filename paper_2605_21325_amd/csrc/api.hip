@@ -16,7 +16,15 @@ bool overlap(const void* a, uint64_t na, const void* b, uint64_t nb)
 }
 
 bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_BF16; }
-bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_BLOCK_DIRECT; }
+bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_NEWTON_SCHULZ; }
+
+constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | 0xff00u;
+
+int ns_iterations(uint32_t flags, int C)
+{
+    const int n = (int)((flags >> 8) & 0xffu);
+    return n ? n : (C == 64 ? 12 : 14);
+}
 uint64_t esize(int d) { return d == TRIINV_F32 ? 4 : 2; }
 
 int finish(int not_built)
@@ -41,10 +49,11 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     if (!aligned16(A) || !aligned16(T)) return TRIINV_ERR_ALIGN;
     const uint64_t n_el = (uint64_t)n_mat * C * C;
     if (overlap(A, n_el * esize(in_dtype), T, n_el * 4)) return TRIINV_ERR_ALIAS;
-    if (flags & ~TRIINV_FLAG_REFINE1) return TRIINV_ERR_UNSUPPORTED;
+    if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
     if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
 
-    TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0};
+    TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0,
+                 ns_iterations(flags, C)};
     int nb = 1;
     if (method == TRIINV_FWD_SUBST) {
         nb = a.refine ? 1 : C == 64 ? launch_tri_inv_nb4_op0_fwd(a) : launch_tri_inv_nb8_op0_fwd(a);
@@ -80,11 +89,11 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
     const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4;
     if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
-    if (flags & ~TRIINV_FLAG_REFINE1) return TRIINV_ERR_UNSUPPORTED;
+    if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
     if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
 
     GdnArgs a{K, beta, need_g ? g : nullptr, T, n_mat, n_chunk, H, d_k, k_dtype, gate_kind, method, static_cast<hipStream_t>(hip_stream),
-              (flags & TRIINV_FLAG_REFINE1) != 0};
+              (flags & TRIINV_FLAG_REFINE1) != 0, ns_iterations(flags, C)};
     int nb = 1;
     if (method == TRIINV_FWD_SUBST && a.refine) {
         nb = 1;

@@ -14,6 +14,7 @@ struct TriInvArgs {
     int method;
     hipStream_t stream;
     bool refine;  // one iterative-refinement step after the method
+    int iters;    // Newton-Schulz iteration count
 };
 
 struct GdnArgs {
@@ -30,6 +31,7 @@ struct GdnArgs {
     int method;
     hipStream_t stream;
     bool refine;
+    int iters;
 };
 
 // Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.

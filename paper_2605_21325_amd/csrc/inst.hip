@@ -28,7 +28,7 @@ constexpr int OP = TRIINV_INST_OP;
 template <int METHOD, bool REFINE = false> static int go_tri(const TriInvArgs& a)
 {
     hipLaunchKernelGGL((k_tri_inv<OP, NB, METHOD, REFINE>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat,
-                       a.in_dt);
+                       a.in_dt, a.iters);
     return 0;
 }
 
@@ -55,6 +55,9 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);
     case M_BLOCK_DIRECT: return go_tri<M_BLOCK_DIRECT>(a);
+#if TRIINV_INST_NB == 4  // X in both orientations does not fit one wave's registers at C = 128
+    case M_NEWTON_SCHULZ: return go_tri<M_NEWTON_SCHULZ>(a);
+#endif
     case M_NEUMANN:
 #if TRIINV_INST_NB == 4
         return go_tri<M_NEUMANN>(a);
@@ -72,7 +75,7 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
-                       dim3(64 * WPB), 0, a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k);
+                       dim3(64 * WPB), 0, a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k, a.iters);
     return 0;
 }
 
@@ -92,6 +95,9 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
     case M_BLOCK_DIRECT: return go_gdn<KD, M_BLOCK_DIRECT, DKS>(a);
+#if TRIINV_INST_NB == 4
+    case M_NEWTON_SCHULZ: return go_gdn<KD, M_NEWTON_SCHULZ, DKS>(a);
+#endif
     case M_NEUMANN:
 #if TRIINV_INST_NB == 4
         return go_gdn<KD, M_NEUMANN, DKS>(a);
@@ -112,7 +118,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 template <int METHOD> static int go_kda(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
-                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k, a.k_dt);
+                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k, a.k_dt, a.iters);
     return 0;
 }
 
@@ -126,6 +132,9 @@ static int kda_method(const GdnArgs& a)
     case M_BLOCK: return go_kda<M_BLOCK>(a);
     case M_MIXED: return go_kda<M_MIXED>(a);
     case M_BLOCK_DIRECT: return go_kda<M_BLOCK_DIRECT>(a);
+#if TRIINV_INST_NB == 4
+    case M_NEWTON_SCHULZ: return go_kda<M_NEWTON_SCHULZ>(a);
+#endif
 #if TRIINV_INST_NB == 4
     case M_NEUMANN: return go_kda<M_NEUMANN>(a);
 #endif

@@ -344,6 +344,63 @@ __device__ __forceinline__ void neumann(const ASrc& A, v4f (&Xt)[NB * (NB + 1) /
 }
 
 // ---------------------------------------------------------------------------------------------
+// Newton-Schulz iteration (paper Alg. 3, Eq. 8) for the matrix I + A:
+//   X <- X0 = I / C;   n_iter times:  Y <- (I + A) X;   X <- 2 X - X Y.
+// Every iterate is a polynomial in A, hence lower triangular: the same tile structure as above.
+// State: X in both orientations (X Y needs X as a left factor, (I + A) X as a right factor).
+// Result: Xt, every tile in T orientation.
+// ---------------------------------------------------------------------------------------------
+template <int OP, int NB, class ASrc>
+__device__ __forceinline__ void newton_schulz(const ASrc& A, v4f (&Xt)[NB * (NB + 1) / 2], int n_iter, Lane ln)
+{
+    constexpr int NT = NB * (NB + 1) / 2;
+    Opnd<OP> Lt[NT];
+    v4f Xn[NT];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            Lt[tix(i, j)] = pack<OP>(A.template get<true>(i, j));
+            v4f x;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = (i == j && 4 * ln.q + r == ln.n) ? 1.f / (16 * NB) : 0.f;
+            Xn[tix(i, j)] = x;
+            Xt[tix(i, j)] = x;
+        }
+#pragma unroll 1
+    for (int it = 0; it < n_iter; ++it) {
+        Opnd<OP> xn[NT], xt[NT], yn[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            xn[t] = pack<OP>(Xn[t]);
+            xt[t] = pack<OP>(Xt[t]);
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {  // Y = X + A X
+                v4f acc = Xn[tix(i, j)];
+#pragma unroll
+                for (int k = j; k <= i; ++k) acc = tn<OP>(Lt[tix(i, k)], xn[tix(k, j)], acc);
+                yn[tix(i, j)] = pack<OP>(acc);
+            }
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {  // X <- 2 X - X Y, in both orientations
+                v4f pn = zero4(), pt = zero4();
+#pragma unroll
+                for (int k = j; k <= i; ++k) {
+                    pn = tn<OP>(xt[tix(i, k)], yn[tix(k, j)], pn);
+                    pt = tn<OP>(yn[tix(k, j)], xt[tix(i, k)], pt);
+                }
+                Xn[tix(i, j)] = 2.f * Xn[tix(i, j)] - pn;
+                Xt[tix(i, j)] = 2.f * Xt[tix(i, j)] - pt;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // One step of iterative refinement (paper Alg. 6, Eq. 9, for the matrix I + A):
 //   R <- I - Y (I + A);   X <- Y + R Y.
 // Y comes in as the tiles Tt in the orientations is_t() reports; each tile is brought to both

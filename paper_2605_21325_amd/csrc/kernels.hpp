@@ -8,7 +8,7 @@
 
 namespace triinv {
 
-enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3, M_BLOCK_DIRECT = 4 };
+enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3, M_BLOCK_DIRECT = 4, M_NEWTON_SCHULZ = 5 };
 enum : int { G_SCALAR = 0, G_CHANNEL = 1, G_NONE = 2 };
 
 __device__ __forceinline__ void wave_lds_sync()
@@ -182,7 +182,7 @@ template <int NB> __host__ __device__ constexpr bool merge_block_is_T(int i, int
 
 template <int NB, int METHOD> __host__ __device__ constexpr bool need_tile(int i, int j, bool tr)
 {
-    if (METHOD == M_FWD) return tr;
+    if (METHOD == M_FWD || METHOD == M_NEWTON_SCHULZ) return tr;
     if (METHOD == M_NEUMANN) return true;
     if (i == j) return METHOD == M_BLOCK_DIRECT ? tr : true;
     return merge_block_is_T<NB>(i, j) ? !tr : tr;
@@ -492,11 +492,15 @@ template <int NB> constexpr int gate_lds_floats() { return 2 * 16 * NB; }
 
 // REFINE: one iterative-refinement step after a matrix-product method (C = 64 only).
 template <int OP, int NB, int METHOD, class ASrc, bool REFINE = false>
-__device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, float* lds, Lane ln)
+__device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, float* lds, Lane ln, int aux = 0)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     if (METHOD == M_FWD) {
         forward_substitution<NB>(src, Tm, lds, ln);
+    } else if (METHOD == M_NEWTON_SCHULZ) {
+        v4f Xt[NT];
+        newton_schulz<OP, NB>(src, Xt, aux, ln);  // aux = number of iterations
+        store_result<NB>(Tm, Xt, [](int, int) { return true; }, lds, ln);
     } else if (METHOD == M_NEUMANN) {
         v4f Xt[NT];
         neumann<OP, NB>(src, Xt, ln);
@@ -521,7 +525,8 @@ template <int NB, int METHOD> constexpr int core_lds_floats()
 }
 
 template <int OP, int NB, int METHOD, bool REFINE = false>
-__global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt)
+__global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt,
+                                                int aux)
 {
     constexpr int C = 16 * NB;
     __shared__ __attribute__((aligned(16))) float lds[core_lds_floats<NB, METHOD>()];
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, floa
     src.base = static_cast<const char*>(A) + m * C * C * (in_dt == OP_F32 ? 4 : 2);
     src.dt = in_dt;
     src.ln = ln;
-    invert_and_store<OP, NB, METHOD, GlobalA<NB>, REFINE>(src, T + m * C * C, lds, ln);
+    invert_and_store<OP, NB, METHOD, GlobalA<NB>, REFINE>(src, T + m * C * C, lds, ln, aux);
 }
 
 // Workgroup -> matrix map of the fused kernels.  Workgroups are handed to the 8 XCDs round-robin
@@ -565,7 +570,7 @@ __device__ __forceinline__ int64_t fused_matrix_index(int64_t n_chunk, int H, in
 template <int KD, int OP, int NB, int METHOD, int DKS, bool REFINE = false, int WPB = 1>
 __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T,
-                                                          int64_t n_chunk, int H, int d_k)
+                                                          int64_t n_chunk, int H, int d_k, int aux)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD>();
@@ -584,14 +589,14 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
     src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
     src.load_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, lds);
-    invert_and_store<OP, NB, METHOD, GramA<KD, NB, DKS>, REFINE>(src, T + m * C * C, lds, ln);
+    invert_and_store<OP, NB, METHOD, GramA<KD, NB, DKS>, REFINE>(src, T + m * C * C, lds, ln, aux);
 }
 
 // Fused kernel for the per-channel gate: g is [B, Tlen, H, d_k]; the gated keys are rounded to OP.
 template <int OP, int NB, int METHOD, int WPB = 1>
 __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T,
-                                                          int64_t n_chunk, int H, int d_k, int k_dt)
+                                                          int64_t n_chunk, int H, int d_k, int k_dt, int aux)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD>();
@@ -608,7 +613,7 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict
     PreA<NB> src;
     build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
                                         beta + tok0 * H + h, H, d_k, lds, ln);
-    invert_and_store<OP, NB, METHOD>(src, T + m * C * C, lds, ln);
+    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, T + m * C * C, lds, ln, aux);
 }
 
 // ---------------------------------------------------------------------------------------------
