@@ -122,6 +122,9 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
  *   T     device, [n_mat][C][C] fp32 with n_mat = B * (Tlen / C) * H and matrix index
  *         m = (b * (Tlen / C) + chunk) * H + h; must not overlap an input.
  *   Tlen must be a multiple of C (a shorter last chunk is rejected), d_k a multiple of 32, <= 256.
+ *   d_k = 64 and 128 have specialised kernels for every method; other values run a channel loop and
+ *   are built for TRIINV_FWD_SUBST, TRIINV_BLOCK_RECURSIVE and TRIINV_BLOCK_DIRECT (and for every
+ *   method with the per-channel gate); anything else returns TRIINV_ERR_UNSUPPORTED.
  * Short form: k_dtype = BF16, scalar gate, method = TRIINV_BLOCK_RECURSIVE, op_dtype = BF16,
  * default stream, flags 0.
  */

@@ -143,6 +143,29 @@ static int kda_method(const GdnArgs& a)
     }
 }
 
+// Head dimensions other than 64 / 128: forward substitution, blocked recursion, blocked recursion from
+// directly solved blocks.
+template <int KD, int METHOD> static int go_any_dk(const GdnArgs& a)
+{
+    hipLaunchKernelGGL((k_gdn_any_dk_tri_inv<KD, OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
+                       a.g, a.T, a.n_chunk, a.H, a.d_k);
+    return 0;
+}
+
+template <int KD> static int any_dk_method(const GdnArgs& a)
+{
+    if (a.refine) return 1;
+    switch (a.method) {
+#if TRIINV_INST_FWD
+    case M_FWD: return go_any_dk<KD, M_FWD>(a);
+#else
+    case M_BLOCK: return go_any_dk<KD, M_BLOCK>(a);
+    case M_BLOCK_DIRECT: return go_any_dk<KD, M_BLOCK_DIRECT>(a);
+#endif
+    default: return 1;
+    }
+}
+
 int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const GdnArgs& a)
 {
     if (a.gate == G_CHANNEL) return kda_method(a);
@@ -159,7 +182,7 @@ int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const GdnArg
         if (a.d_k == 64) return gdn_method<OP_F16, 2>(a);
         if (a.d_k == 128) return gdn_method<OP_F16, 4>(a);
     }
-    return 1;
+    return a.k_dt == OP_F32 ? any_dk_method<OP_F32>(a) : a.k_dt == OP_BF16 ? any_dk_method<OP_BF16>(a) : any_dk_method<OP_F16>(a);
 #endif
 }
 

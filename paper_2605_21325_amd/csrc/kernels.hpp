@@ -94,36 +94,18 @@ template <> __device__ __forceinline__ v4f gram_step<OP_BF16>(v8bf a, v8bf b, v4
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
 }
 
-template <int KD, int NB, int DKS> struct GramA {
-    typedef typename KeyVec<KD>::type kvec;
+// beta / g of one chunk's tokens in the two index patterns a lane needs (by its column n, by its
+// rows 4q + r), and the scalar gate applied to a Gram tile:
+//   A_ij = beta_i exp(g_i - g_j) S_ij for i > j, else 0      (paper Table 1, GDN / DeltaNet rows).
+template <int NB> struct GateVec {
     static constexpr int C = 16 * NB;
-    static constexpr int KSTEP = (KD == OP_F32) ? 16 : 32;  // channels per k-step
-    kvec k[NB][DKS];
-    // gate vectors: *_n indexed by the lane's column n, *_q by its row group (4q + r)
     float beta_n[NB], g_n[NB];
     v4f beta_q[NB], g_q[NB];
     bool gated;
-    Lane ln;
 
-    // Kc: first key element of (chunk row 0, this head); row_stride in elements.
-    __device__ __forceinline__ void load_keys(const void* Kc, int64_t row_stride)
-    {
-        constexpr int per_lane = (KD == OP_F32) ? 4 : 8;
-#pragma unroll
-        for (int i = 0; i < NB; ++i)
-#pragma unroll
-            for (int s = 0; s < DKS; ++s) {
-                const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + KSTEP * s + per_lane * ln.q;
-                if (KD == OP_F32)
-                    k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const float*>(Kc) + off);
-                else
-                    k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const uint16_t*>(Kc) + off);
-            }
-    }
-
-    // beta / g of the chunk's tokens through a wave-private LDS patch of 2*C floats.
     // bc, gc: first element of (chunk row 0, this head); tok_stride in elements; gc may be null.
-    __device__ __forceinline__ void load_gate(const float* bc, const float* gc, int64_t tok_stride, float* lds)
+    // lds: wave-private, 2 * C floats.
+    __device__ __forceinline__ void load(const float* bc, const float* gc, int64_t tok_stride, float* lds, Lane ln)
     {
         const int l = 16 * ln.q + ln.n;
         gated = (gc != nullptr);
@@ -143,11 +125,9 @@ template <int KD, int NB, int DKS> struct GramA {
         wave_lds_sync();
     }
 
-    template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const
+    // s: Gram tile (i, j) in N (TR = false) or T orientation.
+    template <bool TR> __device__ __forceinline__ v4f apply(int i, int j, v4f s, Lane ln) const
     {
-        v4f s = zero4();
-#pragma unroll
-        for (int t = 0; t < DKS; ++t) s = TR ? gram_step<KD>(k[j][t], k[i][t], s) : gram_step<KD>(k[i][t], k[j][t], s);
         v4f a;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -162,6 +142,44 @@ template <int KD, int NB, int DKS> struct GramA {
             a[r] = low ? w * s[r] : 0.f;
         }
         return a;
+    }
+};
+
+template <int KD, int NB, int DKS> struct GramA {
+    typedef typename KeyVec<KD>::type kvec;
+    static constexpr int C = 16 * NB;
+    static constexpr int KSTEP = (KD == OP_F32) ? 16 : 32;  // channels per k-step
+    kvec k[NB][DKS];
+    GateVec<NB> gate;
+    Lane ln;
+
+    // Kc: first key element of (chunk row 0, this head); row_stride in elements.
+    __device__ __forceinline__ void load_keys(const void* Kc, int64_t row_stride)
+    {
+        constexpr int per_lane = (KD == OP_F32) ? 4 : 8;
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int s = 0; s < DKS; ++s) {
+                const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + KSTEP * s + per_lane * ln.q;
+                if (KD == OP_F32)
+                    k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const float*>(Kc) + off);
+                else
+                    k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const uint16_t*>(Kc) + off);
+            }
+    }
+
+    __device__ __forceinline__ void load_gate(const float* bc, const float* gc, int64_t tok_stride, float* lds)
+    {
+        gate.load(bc, gc, tok_stride, lds, ln);
+    }
+
+    template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const
+    {
+        v4f s = zero4();
+#pragma unroll
+        for (int t = 0; t < DKS; ++t) s = TR ? gram_step<KD>(k[j][t], k[i][t], s) : gram_step<KD>(k[i][t], k[j][t], s);
+        return gate.template apply<TR>(i, j, s, ln);
     }
 };
 
@@ -278,7 +296,9 @@ template <bool K16> __device__ __forceinline__ void widen_key8(const RawKey8<K16
 // its second half is still cached when needed (requested one k-step apart, lines were found
 // evicted in between and fetched from HBM twice).
 // Kc / gc: element (chunk row 0, this head, channel 0); row_stride in elements (same for both).
-template <int OPG, int NB, int METHOD, bool K16>
+// GATED = false: no per-channel gate; the stored keys themselves are the operands (OPG = their type,
+// exact products) and gc is not read -- the any-d_k path of the scalar / no-gate kinds.
+template <int OPG, int NB, int METHOD, bool K16, bool GATED = true>
 __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void* Kc, bool is_f16, const float* gc,
                                                       int64_t row_stride, int d_k, Lane ln)
 {
@@ -296,24 +316,34 @@ __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void*
         for (int t = 0; t < STEPS; ++t) {
             if (s0 + t >= d_k / 32) break;
             const int ch = 32 * (s0 + t) + 8 * ln.q;
-            const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch);
-            const v4f a1 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch + 4);
             GOp<OPG> pp[NB], pm[NB];
+            if constexpr (GATED) {
+                const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch);
+                const v4f a1 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch + 4);
 #pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + ch;
-                const v4f g0 = *reinterpret_cast<const v4f*>(gc + off);
-                const v4f g1 = *reinterpret_cast<const v4f*>(gc + off + 4);
-                float kv[8], up[8], dn[8];
-                widen_key8<K16>(raw[t][i], is_f16, kv);
+                for (int i = 0; i < NB; ++i) {
+                    const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + ch;
+                    const v4f g0 = *reinterpret_cast<const v4f*>(gc + off);
+                    const v4f g1 = *reinterpret_cast<const v4f*>(gc + off + 4);
+                    float kv[8], up[8], dn[8];
+                    widen_key8<K16>(raw[t][i], is_f16, kv);
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    const float d = ((r < 4) ? (g0[r] - a0[r]) : (g1[r - 4] - a1[r - 4])) * LOG2E;
-                    up[r] = kv[r] * __builtin_amdgcn_exp2f(d);
-                    dn[r] = kv[r] * __builtin_amdgcn_exp2f(-d);
+                    for (int r = 0; r < 8; ++r) {
+                        const float d = ((r < 4) ? (g0[r] - a0[r]) : (g1[r - 4] - a1[r - 4])) * LOG2E;
+                        up[r] = kv[r] * __builtin_amdgcn_exp2f(d);
+                        dn[r] = kv[r] * __builtin_amdgcn_exp2f(-d);
+                    }
+                    pp[i] = gpack<OPG>(up);
+                    pm[i] = gpack<OPG>(dn);
                 }
-                pp[i] = gpack<OPG>(up);
-                pm[i] = gpack<OPG>(dn);
+            } else {
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    float kv[8];
+                    widen_key8<K16>(raw[t][i], is_f16, kv);
+                    pp[i] = gpack<OPG>(kv);  // exact: OPG is the keys' own type
+                    pm[i] = pp[i];
+                }
             }
 #pragma unroll
             for (int i = 0; i < NB; ++i)
@@ -361,6 +391,31 @@ __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* K
             }
     }
     wave_lds_sync();
+}
+
+// Scalar / no-gate kinds for any d_k (multiple of 32): Gram tiles accumulated 32 channels at a time
+// in a run-time loop with the stored keys as operands, then the scalar gate.  KD = type of K.
+template <int KD, int NB, int METHOD>
+__device__ __forceinline__ void build_A_scalar_any_dk(PreA<NB>& out, const void* Kc, int64_t row_stride, const float* bc,
+                                                      const float* gc, int64_t tok_stride, int d_k, float* lds, Lane ln)
+{
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            out.n[tix(i, j)] = zero4();
+            out.t[tix(i, j)] = zero4();
+        }
+    accumulate_gated_gram<KD, NB, METHOD, KD != OP_F32, false>(out, Kc, KD == OP_F16, nullptr, row_stride, d_k, ln);
+    GateVec<NB> gate;
+    gate.load(bc, gc, tok_stride, lds, ln);
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j) {
+            if (need_tile<NB, METHOD>(i, j, false)) out.n[tix(i, j)] = gate.template apply<false>(i, j, out.n[tix(i, j)], ln);
+            if (need_tile<NB, METHOD>(i, j, true)) out.t[tix(i, j)] = gate.template apply<true>(i, j, out.t[tix(i, j)], ln);
+        }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -590,6 +645,27 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict
     src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
     src.load_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, lds);
     invert_and_store<OP, NB, METHOD, GramA<KD, NB, DKS>, REFINE>(src, T + m * C * C, lds, ln, aux);
+}
+
+// Fused kernel of the scalar / no-gate kinds for head dimensions without a specialised build.
+template <int KD, int OP, int NB, int METHOD>
+__global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
+                                                           const float* __restrict__ g, float* __restrict__ T,
+                                                           int64_t n_chunk, int H, int d_k)
+{
+    constexpr int C = 16 * NB;
+    constexpr int CORE = core_lds_floats<NB, METHOD>();
+    constexpr int GATE = gate_lds_floats<NB>();
+    __shared__ __attribute__((aligned(16))) float lds[CORE > GATE ? CORE : GATE];
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
+    const int h = (int)(m % H);
+    const int64_t tok0 = (m / H) * C;
+    const Lane ln = lane_id();
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    PreA<NB> src;
+    build_A_scalar_any_dk<KD, NB, METHOD>(src, static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz,
+                                          (int64_t)H * d_k, beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, d_k, lds, ln);
+    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, T + m * C * C, lds, ln, 0);
 }
 
 // Fused kernel for the per-channel gate: g is [B, Tlen, H, d_k]; the gated keys are rounded to OP.

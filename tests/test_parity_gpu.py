@@ -201,6 +201,34 @@ def test_per_channel_gate_fp32_and_fp16_keys(cases):
         check(T, ref, 1e-5, f"per-channel gate, keys {dt}")
 
 
+@pytest.mark.parametrize("d_k", [32, 96, 256])
+@pytest.mark.parametrize("C", [64, 128])
+def test_other_head_dimensions(C, d_k):
+    """Scalar and no-gate kinds at head dimensions without a specialised kernel (run-time channel loop)."""
+    for k_dtype, gate in (("bf16", si.GATE_SCALAR), ("f32", si.GATE_NONE)):
+        inp = si.make_inputs(si.workload(2, B=1, Tlen=3 * C, H=3, d_k=d_k, C=C, k_dtype=k_dtype, gate_kind=gate))
+        w = inp["workload"]
+        ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], gate, C)
+        g = None if inp["g"] is None else inp["g"].to(DEV)
+        for method, op in [(tri.BLOCK_RECURSIVE, tri.BF16), (tri.BLOCK_RECURSIVE, tri.F32), (tri.BLOCK_DIRECT, tri.F32),
+                           (tri.BLOCK_DIRECT, tri.F16), (tri.FWD_SUBST, tri.F32)]:
+            T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate, method=method, op_dtype=op)
+            check(T, ref, TOL[op], f"d_k={d_k} C={C} {k_dtype} {ids((method, op))}")
+
+
+def test_group_counts_that_are_not_multiples_of_eight(cases):
+    # 12 (batch, chunk) groups: 8 go through the XCD-aware map, 4 keep the plain order
+    inp = si.make_inputs(si.workload(1, B=1, Tlen=768, H=4))
+    w = inp["workload"]
+    ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    for method, op in [(tri.BLOCK_RECURSIVE, tri.F32), (tri.FWD_SUBST, tri.F32), (tri.NEUMANN, tri.F32)]:
+        check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, method=method, op_dtype=op), ref, 1e-5, f"12 groups {ids((method, op))}")
+    g4 = inp["g"][..., None].expand(-1, -1, -1, w.d_k).contiguous().to(DEV)
+    check(tri.gdn_chunk_tri_inv_ex(K, beta, g4, w.C, gate_kind=tri.GATE_PER_CHANNEL, method=tri.BLOCK_DIRECT, op_dtype=tri.F32),
+          ref, 1e-5, "12 groups, per-channel kernel")
+
+
 def test_refinement_step_recovers_digits(cases):
     """One step of iterative refinement (Alg. 6) after the mixed / blocked recursion.  The residual is
     formed with operands rounded to op_dtype like every other product, so the step cannot go below
@@ -277,10 +305,11 @@ def test_newton_schulz_iteration_count(cases):
 def test_unbuilt_combinations_report_unsupported(cases):
     c = cases[1]
     w, inp = c["w"], c["inp"]
+    # head dimensions other than 64 / 128 are built for three methods only
     K96 = torch.zeros(1, 64, 2, 96, dtype=torch.bfloat16, device=DEV)
     b = torch.zeros(1, 64, 2, device=DEV)
     with pytest.raises(tri.TriInvError) as e:
-        tri.gdn_chunk_tri_inv_ex(K96, b, b, 64)
+        tri.gdn_chunk_tri_inv_ex(K96, b, b, 64, method=tri.MIXED)
     assert e.value.status == -9
     for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=2), dict(method=tri.FWD_SUBST, flags=1), dict(method=tri.NEUMANN, flags=1)):
         with pytest.raises(tri.TriInvError) as e:
