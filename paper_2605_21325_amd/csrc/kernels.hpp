@@ -23,6 +23,7 @@ __device__ __forceinline__ void wave_lds_sync()
 // ---------------------------------------------------------------------------------------------
 template <int NB> struct GlobalA {
     static constexpr int C = 16 * NB;
+    static constexpr bool kFromMemory = true;   // a tile is a plain load: fetch it when it is needed
     const void* base;  // first element of this matrix
     int dt;            // OP_F32 / OP_F16 / OP_BF16 storage
     Lane ln;
@@ -146,6 +147,7 @@ template <int NB> struct GateVec {
 };
 
 template <int KD, int NB, int DKS> struct GramA {
+    static constexpr bool kFromMemory = false;  // a tile costs matrix-core work and pins the key registers
     typedef typename KeyVec<KD>::type kvec;
     static constexpr int C = 16 * NB;
     static constexpr int KSTEP = (KD == OP_F32) ? 16 : 32;  // channels per k-step
@@ -208,6 +210,7 @@ template <int NB, int METHOD> __host__ __device__ constexpr bool need_tile(int i
 
 // Tile source 3: all tiles precomputed in registers.
 template <int NB> struct PreA {
+    static constexpr bool kFromMemory = false;
     v4f n[NB * (NB + 1) / 2], t[NB * (NB + 1) / 2];
     template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const { return TR ? t[tix(i, j)] : n[tix(i, j)]; }
 };
@@ -490,6 +493,8 @@ __device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB
 // so every lane needs the same A[i][j]: the rows of A are staged through LDS, 16 rows at a
 // time (double-buffered), and read back with wave-uniform addresses (LDS broadcast).
 // C = 128 runs two passes of 64 columns; pass p only involves rows and columns >= 64 p.
+// Cost per matrix: C(C-1)/2 FMAs per lane plus one 16-byte LDS broadcast read per four of them; a
+// single running sum per row measured faster than four interleaved partial sums.
 // lds: wave-private, 2 * 16 * (C + 4) floats.
 // ---------------------------------------------------------------------------------------------
 template <int NB> constexpr int fwd_lds_floats() { return 2 * 16 * (16 * NB + 4); }
@@ -540,6 +545,50 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, f
     }
 }
 
+// The same substitution with all of A resident in LDS (tile-packed, 1 KB per lower tile): used at
+// C = 128 when the tiles come out of registers (Gram products), so that the key registers and the
+// tile registers are free before the 128 running values of T take theirs.
+template <int NB> constexpr int fwd_resident_lds_floats() { return NB * (NB + 1) / 2 * 256; }
+
+template <int NB, class ASrc>
+__device__ __forceinline__ void forward_substitution_resident(const ASrc& A, float* Tm, float* lds, Lane ln)
+{
+    constexpr int C = 16 * NB;
+    const int lane = 16 * ln.q + ln.n;
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j <= i; ++j)
+            *reinterpret_cast<v4f*>(&lds[tix(i, j) * 256 + ln.n * 16 + 4 * ln.q]) = A.template get<true>(i, j);
+    wave_lds_sync();
+#pragma unroll
+    for (int p = 0; p < C / 64; ++p) {
+        const int c = 64 * p + lane;
+        float Tc[C];
+        if (p > 0) {
+#pragma unroll 8
+            for (int i = 0; i < 64 * p; ++i) __builtin_nontemporal_store(0.f, Tm + (int64_t)i * C + c);
+        }
+#pragma unroll
+        for (int i = 64 * p; i < C; ++i) {
+            float acc = 0.f;
+#pragma unroll
+            for (int j4 = 64 * p; j4 < i; j4 += 4) {
+                const v4f a = *reinterpret_cast<const v4f*>(&lds[tix(i / 16, j4 / 16) * 256 + (i % 16) * 16 + (j4 % 16)]);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (j4 + r < i) acc += a[r] * Tc[j4 + r - 64 * p];
+            }
+            const float t = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
+            Tc[i - 64 * p] = t;
+            __builtin_nontemporal_store(t, Tm + (int64_t)i * C + c);
+            // keep the scheduler from hoisting later rows' LDS reads over this row (they do not depend on
+            // it, and hoisted by the hundred they would spill the running values of T)
+            if (i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Kernels
 // ---------------------------------------------------------------------------------------------
@@ -551,7 +600,10 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, flo
 {
     constexpr int NT = NB * (NB + 1) / 2;
     if (METHOD == M_FWD) {
-        forward_substitution<NB>(src, Tm, lds, ln);
+        if constexpr (NB == 8 && !ASrc::kFromMemory)
+            forward_substitution_resident<NB>(src, Tm, lds, ln);
+        else
+            forward_substitution<NB>(src, Tm, lds, ln);
     } else if (METHOD == M_NEWTON_SCHULZ) {
         v4f Xt[NT];
         newton_schulz<OP, NB>(src, Xt, aux, ln);  // aux = number of iterations
@@ -573,10 +625,10 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, flo
     }
 }
 
-template <int NB, int METHOD> constexpr int core_lds_floats()
+template <int NB, int METHOD, bool FUSED = false> constexpr int core_lds_floats()
 {
     static_assert(STORE_LDS_FLOATS >= XPOSE_FLOATS && STORE_LDS_FLOATS >= LEAF_FWD_FLOATS, "the store patch is the largest user");
-    return METHOD == M_FWD ? fwd_lds_floats<NB>() : STORE_LDS_FLOATS;
+    return METHOD != M_FWD ? STORE_LDS_FLOATS : (FUSED && NB == 8) ? fwd_resident_lds_floats<NB>() : fwd_lds_floats<NB>();
 }
 
 template <int OP, int NB, int METHOD, bool REFINE = false>
@@ -628,7 +680,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict
                                                           int64_t n_chunk, int H, int d_k, int aux)
 {
     constexpr int C = 16 * NB;
-    constexpr int CORE = core_lds_floats<NB, METHOD>();
+    constexpr int CORE = core_lds_floats<NB, METHOD, true>();
     constexpr int GATE = gate_lds_floats<NB>();
     constexpr int PER_WAVE = CORE > GATE ? CORE : GATE;
     __shared__ __attribute__((aligned(16))) float lds_all[WPB * PER_WAVE];
@@ -654,7 +706,7 @@ __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restric
                                                            int64_t n_chunk, int H, int d_k)
 {
     constexpr int C = 16 * NB;
-    constexpr int CORE = core_lds_floats<NB, METHOD>();
+    constexpr int CORE = core_lds_floats<NB, METHOD, true>();
     constexpr int GATE = gate_lds_floats<NB>();
     __shared__ __attribute__((aligned(16))) float lds[CORE > GATE ? CORE : GATE];
     const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
@@ -675,7 +727,7 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict
                                                           int64_t n_chunk, int H, int d_k, int k_dt, int aux)
 {
     constexpr int C = 16 * NB;
-    constexpr int CORE = core_lds_floats<NB, METHOD>();
+    constexpr int CORE = core_lds_floats<NB, METHOD, true>();
     constexpr int PER_WAVE = CORE > C ? CORE : C;
     __shared__ __attribute__((aligned(16))) float lds_all[WPB * PER_WAVE];
     float* lds = lds_all + ((WPB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * PER_WAVE;
