@@ -72,10 +72,20 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 
 #endif
 
+// Unused dynamic LDS that keeps a compute unit (160 KB of LDS) at two workgroups = two wavefronts per
+// SIMD for the 16-bit-operand recursions at C = 64.  Those kernels are bound by the memory system,
+// not by latency: with more wavefronts resident they measured 2-4 % slower (more requests queued at
+// the memory controllers, none served sooner).
+template <int METHOD> constexpr unsigned occupancy_pad_bytes()
+{
+    return (NB == 4 && WPB == 4 && OP != OP_F32 && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_BLOCK_DIRECT)) ? 24576u : 0u;
+}
+
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
-                       dim3(64 * WPB), 0, a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k, a.iters);
+                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k,
+                       a.iters);
     return 0;
 }
 
