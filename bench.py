@@ -50,8 +50,8 @@ def algorithmic_bytes_per_matrix(w, fused: bool, in_bytes: int = 4) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--method", type=int, default=1, help="0 fwd, 1 block recursive, 2 neumann, 3 mixed, 4 block direct")
     ap.add_argument("--op", type=int, default=2, help="operand type: 0 f32, 1 f16, 2 bf16")

@@ -72,7 +72,8 @@ typedef enum {
     TRIINV_ERR_BAD_C = -2,       /* C is not 64 or 128 */
     TRIINV_ERR_BAD_DTYPE = -3,   /* unknown in_dtype / k_dtype / op_dtype */
     TRIINV_ERR_BAD_METHOD = -4,  /* unknown method or gate kind */
-    TRIINV_ERR_BAD_SHAPE = -5,   /* n_mat < 0; B, H, d_k <= 0; Tlen < 0; Tlen % C != 0; d_k % 32 != 0; d_k > 256 */
+    TRIINV_ERR_BAD_SHAPE = -5,   /* n_mat < 0; B, H, d_k <= 0; Tlen < 0; d_k % 32 != 0; d_k > 256; more than 2^31 - 1 matrices;
+                                    inconsistent varlen totals */
     TRIINV_ERR_ALIGN = -6,       /* a pointer is not 16-byte aligned */
     TRIINV_ERR_ALIAS = -7,       /* T overlaps an input buffer */
     TRIINV_ERR_LAUNCH = -8,      /* the HIP runtime refused the launch */
@@ -119,9 +120,12 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
  *   beta  device, [B][Tlen][H] fp32.
  *   g     device, [B][Tlen][H] fp32: the chunk-local cumulative log-decay (the running sum
  *         restarts at every chunk boundary).
- *   T     device, [n_mat][C][C] fp32 with n_mat = B * (Tlen / C) * H and matrix index
- *         m = (b * (Tlen / C) + chunk) * H + h; must not overlap an input.
- *   Tlen must be a multiple of C (a shorter last chunk is rejected), d_k a multiple of 32, <= 256.
+ *   T     device, [n_mat][C][C] fp32 with n_mat = B * ceil(Tlen / C) * H and matrix index
+ *         m = (b * ceil(Tlen / C) + chunk) * H + h; must not overlap an input.
+ *   Tlen need not be a multiple of C: the last chunk of a sequence then has fewer than C tokens
+ *   (paper Sec. 1: chunks of "at most" C tokens) and is treated as padded with tokens whose key and
+ *   beta are zero, so its matrix still is C x C, with identity rows and columns for the padding;
+ *   nothing is read beyond token Tlen - 1 of a sequence.  d_k: a multiple of 32, <= 256.
  *   d_k = 64 and 128 have specialised kernels for every method; other values run a channel loop and
  *   are built for TRIINV_FWD_SUBST, TRIINV_BLOCK_RECURSIVE and TRIINV_BLOCK_DIRECT (and for every
  *   method with the per-channel gate); anything else returns TRIINV_ERR_UNSUPPORTED.
@@ -145,6 +149,31 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
                          int B, int64_t Tlen, int H, int d_k, int C,
                          int k_dtype, int gate_kind, int method, int op_dtype,
                          void* hip_stream, uint32_t flags);
+
+/*
+ * gdn_chunk_tri_inv_varlen: the fused operation on sequences of different lengths packed back to
+ * back (the layout serving frameworks use for batched prefill; paper Sec. 1 chunking applied to each
+ * sequence on its own).
+ *   K, beta, g     device, [total_tokens][H][d_k], [total_tokens][H], [total_tokens][H] (or
+ *                  [total_tokens][H][d_k] for the per-channel gate); g restarts at every chunk.
+ *   cu_seqlens     device, int64 [n_seq + 1]: row of the first token of each sequence, then
+ *                  total_tokens.  Non-decreasing; an empty sequence has no chunk.
+ *   cu_chunks      device, int64 [n_seq + 1]: id of the first chunk of each sequence, then
+ *                  total_chunks; sequence s owns ceil(len_s / C) consecutive ids.
+ *   total_tokens, total_chunks: the last entries of the two arrays, passed by value because the
+ *                  host cannot read device memory without a synchronisation.
+ *   T              device, [total_chunks * H][C][C] fp32, matrix index chunk_id * H + h; a last chunk
+ *                  with fewer than C tokens is padded as in gdn_chunk_tri_inv.
+ * The two arrays are trusted: the host only checks that the totals are consistent with each other
+ * (TRIINV_ERR_BAD_SHAPE), the kernels clamp every row index into [first token of the chunk, last
+ * token of the sequence].  8-byte alignment is required of cu_seqlens and cu_chunks.
+ * Other arguments as in gdn_chunk_tri_inv_ex.
+ */
+int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, float* T,
+                             const int64_t* cu_seqlens, const int64_t* cu_chunks, int n_seq,
+                             int64_t total_tokens, int64_t total_chunks, int H, int d_k, int C,
+                             int k_dtype, int gate_kind, int method, int op_dtype,
+                             void* hip_stream, uint32_t flags);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* triinv_status_string(int status);

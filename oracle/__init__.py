@@ -133,3 +133,55 @@ def gdn_chunk_tri_inv(K, beta, g, gate_kind: int, C: int, sel: Optional[Sequence
     _check(lib().oracle_gdn_chunk_tri_inv(kp, kcode, bp, gp, gate_kind, T.ctypes.data, B, Tlen, H, d_k, C,
                                           sp, ns, n_threads), "gdn_chunk_tri_inv")
     return T
+
+
+def _pad_to_chunks(K, beta, g, C: int):
+    """[B, Tlen, ...] stored tensors padded along the token axis to a multiple of C with tokens whose key
+    and beta are zero (g = 0 there): the padded rows and columns of A vanish (paper Sec. 1: chunks of at
+    most C tokens; a short last chunk is the leading block of a C x C matrix that is the identity elsewhere)."""
+    import torch
+
+    K = torch.as_tensor(K)
+    Tlen = K.shape[1]
+    pad = (-Tlen) % C
+    if pad == 0:
+        return K, beta, g
+
+    def grow(x):
+        if x is None:
+            return None
+        x = torch.as_tensor(x)
+        z = torch.zeros((x.shape[0], pad) + tuple(x.shape[2:]), dtype=x.dtype)
+        return torch.cat([x.cpu(), z], dim=1)
+
+    return grow(K), grow(beta), grow(g)
+
+
+def gdn_chunk_tri_inv_ragged(K, beta, g, gate_kind: int, C: int, n_threads: int = 0) -> np.ndarray:
+    """Fused flavour for any Tlen: ceil(Tlen / C) chunks per sequence, the last one zero-padded."""
+    Kp, bp, gp = _pad_to_chunks(K, beta, g, C)
+    return gdn_chunk_tri_inv(Kp, bp, gp, gate_kind, C, n_threads=n_threads)
+
+
+def build_A_ragged(K, beta, g, gate_kind: int, C: int, n_threads: int = 0) -> np.ndarray:
+    Kp, bp, gp = _pad_to_chunks(K, beta, g, C)
+    return build_A(Kp, bp, gp, gate_kind, C, n_threads=n_threads)
+
+
+def gdn_chunk_tri_inv_varlen(K, beta, g, seqlens, gate_kind: int, C: int, n_threads: int = 0) -> np.ndarray:
+    """Packed variable-length sequences (K [total, H, d_k], beta [total, H], g [total, H(, d_k)]): every
+    sequence is chunked on its own; results concatenated in sequence order, chunk-major, head-minor."""
+    import torch
+
+    K = torch.as_tensor(K)
+    out, t0 = [], 0
+    for n in seqlens:
+        n = int(n)
+        if n > 0:
+            sl = slice(t0, t0 + n)
+            out.append(gdn_chunk_tri_inv_ragged(K[sl][None], torch.as_tensor(beta)[sl][None],
+                                                None if g is None else torch.as_tensor(g)[sl][None], gate_kind, C,
+                                                n_threads=n_threads))
+        t0 += n
+    H = K.shape[1]
+    return np.concatenate(out, axis=0) if out else np.empty((0, C, C), dtype=np.float64)

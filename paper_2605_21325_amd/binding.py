@@ -33,7 +33,8 @@ METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUM
                 BLOCK_DIRECT: "block_direct", NEWTON_SCHULZ: "newton_schulz"}
 DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
 
-EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "triinv_status_string", "triinv_version")
+EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "gdn_chunk_tri_inv_varlen",
+           "triinv_status_string", "triinv_version")
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -62,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.gdn_chunk_tri_inv.restype = i32
         L.gdn_chunk_tri_inv_ex.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, i32, vp, u32]
         L.gdn_chunk_tri_inv_ex.restype = i32
+        L.gdn_chunk_tri_inv_varlen.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i32, i32, i32, vp, u32]
+        L.gdn_chunk_tri_inv_varlen.restype = i32
         L.triinv_status_string.argtypes = [i32]
         L.triinv_status_string.restype = ctypes.c_char_p
         L.triinv_version.argtypes = []
@@ -126,7 +129,7 @@ def tri_inv_ex(A: torch.Tensor, T: Optional[torch.Tensor] = None, method: int = 
 
 def _n_mat(K: torch.Tensor, C: int) -> int:
     B, Tlen, H, _ = K.shape
-    return B * (Tlen // C) * H
+    return B * ((Tlen + C - 1) // C) * H
 
 
 def gdn_chunk_tri_inv(K: torch.Tensor, beta: torch.Tensor, g: torch.Tensor, C: int,
@@ -155,4 +158,38 @@ def gdn_chunk_tri_inv_ex(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.
                                     dtype_code(K.dtype), gate_kind, method, op_dtype, _stream_ptr(stream), flags)
     if st != OK:
         raise TriInvError(st, "gdn_chunk_tri_inv_ex")
+    return T
+
+
+def varlen_chunk_offsets(seqlens, C: int):
+    """Host lists (cu_seqlens, cu_chunks) for sequences of the given lengths: argument preparation
+    for gdn_chunk_tri_inv_varlen (sequence s owns ceil(len_s / C) consecutive chunk ids)."""
+    cu_s, cu_c = [0], [0]
+    for n in seqlens:
+        n = int(n)
+        cu_s.append(cu_s[-1] + n)
+        cu_c.append(cu_c[-1] + (n + C - 1) // C)
+    return cu_s, cu_c
+
+
+def gdn_chunk_tri_inv_varlen(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], seqlens, C: int,
+                             T: Optional[torch.Tensor] = None, gate_kind: int = GATE_SCALAR,
+                             method: int = BLOCK_RECURSIVE, op_dtype: int = BF16, stream=None, flags: int = 0) -> torch.Tensor:
+    """Fused build + invert on packed variable-length sequences: K [total_tokens, H, d_k], beta
+    [total_tokens, H], g [total_tokens, H] (or [total_tokens, H, d_k]); seqlens = host sequence of lengths."""
+    total, H, d_k = K.shape
+    cu_s, cu_c = varlen_chunk_offsets(seqlens, C)
+    if cu_s[-1] != total:
+        raise ValueError(f"sequence lengths sum to {cu_s[-1]}, K holds {total} tokens")
+    cu_seqlens = torch.tensor(cu_s, dtype=torch.int64, device=K.device)
+    cu_chunks = torch.tensor(cu_c, dtype=torch.int64, device=K.device)
+    if T is None:
+        T = torch.empty((cu_c[-1] * H, C, C), dtype=torch.float32, device=K.device)
+    gp = None if g is None else _dev(g, "g")
+    st = lib().gdn_chunk_tri_inv_varlen(_dev(K, "K"), _dev(beta, "beta"), gp, _dev(T, "T") if T.numel() else None,
+                                        cu_seqlens.data_ptr(), cu_chunks.data_ptr(), len(cu_s) - 1, total, cu_c[-1], H, d_k, C,
+                                        dtype_code(K.dtype), gate_kind, method, op_dtype, _stream_ptr(stream), flags)
+    if st != OK:
+        raise TriInvError(st, "gdn_chunk_tri_inv_varlen")
+    T._triinv_keepalive = (cu_seqlens, cu_chunks)  # the launch is asynchronous: the offsets live as long as the result
     return T

@@ -33,6 +33,40 @@ int finish(int not_built)
     return hipGetLastError() == hipSuccess ? TRIINV_OK : TRIINV_ERR_LAUNCH;
 }
 
+// Shared tail of the fused entry points: everything but the token layout has been validated.
+int launch_fused(const GdnArgs& a, int C, int op_dtype)
+{
+    int nb = 1;
+    if (a.method == TRIINV_FWD_SUBST && a.refine) {
+        nb = 1;
+    } else if (a.method == TRIINV_FWD_SUBST) {
+        if (C == 64)
+            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1_fwd(a) : launch_gdn_nb4_op2_fwd(a);
+        else
+            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1_fwd(a) : launch_gdn_nb8_op2_fwd(a);
+    } else if (C == 64) {
+        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1(a) : launch_gdn_nb4_op2(a);
+    } else {
+        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1(a) : launch_gdn_nb8_op2(a);
+    }
+    return finish(nb);
+}
+
+// Checks common to both token layouts.  n_tok = number of (token, head) pairs, n_mat = matrices to write.
+int check_fused(const void* K, const float* beta, const float* g, float* T, uint64_t n_tok, int64_t n_mat, int H, int d_k,
+                       int C, int k_dtype, int gate_kind, uint32_t flags)
+{
+    const bool need_g = gate_kind != TRIINV_GATE_NONE;
+    if (!K || !beta || !T || (need_g && !g)) return TRIINV_ERR_NULL;
+    if (!aligned16(K) || !aligned16(beta) || !aligned16(T) || (need_g && !aligned16(g))) return TRIINV_ERR_ALIGN;
+    const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4;
+    if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
+    if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
+    if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
+    (void)H;
+    return TRIINV_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -77,37 +111,51 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
     if (!dtype_ok(k_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
     if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
     if (gate_kind < TRIINV_GATE_SCALAR || gate_kind > TRIINV_GATE_NONE) return TRIINV_ERR_BAD_METHOD;
-    if (B <= 0 || H <= 0 || d_k <= 0 || Tlen < 0 || Tlen % C != 0 || d_k % 32 != 0 || d_k > 256) return TRIINV_ERR_BAD_SHAPE;
-    const int64_t n_chunk = (int64_t)B * (Tlen / C);
+    if (B <= 0 || H <= 0 || d_k <= 0 || Tlen < 0 || d_k % 32 != 0 || d_k > 256) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t cps = (Tlen + C - 1) / C;  // chunks per sequence; the last one may hold fewer than C tokens
+    if (cps > 0x7fffffffLL / B) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t n_chunk = (int64_t)B * cps;
+    if (n_chunk > 0x7fffffffLL / H) return TRIINV_ERR_BAD_SHAPE;
     const int64_t n_mat = n_chunk * H;
-    if (n_mat > 0x7fffffffLL) return TRIINV_ERR_BAD_SHAPE;
     if (n_mat == 0) return TRIINV_OK;
-    const bool need_g = gate_kind != TRIINV_GATE_NONE;
-    if (!K || !beta || !T || (need_g && !g)) return TRIINV_ERR_NULL;
-    if (!aligned16(K) || !aligned16(beta) || !aligned16(T) || (need_g && !aligned16(g))) return TRIINV_ERR_ALIGN;
-    const uint64_t n_tok = (uint64_t)B * Tlen * H;
-    const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4;
-    if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
-    if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
-    if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
+    const int st = check_fused(K, beta, g, T, (uint64_t)B * Tlen * H, n_mat, H, d_k, C, k_dtype, gate_kind, flags);
+    if (st != TRIINV_OK) return st;
     if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
 
-    GdnArgs a{K, beta, need_g ? g : nullptr, T, n_mat, n_chunk, H, d_k, k_dtype, gate_kind, method, static_cast<hipStream_t>(hip_stream),
-              (flags & TRIINV_FLAG_REFINE1) != 0, ns_iterations(flags, C)};
-    int nb = 1;
-    if (method == TRIINV_FWD_SUBST && a.refine) {
-        nb = 1;
-    } else if (method == TRIINV_FWD_SUBST) {
-        if (C == 64)
-            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1_fwd(a) : launch_gdn_nb4_op2_fwd(a);
-        else
-            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1_fwd(a) : launch_gdn_nb8_op2_fwd(a);
-    } else if (C == 64) {
-        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1(a) : launch_gdn_nb4_op2(a);
-    } else {
-        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1(a) : launch_gdn_nb8_op2(a);
-    }
-    return finish(nb);
+    const ChunkMap map{Tlen, (uint32_t)cps, 0u, nullptr, nullptr};
+    GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, T, n_mat, n_chunk, map, H, d_k, k_dtype, gate_kind, method,
+              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, ns_iterations(flags, C)};
+    return launch_fused(a, C, op_dtype);
+}
+
+int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, float* T, const int64_t* cu_seqlens,
+                             const int64_t* cu_chunks, int n_seq, int64_t total_tokens, int64_t total_chunks, int H, int d_k,
+                             int C, int k_dtype, int gate_kind, int method, int op_dtype, void* hip_stream, uint32_t flags)
+{
+    if (C != 64 && C != 128) return TRIINV_ERR_BAD_C;
+    if (!dtype_ok(k_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
+    if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
+    if (gate_kind < TRIINV_GATE_SCALAR || gate_kind > TRIINV_GATE_NONE) return TRIINV_ERR_BAD_METHOD;
+    if (n_seq <= 0 || H <= 0 || d_k <= 0 || total_tokens < 0 || total_chunks < 0 || d_k % 32 != 0 || d_k > 256)
+        return TRIINV_ERR_BAD_SHAPE;
+    // every chunk holds between 1 and C tokens, and a sequence wastes at most one partly filled chunk
+    if (total_chunks > total_tokens || total_chunks * C < total_tokens || total_chunks > (total_tokens + C - 1) / C + n_seq)
+        return TRIINV_ERR_BAD_SHAPE;
+    if (total_chunks > 0x7fffffffLL / H) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t n_mat = total_chunks * H;
+    if (n_mat == 0) return TRIINV_OK;
+    if (!cu_seqlens || !cu_chunks) return TRIINV_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 7u) || (reinterpret_cast<uintptr_t>(cu_chunks) & 7u)) return TRIINV_ERR_ALIGN;
+    const int st = check_fused(K, beta, g, T, (uint64_t)total_tokens * H, n_mat, H, d_k, C, k_dtype, gate_kind, flags);
+    if (st != TRIINV_OK) return st;
+    const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4, cu_bytes = (uint64_t)(n_seq + 1) * 8;
+    if (overlap(cu_seqlens, cu_bytes, T, t_bytes) || overlap(cu_chunks, cu_bytes, T, t_bytes)) return TRIINV_ERR_ALIAS;
+    if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
+
+    const ChunkMap map{0, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
+    GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, T, n_mat, total_chunks, map, H, d_k, k_dtype, gate_kind, method,
+              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, ns_iterations(flags, C)};
+    return launch_fused(a, C, op_dtype);
 }
 
 int gdn_chunk_tri_inv(const void* K, const float* beta, const float* g, float* T, int B, int64_t Tlen, int H, int d_k, int C)

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "chunk_map.hpp"
 
 namespace triinv {
 
@@ -23,7 +24,8 @@ struct GdnArgs {
     const float* g;  // null for the no-gate kind
     float* T;
     int64_t n_mat;
-    int64_t n_chunk;  // B * Tlen / C
+    int64_t n_chunk;  // total number of chunks
+    ChunkMap map;     // where each chunk's tokens are
     int H;
     int d_k;
     int k_dt;

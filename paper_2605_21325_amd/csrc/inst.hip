@@ -84,7 +84,7 @@ template <int METHOD> constexpr unsigned occupancy_pad_bytes()
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
-                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k,
+                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
                        a.iters);
     return 0;
 }
@@ -116,7 +116,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
             return 1;  // 128 fp32 channels x 128 rows of keys per wave do not fit the register file
         } else {
             hipLaunchKernelGGL((k_gdn_tri_inv_neumann128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
-                               a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k);
+                               a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
             return 0;
         }
 #endif
@@ -128,7 +128,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 template <int METHOD> static int go_kda(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
-                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.H, a.d_k, a.k_dt, a.iters);
+                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters);
     return 0;
 }
 
@@ -158,7 +158,7 @@ static int kda_method(const GdnArgs& a)
 template <int KD, int METHOD> static int go_any_dk(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_gdn_any_dk_tri_inv<KD, OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
-                       a.g, a.T, a.n_chunk, a.H, a.d_k);
+                       a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
     return 0;
 }
 

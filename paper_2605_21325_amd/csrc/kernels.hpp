@@ -4,6 +4,7 @@
 // Methods: forward substitution (fp32 VALU, A broadcast through LDS), blocked recursion,
 // Neumann product, mixed recursion (MFMA, see inv_core.hpp).
 #pragma once
+#include "chunk_map.hpp"
 #include "inv_core.hpp"
 
 namespace triinv {
@@ -109,17 +110,28 @@ template <int NB> struct GateVec {
     // redistributes them through LDS into the two index patterns.  Vector-memory loads return in
     // order, so issuing these first lets stage() wait for them alone while later loads stay in flight.
     // bc, gc: first element of (chunk row 0, this head); tok_stride in elements; gc may be null.
-    float raw_b[C / 64], raw_g[C / 64];
+    static constexpr int RAW = C >= 64 ? C / 64 : 1;
+    float raw_b[RAW], raw_g[RAW];
 
-    __device__ __forceinline__ void issue(const float* bc, const float* gc, int64_t tok_stride, Lane ln)
+    // valid: number of tokens the chunk really has; the rows beyond read the last real token (a valid
+    // address, and a g that keeps every exponent of the gate <= 0) and get beta = 0.
+    __device__ __forceinline__ void issue(const float* bc, const float* gc, int64_t tok_stride, Lane ln, int valid = C)
     {
         const int l = 16 * ln.q + ln.n;
         gated = (gc != nullptr);
         const float* gp = gated ? gc : bc;  // always a valid address: the load is unconditional, the value is not
 #pragma unroll
-        for (int k = 0; k < C / 64; ++k) {
-            raw_b[k] = bc[(l + 64 * k) * tok_stride];
-            raw_g[k] = gp[(l + 64 * k) * tok_stride];
+        for (int k = 0; k < RAW; ++k) {
+            const int t = l + 64 * k;
+            if (C < 64 && t >= C) {  // more lanes than tokens
+                raw_b[k] = 0.f;
+                raw_g[k] = 0.f;
+                continue;
+            }
+            const int tc = t < valid ? t : valid - 1;
+            const float b = bc[tc * tok_stride];
+            raw_b[k] = t < valid ? b : 0.f;
+            raw_g[k] = gp[tc * tok_stride];
         }
     }
 
@@ -128,7 +140,8 @@ template <int NB> struct GateVec {
     {
         const int l = 16 * ln.q + ln.n;
 #pragma unroll
-        for (int k = 0; k < C / 64; ++k) {
+        for (int k = 0; k < RAW; ++k) {
+            if (C < 64 && l >= C) continue;
             lds[l + 64 * k] = raw_b[k];
             lds[C + l + 64 * k] = gated ? raw_g[k] : 0.f;
         }
@@ -143,9 +156,9 @@ template <int NB> struct GateVec {
         wave_lds_sync();
     }
 
-    __device__ __forceinline__ void load(const float* bc, const float* gc, int64_t tok_stride, float* lds, Lane ln)
+    __device__ __forceinline__ void load(const float* bc, const float* gc, int64_t tok_stride, float* lds, Lane ln, int valid = C)
     {
-        issue(bc, gc, tok_stride, ln);
+        issue(bc, gc, tok_stride, ln, valid);
         stage(lds, ln);
     }
 
@@ -179,27 +192,41 @@ template <int KD, int NB, int DKS> struct GramA {
     Lane ln;
 
     // Kc: first key element of (chunk row 0, this head); row_stride in elements.
-    __device__ __forceinline__ void load_keys(const void* Kc, int64_t row_stride)
+    // valid: number of tokens the chunk really has; rows beyond it read the last real token (a valid
+    // address) and are then replaced by zero keys.
+    __device__ __forceinline__ void load_keys(const void* Kc, int64_t row_stride, int valid = C)
     {
         constexpr int per_lane = (KD == OP_F32) ? 4 : 8;
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
             for (int s = 0; s < DKS; ++s) {
-                const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + KSTEP * s + per_lane * ln.q;
+                const int row = 16 * i + ln.n;
+                const int64_t off = (int64_t)(row < valid ? row : valid - 1) * row_stride + KSTEP * s + per_lane * ln.q;
                 // plain loads: the non-temporal hint measured ~5 % slower here
                 if (KD == OP_F32)
                     k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const float*>(Kc) + off);
                 else
                     k[i][s] = *reinterpret_cast<const kvec*>(static_cast<const uint16_t*>(Kc) + off);
             }
+        if (valid < C) {  // wave-uniform: only a sequence's last chunk comes here
+            const kvec zero = __builtin_bit_cast(kvec, v4u{0u, 0u, 0u, 0u});
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+#pragma unroll
+                for (int s = 0; s < DKS; ++s)
+                    if (16 * i + ln.n >= valid) k[i][s] = zero;
+        }
     }
 
-    __device__ __forceinline__ void load_gate(const float* bc, const float* gc, int64_t tok_stride, float* lds)
+    __device__ __forceinline__ void load_gate(const float* bc, const float* gc, int64_t tok_stride, float* lds, int valid = C)
     {
-        gate.load(bc, gc, tok_stride, lds, ln);
+        gate.load(bc, gc, tok_stride, lds, ln, valid);
     }
-    __device__ __forceinline__ void issue_gate(const float* bc, const float* gc, int64_t tok_stride) { gate.issue(bc, gc, tok_stride, ln); }
+    __device__ __forceinline__ void issue_gate(const float* bc, const float* gc, int64_t tok_stride, int valid = C)
+    {
+        gate.issue(bc, gc, tok_stride, ln, valid);
+    }
     __device__ __forceinline__ void stage_gate(float* lds) { gate.stage(lds, ln); }
 
     template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const
@@ -329,29 +356,40 @@ template <bool K16> __device__ __forceinline__ void widen_key8(const RawKey8<K16
 // exact products) and gc is not read -- the any-d_k path of the scalar / no-gate kinds.
 template <int OPG, int NB, int METHOD, bool K16, bool GATED = true>
 __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void* Kc, bool is_f16, const float* gc,
-                                                      int64_t row_stride, int d_k, Lane ln)
+                                                      int64_t row_stride, int d_k, Lane ln, int valid)
 {
     constexpr int C = 16 * NB;
     constexpr float LOG2E = 1.44269504088896340736f;
     constexpr int STEPS = (K16 && NB <= 4) ? 2 : 1;  // C = 128 has no registers to spare for the pairing
+    // rows beyond the chunk's real tokens read the last real one (valid addresses, finite exponents)
+    // and contribute zero keys; the anchor is a real row too
+    int rowc[NB];
+    float keep[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int row = 16 * i + ln.n;
+        rowc[i] = row < valid ? row : valid - 1;
+        keep[i] = row < valid ? 1.f : 0.f;
+    }
+    const int anchor = C / 2 < valid ? C / 2 : valid - 1;
     for (int s0 = 0; s0 < d_k / 32; s0 += STEPS) {
         RawKey8<K16> raw[STEPS][NB];
 #pragma unroll
         for (int t = 0; t < STEPS; ++t)
 #pragma unroll
             for (int i = 0; i < NB; ++i)
-                if (s0 + t < d_k / 32) raw[t][i] = load_key8<K16>(Kc, (int64_t)(16 * i + ln.n) * row_stride + 32 * (s0 + t) + 8 * ln.q);
+                if (s0 + t < d_k / 32) raw[t][i] = load_key8<K16>(Kc, (int64_t)rowc[i] * row_stride + 32 * (s0 + t) + 8 * ln.q);
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
             if (s0 + t >= d_k / 32) break;
             const int ch = 32 * (s0 + t) + 8 * ln.q;
             GOp<OPG> pp[NB], pm[NB];
             if constexpr (GATED) {
-                const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch);
-                const v4f a1 = *reinterpret_cast<const v4f*>(gc + (int64_t)(C / 2) * row_stride + ch + 4);
+                const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)anchor * row_stride + ch);
+                const v4f a1 = *reinterpret_cast<const v4f*>(gc + (int64_t)anchor * row_stride + ch + 4);
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
-                    const int64_t off = (int64_t)(16 * i + ln.n) * row_stride + ch;
+                    const int64_t off = (int64_t)rowc[i] * row_stride + ch;
                     const v4f g0 = *reinterpret_cast<const v4f*>(gc + off);
                     const v4f g1 = *reinterpret_cast<const v4f*>(gc + off + 4);
                     float kv[8], up[8], dn[8];
@@ -359,8 +397,9 @@ __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void*
 #pragma unroll
                     for (int r = 0; r < 8; ++r) {
                         const float d = ((r < 4) ? (g0[r] - a0[r]) : (g1[r - 4] - a1[r - 4])) * LOG2E;
-                        up[r] = kv[r] * __builtin_amdgcn_exp2f(d);
-                        dn[r] = kv[r] * __builtin_amdgcn_exp2f(-d);
+                        const float kk = kv[r] * keep[i];
+                        up[r] = kk * __builtin_amdgcn_exp2f(d);
+                        dn[r] = kk * __builtin_amdgcn_exp2f(-d);
                     }
                     pp[i] = gpack<OPG>(up);
                     pm[i] = gpack<OPG>(dn);
@@ -370,6 +409,8 @@ __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void*
                 for (int i = 0; i < NB; ++i) {
                     float kv[8];
                     widen_key8<K16>(raw[t][i], is_f16, kv);
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) kv[r] *= keep[i];
                     pp[i] = gpack<OPG>(kv);  // exact: OPG is the keys' own type
                     pm[i] = pp[i];
                 }
@@ -387,7 +428,7 @@ __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void*
 
 template <int OPG, int NB, int METHOD>
 __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* Kc, int kd, const float* gc, int64_t row_stride,
-                                                    const float* bc, int64_t tok_stride, int d_k, float* lds, Lane ln)
+                                                    const float* bc, int64_t tok_stride, int d_k, float* lds, Lane ln, int valid)
 {
     constexpr int C = 16 * NB;
 #pragma unroll
@@ -398,13 +439,13 @@ __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* K
             out.t[tix(i, j)] = zero4();
         }
     if (kd == OP_F32)
-        accumulate_gated_gram<OPG, NB, METHOD, false>(out, Kc, false, gc, row_stride, d_k, ln);
+        accumulate_gated_gram<OPG, NB, METHOD, false>(out, Kc, false, gc, row_stride, d_k, ln, valid);
     else
-        accumulate_gated_gram<OPG, NB, METHOD, true>(out, Kc, kd == OP_F16, gc, row_stride, d_k, ln);
+        accumulate_gated_gram<OPG, NB, METHOD, true>(out, Kc, kd == OP_F16, gc, row_stride, d_k, ln, valid);
     // beta_i row scaling and the strictly-lower mask
     const int l = 16 * ln.q + ln.n;
 #pragma unroll
-    for (int t = l; t < C; t += 64) lds[t] = bc[t * tok_stride];
+    for (int t = l; t < C; t += 64) lds[t] = t < valid ? bc[t * tok_stride] : 0.f;
     wave_lds_sync();
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
@@ -426,7 +467,7 @@ __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* K
 // in a run-time loop with the stored keys as operands, then the scalar gate.  KD = type of K.
 template <int KD, int NB, int METHOD>
 __device__ __forceinline__ void build_A_scalar_any_dk(PreA<NB>& out, const void* Kc, int64_t row_stride, const float* bc,
-                                                      const float* gc, int64_t tok_stride, int d_k, float* lds, Lane ln)
+                                                      const float* gc, int64_t tok_stride, int d_k, float* lds, Lane ln, int valid)
 {
 #pragma unroll
     for (int i = 0; i < NB; ++i)
@@ -435,9 +476,9 @@ __device__ __forceinline__ void build_A_scalar_any_dk(PreA<NB>& out, const void*
             out.n[tix(i, j)] = zero4();
             out.t[tix(i, j)] = zero4();
         }
-    accumulate_gated_gram<KD, NB, METHOD, KD != OP_F32, false>(out, Kc, KD == OP_F16, nullptr, row_stride, d_k, ln);
+    accumulate_gated_gram<KD, NB, METHOD, KD != OP_F32, false>(out, Kc, KD == OP_F16, nullptr, row_stride, d_k, ln, valid);
     GateVec<NB> gate;
-    gate.load(bc, gc, tok_stride, lds, ln);
+    gate.load(bc, gc, tok_stride, lds, ln, valid);
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -725,7 +766,7 @@ __device__ __forceinline__ int64_t fused_matrix_index(int64_t n_chunk, int H, in
 template <int KD, int OP, int NB, int METHOD, int DKS, bool REFINE = false, int WPB = 1>
 __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T,
-                                                          int64_t n_chunk, int H, int d_k, int aux)
+                                                          int64_t n_chunk, ChunkMap map, int H, int d_k, int aux)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
@@ -733,17 +774,18 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict
     constexpr int PER_WAVE = CORE > GATE ? CORE : GATE;
     __shared__ __attribute__((aligned(16))) float lds_all[WPB * PER_WAVE];
     float* lds = lds_all + ((WPB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * PER_WAVE;
-    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H);  // (b * n_chunk + chunk) * H + h
+    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H);  // chunk id * H + h
     if (m < 0) return;
-    const int h = (int)(m % H);
-    const int64_t bc = m / H;           // b * n_chunk + chunk  (Tlen = n_chunk * C, so token0 = bc * C)
-    const int64_t tok0 = bc * C;
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;  // m < 2^31 (checked by the host)
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
     const Lane ln = lane_id();
     GramA<KD, NB, DKS> src;
     src.ln = ln;
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
-    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H);
-    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
+    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
+    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
     src.stage_gate(lds);
     invert_and_store<OP, NB, METHOD, GramA<KD, NB, DKS>, REFINE>(src, T + m * C * C, lds, ln, aux);
 }
@@ -752,20 +794,23 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict
 template <int KD, int OP, int NB, int METHOD>
 __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                            const float* __restrict__ g, float* __restrict__ T,
-                                                           int64_t n_chunk, int H, int d_k)
+                                                           int64_t n_chunk, ChunkMap map, int H, int d_k)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
     constexpr int GATE = gate_lds_floats<NB>();
     __shared__ __attribute__((aligned(16))) float lds[CORE > GATE ? CORE : GATE];
     const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
-    const int h = (int)(m % H);
-    const int64_t tok0 = (m / H) * C;
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
     const Lane ln = lane_id();
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
     PreA<NB> src;
     build_A_scalar_any_dk<KD, NB, METHOD>(src, static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz,
-                                          (int64_t)H * d_k, beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, d_k, lds, ln);
+                                          (int64_t)H * d_k, beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, d_k, lds, ln,
+                                          pos.valid);
     invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, T + m * C * C, lds, ln, 0);
 }
 
@@ -773,7 +818,7 @@ __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restric
 template <int OP, int NB, int METHOD, int WPB = 1>
 __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T,
-                                                          int64_t n_chunk, int H, int d_k, int k_dt, int aux)
+                                                          int64_t n_chunk, ChunkMap map, int H, int d_k, int k_dt, int aux)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
@@ -782,14 +827,16 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict
     float* lds = lds_all + ((WPB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * PER_WAVE;
     const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H);
     if (m < 0) return;
-    const int h = (int)(m % H);
-    const int64_t tok0 = (m / H) * C;
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
     const Lane ln = lane_id();
     const int64_t esz = (k_dt == OP_F32) ? 4 : 2;
     const int64_t e0 = (tok0 * H + h) * (int64_t)d_k;  // element offset of (token 0, head h, channel 0)
     PreA<NB> src;
     build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
-                                        beta + tok0 * H + h, H, d_k, lds, ln);
+                                        beta + tok0 * H + h, H, d_k, lds, ln, pos.valid);
     invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, T + m * C * C, lds, ln, aux);
 }
 
@@ -951,21 +998,24 @@ __global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* __restri
 template <int KD, int OP, int DKS>
 __global__ __launch_bounds__(256) void k_gdn_tri_inv_neumann128(const void* __restrict__ K, const float* __restrict__ beta,
                                                                 const float* __restrict__ g, float* __restrict__ T,
-                                                                int64_t n_chunk, int H, int d_k)
+                                                                int64_t n_chunk, ChunkMap map, int H, int d_k)
 {
     constexpr int C = 128;
     __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
     const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
-    const int h = (int)(m % H);
-    const int64_t tok0 = (m / H) * C;
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Lane ln = lane_id();
     GramA<KD, N128_NB, DKS> src;
     src.ln = ln;
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
-    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k);
+    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
+    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
     // every wave stages beta / g for itself: a private 2 * C floats inside the (not yet used) Y buffer
-    src.load_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, Y + w * 2 * C);
+    src.stage_gate(Y + w * 2 * C);
     __syncthreads();
     neumann_c128_workgroup<OP>(src, T + m * C * C, Y, ln, w);
 }

@@ -51,7 +51,7 @@ class Workload:
 
     @property
     def n_mat(self) -> int:
-        return self.B * (self.Tlen // self.C) * self.H
+        return self.B * ((self.Tlen + self.C - 1) // self.C) * self.H
 
 
 WORKLOADS = (
@@ -78,7 +78,6 @@ def make_inputs(w: Workload, seed_offset: int = 0) -> dict:
     gen = torch.Generator(device="cpu")
     gen.manual_seed(SEED_BASE + w.index + 1000003 * seed_offset)
     B, Tlen, H, d_k, C = w.B, w.Tlen, w.H, w.d_k, w.C
-    assert Tlen % C == 0
 
     # --- keys -----------------------------------------------------------------------------
     if w.keys == "gaussian":
@@ -115,7 +114,12 @@ def make_inputs(w: Workload, seed_offset: int = 0) -> dict:
         rate = -torch.nn.functional.softplus(torch.randn(*shape, generator=gen, dtype=torch.float32))
         rate = rate * w.rate_scale
         # inclusive cumulative sum over the tokens of each chunk, restarted per chunk
-        g = rate.reshape(B, Tlen // C, C, *shape[2:]).cumsum(dim=2).reshape(shape).contiguous()
+        # (a last chunk with fewer than C tokens is padded for the reshape and cut again)
+        pad = (-Tlen) % C
+        if pad:
+            rate = torch.cat([rate, torch.zeros(B, pad, *shape[2:])], dim=1)
+        g = rate.reshape(B, (Tlen + pad) // C, C, *shape[2:]).cumsum(dim=2).reshape(B, Tlen + pad, *shape[2:])
+        g = g[:, :Tlen].contiguous()
 
     return {"K": K.contiguous(), "beta": beta.contiguous(), "g": g, "workload": w}
 

@@ -104,12 +104,35 @@ def test_gdn_argument_errors(L):
     assert call(kd=5) == -3 and call(op=9) == -3
     assert call(m=17) == -4 and call(gate=3) == -4
     assert call(B=0) == -5 and call(H=-1) == -5 and call(d_k=0) == -5
-    assert call(Tlen=100) == -5                 # not a multiple of C
+    assert call(Tlen=-64) == -5
+    assert call(B=1 << 20, Tlen=1 << 40) == -5      # more than 2^31 - 1 matrices
     assert call(d_k=48) == -5 and call(d_k=512) == -5
     assert call(K=None) == -1 and call(beta=None) == -1 and call(T=None) == -1 and call(g=None) == -1
     assert call(K=P + 2) == -6 and call(g=Q + (1 << 30) + 4) == -6
     assert call(T=P) == -7 and call(T=Q) == -7 and call(T=Q + (1 << 30)) == -7
     assert L.gdn_chunk_tri_inv(P, Q, None, Q + (2 << 30), 1, 128, 2, 128, 64) == -1
+
+
+def test_varlen_argument_errors(L):
+    vl = L.gdn_chunk_tri_inv_varlen
+    R = Q + (3 << 30)
+    base = dict(K=P, beta=Q, g=Q + (1 << 30), T=Q + (2 << 30), cs=R, cc=R + 4096, n_seq=3, tok=200, chunks=5, H=2, d_k=128,
+                C=64, kd=2, gate=0, m=1, op=2)
+
+    def call(**kw):
+        a = {**base, **kw}
+        return vl(a["K"], a["beta"], a["g"], a["T"], a["cs"], a["cc"], a["n_seq"], a["tok"], a["chunks"], a["H"], a["d_k"],
+                  a["C"], a["kd"], a["gate"], a["m"], a["op"], None, 0)
+
+    assert call(tok=0, chunks=0) == 0               # nothing to do
+    assert call(C=32) == -2 and call(kd=7) == -3 and call(m=9) == -4 and call(gate=-1) == -4
+    assert call(n_seq=0) == -5 and call(H=0) == -5 and call(d_k=40) == -5 and call(tok=-1) == -5
+    assert call(chunks=3) == -5                     # 3 chunks of 64 cannot hold 200 tokens
+    assert call(chunks=201) == -5                   # more chunks than tokens
+    assert call(chunks=8) == -5                     # more than one partly filled chunk per sequence
+    assert call(cs=None) == -1 and call(cc=None) == -1 and call(K=None) == -1
+    assert call(cs=R + 4) == -6 and call(T=Q + (2 << 30) + 8) == -6
+    assert call(T=R) == -7 and call(T=P) == -7
 
 
 def test_binding_refuses_host_tensors_and_missing_library(monkeypatch, L):

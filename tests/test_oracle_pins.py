@@ -268,3 +268,69 @@ def test_matmul_counts_table2():
         levels = []
         methods.mbh(np.zeros((n, n)), levels_out=levels)
         assert 2 * len(levels) == mbh_cnt
+
+
+# ---------------------------------------------------------------- short last chunk, packed sequences
+def _direct_A(k, b, g, gate_kind):
+    """A of one chunk from fp64 arrays, written with an explicit double loop (independent of oracle/)."""
+    n = k.shape[0]
+    A = np.zeros((n, n))
+    for i in range(n):
+        for j in range(i):
+            if gate_kind == 0:
+                A[i, j] = b[i] * math.exp(g[i] - g[j]) * float(k[i] @ k[j])
+            elif gate_kind == 1:
+                A[i, j] = b[i] * float(np.sum(k[i] * k[j] * np.exp(g[i] - g[j])))
+            else:
+                A[i, j] = b[i] * float(k[i] @ k[j])
+    return A
+
+
+@pytest.mark.parametrize("gate_kind", [0, 1, 2])
+@pytest.mark.parametrize("Tlen", [1, 37, 64, 100])
+def test_short_last_chunk_is_the_leading_block_of_an_identity_padded_matrix(gate_kind, Tlen):
+    C, H = 64, 2
+    idx = {0: 1, 1: 3, 2: 4}[gate_kind]
+    inp = _small(idx, B=1, Tlen=Tlen, H=H, C=C, d_k=32)
+    T = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)
+    n_chunk = (Tlen + C - 1) // C
+    assert T.shape == (n_chunk * H, C, C)
+    for chunk in range(n_chunk):
+        v = min(C, Tlen - chunk * C)
+        for h in range(H):
+            sl = slice(chunk * C, chunk * C + v)
+            k = inp["K"][0, sl, h].double().numpy()
+            b = inp["beta"][0, sl, h].double().numpy()
+            g = None if inp["g"] is None else inp["g"][0, sl, h].double().numpy()
+            ref = np.linalg.inv(np.eye(v) + _direct_A(k, b, g, gate_kind))
+            Tm = T[chunk * H + h]
+            assert np.allclose(Tm[:v, :v], ref, rtol=0, atol=1e-12)
+            assert np.array_equal(Tm[v:, :v], np.zeros((C - v, v)))       # padded rows: identity
+            assert np.array_equal(Tm[v:, v:], np.eye(C - v))
+            assert np.array_equal(Tm[:v, v:], np.zeros((v, C - v)))
+
+
+def test_packed_sequences_are_chunked_one_by_one():
+    C, H, d = 64, 3, 32
+    seqlens = [64, 1, 0, 133, 63]
+    inp = _small(1, B=1, Tlen=sum(seqlens), H=H, C=C, d_k=d)
+    K, beta = inp["K"][0], inp["beta"][0]
+    # chunk-local cumulative gate per sequence
+    gen = torch.Generator().manual_seed(5)
+    g = torch.zeros(sum(seqlens), H)
+    t0 = 0
+    for n in seqlens:
+        for c0 in range(0, n, C):
+            m = min(C, n - c0)
+            g[t0 + c0:t0 + c0 + m] = torch.cumsum(-0.1 * torch.rand(m, H, generator=gen), 0)
+        t0 += n
+    T = oracle.gdn_chunk_tri_inv_varlen(K, beta, g, seqlens, 0, C)
+    assert T.shape == ((1 + 1 + 0 + 3 + 1) * H, C, C)
+    # sequence 3 (133 tokens) starts at token 65 and at chunk id 2; its last chunk has 5 tokens
+    t0, c0, h = 65 + 128, 2 + 2, 1
+    k, b, gg = K[t0:t0 + 5, h].double().numpy(), beta[t0:t0 + 5, h].double().numpy(), g[t0:t0 + 5, h].double().numpy()
+    ref = np.linalg.inv(np.eye(5) + _direct_A(k, b, gg, 0))
+    assert np.allclose(T[c0 * H + h][:5, :5], ref, rtol=0, atol=1e-13)
+    assert np.array_equal(T[c0 * H + h][5:, 5:], np.eye(C - 5))
+    # the one-token sequence: A = 0, T = I
+    assert np.array_equal(T[1 * H + 0], np.eye(C))

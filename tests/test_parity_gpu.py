@@ -417,3 +417,68 @@ def test_neumann_c128_on_benign_input(op):
     Tf = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), 128, gate_kind=w.gate_kind,
                                   method=tri.NEUMANN, op_dtype=op)
     check(Tf, ref, TOL[op], f"neumann C=128 fused benign {tri.DTYPE_NAMES[op]}")
+
+
+# ------------------------------------------------------------------ short last chunks, packed sequences
+RAGGED_METHODS = [(tri.FWD_SUBST, tri.F32), (tri.BLOCK_RECURSIVE, tri.BF16), (tri.BLOCK_DIRECT, tri.F32), (tri.MIXED, tri.F16),
+                  (tri.NEUMANN, tri.F32)]
+
+
+@pytest.mark.parametrize("mo", RAGGED_METHODS, ids=ids)
+@pytest.mark.parametrize("gate_kind", [0, 1, 2])
+@pytest.mark.parametrize("C,Tlen", [(64, 1), (64, 63), (64, 65), (64, 200), (128, 127), (128, 300)])
+def test_sequence_lengths_that_are_not_multiples_of_the_chunk(C, Tlen, gate_kind, mo):
+    method, op = mo
+    if C == 128 and method == tri.NEUMANN and gate_kind == 1:
+        pytest.skip("not built: Neumann with the per-channel gate at C = 128")
+    idx = {0: 1, 1: 3, 2: 4}[gate_kind]
+    inp = si.make_inputs(si.workload(idx, B=2, Tlen=Tlen, H=3, C=C, d_k=128, k_dtype="bf16"))
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)
+    K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    n_mat = 2 * ((Tlen + C - 1) // C) * 3
+    guard = torch.full((n_mat + 1, C, C), 7.0, device=DEV)           # one matrix of slack behind the output
+    tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=guard[:n_mat], gate_kind=gate_kind, method=method, op_dtype=op)
+    torch.cuda.synchronize()
+    assert bool((guard[n_mat] == 7.0).all()), "wrote past the last matrix"
+    tol = TOL[op] if not (idx == 4 and method == tri.MIXED) else 4e-2
+    if idx == 4 and method == tri.NEUMANN:
+        return  # the Neumann product on the stress recipe is reported elsewhere, not asserted
+    check(guard[:n_mat], T_ref, tol, f"ragged C={C} Tlen={Tlen} gate={gate_kind} {ids(mo)}")
+
+
+@pytest.mark.parametrize("d_k", [96, 128])
+@pytest.mark.parametrize("gate_kind", [0, 1, 2])
+@pytest.mark.parametrize("C", [64, 128])
+def test_packed_variable_length_sequences(C, gate_kind, d_k):
+    H = 3
+    seqlens = [C, 1, 0, 2 * C + 5, C - 1, 3 * C, 0, 17]
+    total = sum(seqlens)
+    idx = {0: 1, 1: 3, 2: 4}[gate_kind]
+    inp = si.make_inputs(si.workload(idx, B=1, Tlen=total, H=H, C=C, d_k=d_k, k_dtype="bf16"))
+    K, beta = inp["K"][0].contiguous(), inp["beta"][0].contiguous()
+    g = None
+    if gate_kind != 2:
+        # chunk-local cumulative log-decay, restarted at every chunk of every sequence
+        gen = torch.Generator().manual_seed(11)
+        shape = (total, H) if gate_kind == 0 else (total, H, d_k)
+        rate = -0.05 * torch.nn.functional.softplus(torch.randn(*shape, generator=gen))
+        g, t0 = torch.zeros(shape), 0
+        for n in seqlens:
+            for c0 in range(0, n, C):
+                m = min(C, n - c0)
+                g[t0 + c0:t0 + c0 + m] = torch.cumsum(rate[t0 + c0:t0 + c0 + m], 0)
+            t0 += n
+    T_ref = oracle.gdn_chunk_tri_inv_varlen(K, beta, g, seqlens, gate_kind, C)
+    for method, op in [(tri.BLOCK_RECURSIVE, tri.BF16), (tri.FWD_SUBST, tri.F32), (tri.BLOCK_DIRECT, tri.F32)]:
+        T = tri.gdn_chunk_tri_inv_varlen(K.to(DEV), beta.to(DEV), None if g is None else g.to(DEV), seqlens, C,
+                                         gate_kind=gate_kind, method=method, op_dtype=op)
+        assert T.shape[0] == T_ref.shape[0]
+        check(T, T_ref, TOL[op], f"varlen C={C} gate={gate_kind} d_k={d_k} {ids((method, op))}")
+
+
+def test_packed_sequences_with_no_tokens_are_a_no_op():
+    K = torch.zeros((0, 2, 128), dtype=torch.bfloat16, device=DEV)
+    beta = torch.zeros((0, 2), device=DEV)
+    T = tri.gdn_chunk_tri_inv_varlen(K, beta, None, [0, 0], 64, gate_kind=tri.GATE_NONE)
+    assert T.shape == (0, 64, 64)
