@@ -55,7 +55,7 @@ typedef enum {
     TRIINV_BLOCK_DIRECT = 4,
     /* Newton-Schulz iteration (paper Alg. 3, Eq. 8): X <- I / C, then n times Y <- (I + A) X,
      * X <- 2X - XY.  n = TRIINV_FLAG_ITERS(n) in flags, default 12 (the count the paper finds
-     * sufficient at C = 64).  Built for C = 64. */
+     * sufficient at C = 64; 2 log2 C elsewhere).  Built for C <= 64. */
     TRIINV_NEWTON_SCHULZ = 5
 } triinv_method;
 
@@ -69,7 +69,7 @@ typedef enum {
 typedef enum {
     TRIINV_OK = 0,
     TRIINV_ERR_NULL = -1,        /* a required pointer is NULL while there is work to do */
-    TRIINV_ERR_BAD_C = -2,       /* C is not 64 or 128 */
+    TRIINV_ERR_BAD_C = -2,       /* C is not 16, 32, 64 or 128 */
     TRIINV_ERR_BAD_DTYPE = -3,   /* unknown in_dtype / k_dtype / op_dtype */
     TRIINV_ERR_BAD_METHOD = -4,  /* unknown method or gate kind */
     TRIINV_ERR_BAD_SHAPE = -5,   /* n_mat < 0; B, H, d_k <= 0; Tlen < 0; d_k % 32 != 0; d_k > 256; more than 2^31 - 1 matrices;
@@ -83,7 +83,7 @@ typedef enum {
 /* Bits of `flags` (0 = none). */
 #define TRIINV_FLAG_REFINE1 0x1u /* one iterative-refinement step X <- X + (I - X(I+A))X after the
                                     method (paper Alg. 6, Eq. 9).  Built for TRIINV_BLOCK_RECURSIVE and
-                                    TRIINV_MIXED at C = 64 (tri_inv and the scalar / no-gate fused
+                                    TRIINV_MIXED at C <= 64 (tri_inv and the scalar / no-gate fused
                                     kinds); anything else returns TRIINV_ERR_UNSUPPORTED */
 
 #define TRIINV_FLAG_ITERS(n) (((uint32_t)(n) & 0xffu) << 8) /* iteration count of TRIINV_NEWTON_SCHULZ (0 = default) */
@@ -96,7 +96,7 @@ typedef enum {
  *            NaN there does not change the result (the mask of Eq. 3 is applied on load).
  *   T        device, [n_mat][C][C] fp32, output; must not overlap A.
  *   n_mat    number of matrices, >= 0; 0 is a successful no-op (pointers may then be NULL).
- *   C        64 or 128.
+ *   C        16, 32, 64 or 128 (the chunk sizes used in practice, paper Sec. 1).
  *   in_dtype triinv_dtype of A.
  *   method   triinv_method.
  * Short form: op_dtype = in_dtype, default stream, flags 0.

@@ -30,10 +30,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-pass-faile
 # slowest units first so the pool stays busy
 UNITS = [
     (f"inst_nb{nb}_op{op}_fwd", "inst.hip", [f"-DTRIINV_INST_NB={nb}", f"-DTRIINV_INST_OP={op}", "-DTRIINV_INST_FWD=1"])
-    for nb in (8, 4) for op in (0, 1, 2)
+    for nb in (8, 4, 2, 1) for op in (0, 1, 2)
 ] + [
     (f"inst_nb{nb}_op{op}", "inst.hip", [f"-DTRIINV_INST_NB={nb}", f"-DTRIINV_INST_OP={op}"])
-    for nb in (8, 4) for op in (0, 1, 2)
+    for nb in (8, 4, 2, 1) for op in (0, 1, 2)
 ] + [("api", "api.hip", [])]
 
 

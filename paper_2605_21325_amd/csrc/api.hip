@@ -16,6 +16,7 @@ bool overlap(const void* a, uint64_t na, const void* b, uint64_t nb)
 }
 
 bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_BF16; }
+bool chunk_size_ok(int C) { return C == 16 || C == 32 || C == 64 || C == 128; }
 bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_NEWTON_SCHULZ; }
 
 constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | 0xff00u;
@@ -23,7 +24,7 @@ constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | 0xff00u;
 int ns_iterations(uint32_t flags, int C)
 {
     const int n = (int)((flags >> 8) & 0xffu);
-    return n ? n : (C == 64 ? 12 : 14);
+    return n ? n : (C == 16 ? 8 : C == 32 ? 10 : C == 64 ? 12 : 14);  // 2 log2 C (paper Sec. 3.5; 12 at C = 64, Sec. 4.2)
 }
 uint64_t esize(int d) { return d == TRIINV_F32 ? 4 : 2; }
 
@@ -37,18 +38,16 @@ int finish(int not_built)
 int launch_fused(const GdnArgs& a, int C, int op_dtype)
 {
     int nb = 1;
+#define TRIINV_PICK_OP(NBV, SUFFIX) \
+    (op_dtype == TRIINV_F32 ? launch_gdn_nb##NBV##_op0##SUFFIX(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb##NBV##_op1##SUFFIX(a) : launch_gdn_nb##NBV##_op2##SUFFIX(a))
     if (a.method == TRIINV_FWD_SUBST && a.refine) {
         nb = 1;
     } else if (a.method == TRIINV_FWD_SUBST) {
-        if (C == 64)
-            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1_fwd(a) : launch_gdn_nb4_op2_fwd(a);
-        else
-            nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0_fwd(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1_fwd(a) : launch_gdn_nb8_op2_fwd(a);
-    } else if (C == 64) {
-        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb4_op1(a) : launch_gdn_nb4_op2(a);
+        nb = C == 16 ? TRIINV_PICK_OP(1, _fwd) : C == 32 ? TRIINV_PICK_OP(2, _fwd) : C == 64 ? TRIINV_PICK_OP(4, _fwd) : TRIINV_PICK_OP(8, _fwd);
     } else {
-        nb = op_dtype == TRIINV_F32 ? launch_gdn_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb8_op1(a) : launch_gdn_nb8_op2(a);
+        nb = C == 16 ? TRIINV_PICK_OP(1, ) : C == 32 ? TRIINV_PICK_OP(2, ) : C == 64 ? TRIINV_PICK_OP(4, ) : TRIINV_PICK_OP(8, );
     }
+#undef TRIINV_PICK_OP
     return finish(nb);
 }
 
@@ -74,7 +73,7 @@ extern "C" {
 int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int method, int op_dtype, void* hip_stream,
                uint32_t flags)
 {
-    if (C != 64 && C != 128) return TRIINV_ERR_BAD_C;
+    if (!chunk_size_ok(C)) return TRIINV_ERR_BAD_C;
     if (!dtype_ok(in_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
     if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
     if (n_mat < 0 || n_mat > 0x7fffffffLL) return TRIINV_ERR_BAD_SHAPE;
@@ -89,13 +88,24 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0,
                  ns_iterations(flags, C)};
     int nb = 1;
+#define TRIINV_PICK_OP(PREFIX, NBV, ARG) \
+    (op_dtype == TRIINV_F32 ? PREFIX##NBV##_op0(ARG) : op_dtype == TRIINV_F16 ? PREFIX##NBV##_op1(ARG) : PREFIX##NBV##_op2(ARG))
     if (method == TRIINV_FWD_SUBST) {
-        nb = a.refine ? 1 : C == 64 ? launch_tri_inv_nb4_op0_fwd(a) : launch_tri_inv_nb8_op0_fwd(a);
+        nb = a.refine ? 1
+             : C == 16 ? launch_tri_inv_nb1_op0_fwd(a)
+             : C == 32 ? launch_tri_inv_nb2_op0_fwd(a)
+             : C == 64 ? launch_tri_inv_nb4_op0_fwd(a)
+                       : launch_tri_inv_nb8_op0_fwd(a);
+    } else if (C == 16) {
+        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 1, a);
+    } else if (C == 32) {
+        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 2, a);
     } else if (C == 64) {
-        nb = op_dtype == TRIINV_F32 ? launch_tri_inv_nb4_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb4_op1(a) : launch_tri_inv_nb4_op2(a);
+        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 4, a);
     } else {
-        nb = op_dtype == TRIINV_F32 ? launch_tri_inv_nb8_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb8_op1(a) : launch_tri_inv_nb8_op2(a);
+        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 8, a);
     }
+#undef TRIINV_PICK_OP
     return finish(nb);
 }
 
@@ -107,7 +117,7 @@ int tri_inv(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int met
 int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float* T, int B, int64_t Tlen, int H, int d_k,
                          int C, int k_dtype, int gate_kind, int method, int op_dtype, void* hip_stream, uint32_t flags)
 {
-    if (C != 64 && C != 128) return TRIINV_ERR_BAD_C;
+    if (!chunk_size_ok(C)) return TRIINV_ERR_BAD_C;
     if (!dtype_ok(k_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
     if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
     if (gate_kind < TRIINV_GATE_SCALAR || gate_kind > TRIINV_GATE_NONE) return TRIINV_ERR_BAD_METHOD;
@@ -132,7 +142,7 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
                              const int64_t* cu_chunks, int n_seq, int64_t total_tokens, int64_t total_chunks, int H, int d_k,
                              int C, int k_dtype, int gate_kind, int method, int op_dtype, void* hip_stream, uint32_t flags)
 {
-    if (C != 64 && C != 128) return TRIINV_ERR_BAD_C;
+    if (!chunk_size_ok(C)) return TRIINV_ERR_BAD_C;
     if (!dtype_ok(k_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
     if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
     if (gate_kind < TRIINV_GATE_SCALAR || gate_kind > TRIINV_GATE_NONE) return TRIINV_ERR_BAD_METHOD;
@@ -169,7 +179,7 @@ const char* triinv_status_string(int status)
     switch (status) {
     case TRIINV_OK: return "ok";
     case TRIINV_ERR_NULL: return "null pointer";
-    case TRIINV_ERR_BAD_C: return "C must be 64 or 128";
+    case TRIINV_ERR_BAD_C: return "C must be 16, 32, 64 or 128";
     case TRIINV_ERR_BAD_DTYPE: return "unknown element type";
     case TRIINV_ERR_BAD_METHOD: return "unknown method or gate kind";
     case TRIINV_ERR_BAD_SHAPE: return "bad shape";

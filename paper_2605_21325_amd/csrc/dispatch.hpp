@@ -41,6 +41,12 @@ struct GdnArgs {
     int launch_tri_inv_nb##NB##_op##OP(const TriInvArgs& a); \
     int launch_gdn_nb##NB##_op##OP(const GdnArgs& a);        \
     int launch_gdn_nb##NB##_op##OP##_fwd(const GdnArgs& a);
+TRIINV_DECL(1, 0)
+TRIINV_DECL(1, 1)
+TRIINV_DECL(1, 2)
+TRIINV_DECL(2, 0)
+TRIINV_DECL(2, 1)
+TRIINV_DECL(2, 2)
 TRIINV_DECL(4, 0)
 TRIINV_DECL(4, 1)
 TRIINV_DECL(4, 2)
@@ -48,6 +54,8 @@ TRIINV_DECL(8, 0)
 TRIINV_DECL(8, 1)
 TRIINV_DECL(8, 2)
 #undef TRIINV_DECL
+int launch_tri_inv_nb1_op0_fwd(const TriInvArgs& a);
+int launch_tri_inv_nb2_op0_fwd(const TriInvArgs& a);
 int launch_tri_inv_nb4_op0_fwd(const TriInvArgs& a);
 int launch_tri_inv_nb8_op0_fwd(const TriInvArgs& a);
 

@@ -6,7 +6,7 @@
 #include "kernels.hpp"
 
 #ifndef TRIINV_INST_NB
-#error "compile with -DTRIINV_INST_NB=4|8 -DTRIINV_INST_OP=0|1|2 [-DTRIINV_INST_FWD=1]"
+#error "compile with -DTRIINV_INST_NB=1|2|4|8 -DTRIINV_INST_OP=0|1|2 [-DTRIINV_INST_FWD=1]"
 #endif
 #ifndef TRIINV_INST_FWD
 #define TRIINV_INST_FWD 0
@@ -32,11 +32,11 @@ template <int METHOD, bool REFINE = false> static int go_tri(const TriInvArgs& a
     return 0;
 }
 
-// Fused matrix-core kernels at C = 64 run four matrices (adjacent heads) per workgroup.
-constexpr int WPB = (TRIINV_INST_NB == 4 && !TRIINV_INST_FWD) ? 4 : 1;
+// Fused matrix-core kernels at C <= 64 run four matrices (adjacent heads) per workgroup.
+constexpr int WPB = (TRIINV_INST_NB <= 4 && !TRIINV_INST_FWD) ? 4 : 1;
 
-// The refinement step is built for the blocked and the mixed recursion at C = 64.
-constexpr bool HAS_REFINE = (TRIINV_INST_NB == 4) && !TRIINV_INST_FWD;
+// The refinement step is built for the blocked and the mixed recursion at C <= 64.
+constexpr bool HAS_REFINE = (TRIINV_INST_NB <= 4) && !TRIINV_INST_FWD;
 
 #if !(TRIINV_INST_FWD && TRIINV_INST_OP != 0)
 int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const TriInvArgs& a)
@@ -55,11 +55,11 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);
     case M_BLOCK_DIRECT: return go_tri<M_BLOCK_DIRECT>(a);
-#if TRIINV_INST_NB == 4  // X in both orientations does not fit one wave's registers at C = 128
+#if TRIINV_INST_NB <= 4  // X in both orientations does not fit one wave's registers at C = 128
     case M_NEWTON_SCHULZ: return go_tri<M_NEWTON_SCHULZ>(a);
 #endif
     case M_NEUMANN:
-#if TRIINV_INST_NB == 4
+#if TRIINV_INST_NB <= 4
         return go_tri<M_NEUMANN>(a);
 #else   // C = 128: the one-wave register version would spill; a workgroup of four waves shares Y in LDS
         hipLaunchKernelGGL((k_tri_inv_neumann128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
@@ -105,11 +105,11 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
     case M_BLOCK_DIRECT: return go_gdn<KD, M_BLOCK_DIRECT, DKS>(a);
-#if TRIINV_INST_NB == 4
+#if TRIINV_INST_NB <= 4
     case M_NEWTON_SCHULZ: return go_gdn<KD, M_NEWTON_SCHULZ, DKS>(a);
 #endif
     case M_NEUMANN:
-#if TRIINV_INST_NB == 4
+#if TRIINV_INST_NB <= 4
         return go_gdn<KD, M_NEUMANN, DKS>(a);
 #else
         if constexpr (KD == OP_F32 && DKS == 8) {
@@ -142,10 +142,10 @@ static int kda_method(const GdnArgs& a)
     case M_BLOCK: return go_kda<M_BLOCK>(a);
     case M_MIXED: return go_kda<M_MIXED>(a);
     case M_BLOCK_DIRECT: return go_kda<M_BLOCK_DIRECT>(a);
-#if TRIINV_INST_NB == 4
+#if TRIINV_INST_NB <= 4
     case M_NEWTON_SCHULZ: return go_kda<M_NEWTON_SCHULZ>(a);
 #endif
-#if TRIINV_INST_NB == 4
+#if TRIINV_INST_NB <= 4
     case M_NEUMANN: return go_kda<M_NEUMANN>(a);
 #endif
 #endif

@@ -593,10 +593,12 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, f
 {
     constexpr int C = 16 * NB;
     constexpr int LD = C + 4;
+    constexpr int PASSES = C >= 64 ? C / 64 : 1;  // C < 64: one pass, lanes >= C idle along (they store nothing)
     const int lane = 16 * ln.q + ln.n;
 #pragma unroll
-    for (int p = 0; p < C / 64; ++p) {
+    for (int p = 0; p < PASSES; ++p) {
         const int c = 64 * p + lane;  // this lane's column
+        const bool mine = C >= 64 || c < C;
         float Tc[C];                  // Tc[k] = T[64p + k][c]
         if (p > 0) {
             // rows above this pass's diagonal block: columns >= 64p are zero there
@@ -628,7 +630,7 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, f
                 }
                 const float t = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
                 Tc[i - 64 * p] = t;
-                stream_store(t, Tm + (int64_t)i * C + c);
+                if (mine) stream_store(t, Tm + (int64_t)i * C + c);
             }
         }
     }

@@ -69,7 +69,7 @@ def test_tri_inv_argument_errors(L):
 
     assert call(n=0) == 0                       # empty batch: success, nothing launched
     assert call(n=0, A=None, T=None) == 0
-    assert call(C=32) == -2 and call(C=96) == -2 and call(C=0) == -2
+    assert call(C=48) == -2 and call(C=96) == -2 and call(C=0) == -2 and call(C=256) == -2
     assert call(dt=3) == -3 and call(op=-1) == -3
     assert call(m=6) == -4 and call(m=-1) == -4
     assert call(n=-1) == -5
@@ -125,7 +125,7 @@ def test_varlen_argument_errors(L):
                   a["C"], a["kd"], a["gate"], a["m"], a["op"], None, 0)
 
     assert call(tok=0, chunks=0) == 0               # nothing to do
-    assert call(C=32) == -2 and call(kd=7) == -3 and call(m=9) == -4 and call(gate=-1) == -4
+    assert call(C=48) == -2 and call(kd=7) == -3 and call(m=9) == -4 and call(gate=-1) == -4
     assert call(n_seq=0) == -5 and call(H=0) == -5 and call(d_k=40) == -5 and call(tok=-1) == -5
     assert call(chunks=3) == -5                     # 3 chunks of 64 cannot hold 200 tokens
     assert call(chunks=201) == -5                   # more chunks than tokens

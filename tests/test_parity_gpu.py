@@ -482,3 +482,45 @@ def test_packed_sequences_with_no_tokens_are_a_no_op():
     beta = torch.zeros((0, 2), device=DEV)
     T = tri.gdn_chunk_tri_inv_varlen(K, beta, None, [0, 0], 64, gate_kind=tri.GATE_NONE)
     assert T.shape == (0, 64, 64)
+
+
+# ------------------------------------------------------------------ the small chunk sizes, C = 16 and 32
+SMALL_C_METHODS = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in (tri.BLOCK_RECURSIVE, tri.BLOCK_DIRECT, tri.MIXED, tri.NEUMANN,
+                                                               tri.NEWTON_SCHULZ) for o in (tri.F32, tri.F16, tri.BF16)]
+
+
+@pytest.mark.parametrize("mo", SMALL_C_METHODS, ids=ids)
+@pytest.mark.parametrize("C", [16, 32])
+def test_small_chunk_sizes_standalone(C, mo):
+    method, op = mo
+    A = si.random_strict_lower(37, C, 0.15, seed=3)
+    T_ref = oracle.tri_inv(A)
+    T = tri.tri_inv_ex(A.to(DEV), method=method, op_dtype=op)
+    check(T, T_ref, TOL[op], f"standalone C={C} {ids(mo)}")
+
+
+@pytest.mark.parametrize("mo", SMALL_C_METHODS, ids=ids)
+@pytest.mark.parametrize("gate_kind", [0, 1, 2])
+@pytest.mark.parametrize("C", [16, 32])
+def test_small_chunk_sizes_fused(C, gate_kind, mo):
+    method, op = mo
+    idx = {0: 1, 1: 3, 2: 2}[gate_kind]
+    inp = si.make_inputs(si.workload(idx, B=2, Tlen=5 * C + 3, H=5, C=C, d_k=128, k_dtype="bf16", gate_kind=gate_kind))
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate_kind, method=method, op_dtype=op)
+    check(T, T_ref, TOL[op], f"fused C={C} gate={gate_kind} {ids(mo)}")
+
+
+@pytest.mark.parametrize("C", [16, 32])
+def test_small_chunk_sizes_refinement_and_other_head_dimensions(C):
+    inp = si.make_inputs(si.workload(1, B=1, Tlen=8 * C, H=3, C=C, d_k=96, k_dtype="f32"))
+    T_ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], 0, C)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    T = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32)   # channel-loop kernel
+    check(T, T_ref, 1e-5, f"C={C} d_k=96")
+    inp = si.make_inputs(si.workload(1, B=1, Tlen=8 * C, H=4, C=C, d_k=64, k_dtype="bf16"))
+    T_ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], 0, C)
+    T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), C, method=tri.MIXED, op_dtype=tri.BF16,
+                                 flags=tri.FLAG_REFINE1)
+    check(T, T_ref, 2e-2, f"C={C} mixed + refinement")
