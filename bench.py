@@ -58,6 +58,9 @@ def main() -> int:
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--accuracy", action="store_true",
+                    help="instead of timing: error and residual of every method / operand type against the oracle on "
+                         "sampled matrices of the full-size workload, fused entry point and (scalar / no gate) standalone")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run plain device copies of 1 GiB (reference for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -93,6 +96,61 @@ def main() -> int:
         T = torch.empty((n_mat, C, C), dtype=torch.float32, device=dev)
         sets.append((K, beta, g, T))
     torch.cuda.synchronize()
+
+    if args.accuracy:
+        import oracle
+        from oracle import metrics
+
+        rng = np.random.default_rng(2605)
+        sel = np.unique(np.concatenate([[0, n_mat - 1], rng.integers(0, n_mat, size=254)])).tolist()
+        A_ref = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, C, sel=sel)
+        T_ref = oracle.tri_inv(A_ref)
+        A32 = torch.from_numpy(A_ref.astype(np.float32)).to(dev)
+        T32_ref = oracle.tri_inv(A32.cpu())
+        A32_ref = A32.cpu().numpy().astype(np.float64)
+        K, beta, g, T = sets[0]
+        rows = []
+
+        def stats(Tg, Tr, Ar):
+            Tg = Tg.cpu().numpy().astype(np.float64)
+            e = metrics.forward_errors(Tr, Tg)
+            r = metrics.residual(Ar, Tg)
+            bad = int((~np.isfinite(e["rel_fro"])).sum())
+            with np.errstate(invalid="ignore"):
+                return {"rel_fro_max": float(np.nanmax(e["rel_fro"])) if bad < len(sel) else float("nan"),
+                        "rel_fro_median": float(np.nanmedian(e["rel_fro"])) if bad < len(sel) else float("nan"),
+                        "max_abs_max": float(np.nanmax(e["max_abs"])) if bad < len(sel) else float("nan"),
+                        "residual_abs_max": float(np.nanmax(r["abs"])) if bad < len(sel) else float("nan"),
+                        "residual_normalised_max": float(np.nanmax(r["normalised"])) if bad < len(sel) else float("nan"),
+                        "non_finite_matrices": bad, "structure_ok": bool(metrics.structure_ok(Tg))}
+
+        for method in (0, 1, 4, 3, 2, 5):
+            for op in (0, 1, 2):
+                if method == 0 and op != 0:
+                    continue
+                for flags, tag in ((0, ""), (tri.FLAG_REFINE1, "+refine")):
+                    if flags and method not in (1, 3):
+                        continue
+                    row = {"method": tri.METHOD_NAMES[method] + tag, "op": tri.DTYPE_NAMES[op]}
+                    try:
+                        tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=T, gate_kind=w.gate_kind, method=method, op_dtype=op, flags=flags)
+                        torch.cuda.synchronize()
+                        row["fused"] = stats(T[sel], T_ref, A_ref)
+                    except tri.TriInvError as e:
+                        row["fused"] = {"error": str(e)}
+                    try:
+                        Ts = tri.tri_inv_ex(A32, method=method, op_dtype=op, flags=flags)
+                        torch.cuda.synchronize()
+                        row["standalone"] = stats(Ts, T32_ref, A32_ref)
+                    except tri.TriInvError as e:
+                        row["standalone"] = {"error": str(e)}
+                    rows.append(row)
+        print(json.dumps({"accuracy": rows, "sampled_matrices": len(sel),
+                          "workload": f"configs[{w.index}] {w.name}: B={w.B} T={w.Tlen} H={w.H} d_k={w.d_k} C={w.C} -> {n_mat} matrices",
+                          "tolerances": {"f32": 1e-5, "f16": 2e-2, "bf16": 2e-2},
+                          "note": "fused: against the oracle on the stored keys; standalone: A built by the oracle in fp64, "
+                                  "stored fp32, inverted by tri_inv_ex and compared with the oracle on those stored values"}))
+        return 0
 
     def step(i: int, method: int, op: int):
         K, beta, g, T = sets[i % len(sets)]
