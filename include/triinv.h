@@ -46,8 +46,9 @@ typedef enum {
      * X <- I - A, Y <- A, then log2(C/2) times Y <- Y Y, X <- X + X Y.  Unstable: intermediate
      * powers may overflow / cancel; the result is returned as computed. */
     TRIINV_NEUMANN = 2,
-    /* Mixed recursion (paper Alg. 2, Sec. 3.4): Neumann product on the 16 x 16 diagonal blocks,
-     * then the blocked recursion from block size 16.  Log-stable. */
+    /* Mixed recursion (paper Alg. 2, Sec. 3.4): Neumann product on the 16 x 16 diagonal blocks, r steps
+     * of iterative refinement on those blocks (r = TRIINV_FLAG_MXR_R(r) in flags, default 1), then the
+     * blocked recursion from block size 16.  Log-stable. */
     TRIINV_MIXED = 3,
     /* Blocked recursion started at block size 16 (paper Alg. 4 with b0 = 16) from 16 x 16 diagonal
      * blocks inverted directly by forward substitution in fp32 (the stable direct method of
@@ -85,6 +86,9 @@ typedef enum {
                                     method (paper Alg. 6, Eq. 9).  Built for TRIINV_BLOCK_RECURSIVE and
                                     TRIINV_MIXED at C <= 64 (tri_inv and the scalar / no-gate fused
                                     kinds); anything else returns TRIINV_ERR_UNSUPPORTED */
+
+#define TRIINV_FLAG_MXR_R(r) ((((uint32_t)(r) + 1u) & 7u) << 16) /* refinement steps r = 0..6 inside TRIINV_MIXED
+                                                                 (paper Alg. 2); flags without it: r = 1 */
 
 #define TRIINV_FLAG_ITERS(n) (((uint32_t)(n) & 0xffu) << 8) /* iteration count of TRIINV_NEWTON_SCHULZ (0 = default) */
 

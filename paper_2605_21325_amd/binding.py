@@ -22,6 +22,11 @@ FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED, BLOCK_DIRECT, NEWTON_SCHULZ = 0, 1, 
 FLAG_REFINE1 = 0x1
 
 
+def flag_mxr_r(r: int) -> int:
+    """flags bits carrying the number of refinement steps inside the mixed recursion (default 1)."""
+    return ((int(r) + 1) & 7) << 16
+
+
 def flag_iters(n: int) -> int:
     """flags bits carrying the Newton-Schulz iteration count."""
     return (int(n) & 0xFF) << 8

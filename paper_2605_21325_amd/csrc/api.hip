@@ -19,12 +19,23 @@ bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_
 bool chunk_size_ok(int C) { return C == 16 || C == 32 || C == 64 || C == 128; }
 bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_NEWTON_SCHULZ; }
 
-constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | 0xff00u;
+constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | 0xff00u | 0x70000u;
 
 int ns_iterations(uint32_t flags, int C)
 {
     const int n = (int)((flags >> 8) & 0xffu);
     return n ? n : (C == 16 ? 8 : C == 32 ? 10 : C == 64 ? 12 : 14);  // 2 log2 C (paper Sec. 3.5; 12 at C = 64, Sec. 4.2)
+}
+// The run-time count a method takes: Newton-Schulz iterations, or the refinement steps the mixed
+// recursion applies to its 16 x 16 blocks (paper Alg. 2's r; default 1, the step the paper finds
+// necessary and sufficient for the mixed recursion to reach the accuracy of the stable methods, Sec. 4.1).
+int method_count(int method, uint32_t flags, int C)
+{
+    if (method == TRIINV_MIXED) {
+        const int code = (int)((flags >> 16) & 7u);
+        return code ? code - 1 : 1;
+    }
+    return ns_iterations(flags, C);
 }
 uint64_t esize(int d) { return d == TRIINV_F32 ? 4 : 2; }
 
@@ -86,7 +97,7 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
 
     TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0,
-                 ns_iterations(flags, C)};
+                 method_count(method, flags, C)};
     int nb = 1;
 #define TRIINV_PICK_OP(PREFIX, NBV, ARG) \
     (op_dtype == TRIINV_F32 ? PREFIX##NBV##_op0(ARG) : op_dtype == TRIINV_F16 ? PREFIX##NBV##_op1(ARG) : PREFIX##NBV##_op2(ARG))
@@ -134,7 +145,7 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
 
     const ChunkMap map{Tlen, (uint32_t)cps, 0u, nullptr, nullptr};
     GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, T, n_mat, n_chunk, map, H, d_k, k_dtype, gate_kind, method,
-              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, ns_iterations(flags, C)};
+              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, method_count(method, flags, C)};
     return launch_fused(a, C, op_dtype);
 }
 
@@ -164,7 +175,7 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
 
     const ChunkMap map{0, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
     GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, T, n_mat, total_chunks, map, H, d_k, k_dtype, gate_kind, method,
-              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, ns_iterations(flags, C)};
+              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, method_count(method, flags, C)};
     return launch_fused(a, C, op_dtype);
 }
 

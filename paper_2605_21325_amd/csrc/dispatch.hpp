@@ -15,7 +15,7 @@ struct TriInvArgs {
     int method;
     hipStream_t stream;
     bool refine;  // one iterative-refinement step after the method
-    int iters;    // Newton-Schulz iteration count
+    int iters;    // Newton-Schulz iteration count; for the mixed recursion: refinement steps on the 16 x 16 blocks
 };
 
 struct GdnArgs {

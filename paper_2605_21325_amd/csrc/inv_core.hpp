@@ -54,16 +54,20 @@ __device__ __forceinline__ void leaf_block_recursive(v4f LN, v4f LT, v4f& XN, v4
     }
 }
 
-// Neumann product on the leaf (paper Alg. 5 with n = 16: three squarings), both orientations.
+// Neumann product on the leaf (paper Alg. 5 with n = 16: three squarings), both orientations, followed
+// by r steps of iterative refinement on the leaf (paper Alg. 2: the refinement of the mixed recursion
+// acts on the b0 x b0 diagonal blocks, before the merges; Alg. 6 / Eq. 9 read for I + L):
+//   R <- I - Y (I + L) = I - Y - Y L;   Y <- Y + R Y.
 template <int OP>
-__device__ __forceinline__ void leaf_neumann(v4f LN, v4f LT, v4f& XN, v4f& XT, Lane ln)
+__device__ __forceinline__ void leaf_neumann(v4f LN, v4f LT, v4f& XN, v4f& XT, Lane ln, int r = 0)
 {
     v4f YN = LN, YT = LT;
+    v4f id;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const float id = (4 * ln.q + r == ln.n) ? 1.f : 0.f;
-        XN[r] = id - LN[r];
-        XT[r] = id - LT[r];
+    for (int e = 0; e < 4; ++e) {
+        id[e] = (4 * ln.q + e == ln.n) ? 1.f : 0.f;
+        XN[e] = id[e] - LN[e];
+        XT[e] = id[e] - LT[e];
     }
 #pragma unroll
     for (int it = 0; it < 3; ++it) {
@@ -73,6 +77,16 @@ __device__ __forceinline__ void leaf_neumann(v4f LN, v4f LT, v4f& XN, v4f& XT, L
         const Opnd<OP> Yn = pack<OP>(YN), XTo = pack<OP>(XT);
         const v4f XNn = tn<OP>(XTo, Yn, XN);                   // X + X Y
         XT = tn<OP>(Yn, XTo, XT);                              // (X + X Y)^T
+        XN = XNn;
+    }
+    const Opnd<OP> LNo = pack<OP>(LN);
+#pragma unroll 1
+    for (int s = 0; s < r; ++s) {
+        const Opnd<OP> Xn = pack<OP>(XN), Xt = pack<OP>(XT);
+        const v4f RT = id - XT - tn<OP>(LNo, Xt, zero4());     // R^T = I - X^T - L^T X^T
+        const Opnd<OP> Rt = pack<OP>(RT);
+        const v4f XNn = tn<OP>(Rt, Xn, XN);                    // X + R X
+        XT = tn<OP>(Xn, Rt, XT);                               // (X + R X)^T = X^T + X^T R^T
         XN = XNn;
     }
 }
@@ -174,7 +188,7 @@ __host__ __device__ constexpr bool result_is_T(int i, int j)
 enum : int { LEAF_BLOCK_RECURSIVE = 0, LEAF_NEUMANN = 1, LEAF_FORWARD = 2 };
 
 template <int OP, int NB, bool ROOT_T, int LEAF, class ASrc>
-__device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln)
+__device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln, int leaf_r = 0)
 {
     v4f leafN[NB], leafT[NB];
     if constexpr (LEAF == LEAF_FORWARD) {
@@ -186,7 +200,7 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
             if (LEAF == LEAF_BLOCK_RECURSIVE)
                 leaf_block_recursive<OP>(LN, LT, leafN[d], leafT[d], ln);
             else
-                leaf_neumann<OP>(LN, LT, leafN[d], leafT[d], ln);
+                leaf_neumann<OP>(LN, LT, leafN[d], leafT[d], ln, leaf_r);
         }
     }
 

@@ -706,7 +706,7 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, flo
     } else {
         v4f Tt[NT];
         constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : METHOD == M_BLOCK_DIRECT ? LEAF_FORWARD : LEAF_BLOCK_RECURSIVE;
-        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln);
+        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln, aux);  // aux = refinement steps on the leaves (mixed recursion)
         if constexpr (REFINE) {
             refine_once<OP, NB>(src, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, lds, ln);
             store_result<NB>(Tm, Tt, [](int, int) { return true; }, lds, ln);
