@@ -30,7 +30,7 @@ METRIC = "64x64 tri-inversions/sec + effective TFLOP/s & GB/s vs roofline; rel e
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
 # keyed by (workload index, method, op_dtype).  None = not measured for that configuration.
-MEASURED_TRAFFIC = {(2, 1, 2): 549.5e6, (3, 1, 2): 2160.3e6, (4, 1, 2): 819.7e6}
+MEASURED_TRAFFIC = {(2, 1, 2): 545.4e6, (3, 1, 2): 2149.9e6, (4, 1, 2): 809.9e6}
 
 
 def algorithmic_bytes_per_matrix(w, fused: bool, in_bytes: int = 4) -> int:
