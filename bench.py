@@ -305,8 +305,6 @@ def main() -> int:
             for op in (0, 1, 2):
                 if method == 0 and op != 0:
                     continue
-                if method == 5 and C != 64:
-                    continue
                 row = {"method": tri.METHOD_NAMES[method], "op": tri.DTYPE_NAMES[op]}
                 try:
                     _, km = timed(method, op, 10, 3)

@@ -56,7 +56,8 @@ typedef enum {
     TRIINV_BLOCK_DIRECT = 4,
     /* Newton-Schulz iteration (paper Alg. 3, Eq. 8): X <- I / C, then n times Y <- (I + A) X,
      * X <- 2X - XY.  n = TRIINV_FLAG_ITERS(n) in flags, default 12 (the count the paper finds
-     * sufficient at C = 64; 2 log2 C elsewhere).  Built for C <= 64. */
+     * sufficient at C = 64; 2 log2 C elsewhere).  At C = 128 not built for the per-channel gate
+     * and for fp32 keys with d_k = 128. */
     TRIINV_NEWTON_SCHULZ = 5
 } triinv_method;
 

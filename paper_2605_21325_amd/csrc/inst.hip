@@ -55,8 +55,12 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);
     case M_BLOCK_DIRECT: return go_tri<M_BLOCK_DIRECT>(a);
-#if TRIINV_INST_NB <= 4  // X in both orientations does not fit one wave's registers at C = 128
-    case M_NEWTON_SCHULZ: return go_tri<M_NEWTON_SCHULZ>(a);
+    case M_NEWTON_SCHULZ:
+#if TRIINV_INST_NB <= 4
+        return go_tri<M_NEWTON_SCHULZ>(a);
+#else   // X in both orientations does not fit one wave's registers at C = 128: four waves, X and Y in LDS
+        hipLaunchKernelGGL((k_tri_inv_ns128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.iters);
+        return 0;
 #endif
     case M_NEUMANN:
 #if TRIINV_INST_NB <= 4
@@ -105,8 +109,17 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
     case M_BLOCK_DIRECT: return go_gdn<KD, M_BLOCK_DIRECT, DKS>(a);
+    case M_NEWTON_SCHULZ:
 #if TRIINV_INST_NB <= 4
-    case M_NEWTON_SCHULZ: return go_gdn<KD, M_NEWTON_SCHULZ, DKS>(a);
+        return go_gdn<KD, M_NEWTON_SCHULZ, DKS>(a);
+#else
+        if constexpr (KD == OP_F32 && DKS == 8) {
+            return 1;  // 128 fp32 channels x 128 rows of keys per wave do not fit the register file
+        } else {
+            hipLaunchKernelGGL((k_gdn_tri_inv_ns128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K, a.beta,
+                               a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters);
+            return 0;
+        }
 #endif
     case M_NEUMANN:
 #if TRIINV_INST_NB <= 4

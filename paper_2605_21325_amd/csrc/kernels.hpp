@@ -982,6 +982,118 @@ __device__ __forceinline__ void neumann_c128_workgroup(const ASrc& A, float* Tm,
     TRIINV_PER_WAVE(w, (n128_store<W>(Tm, Xt, Y + w * STORE_LDS_FLOATS, ln)))
 }
 
+// ---------------------------------------------------------------------------------------------
+// Newton-Schulz at C = 128 (paper Alg. 3, Eq. 8, for I + A): the same four-wavefront workgroup.
+//   X <- I / C;  n_iter times:  Y <- X + A X;  X <- 2 X - X Y.
+// X and Y live in LDS as 36 fp32 tiles each (N orientation; 92 KB together, one workgroup per compute
+// unit); wave w owns tile rows w and 7 - w: it keeps its rows of A (T orientation, packed operands) and of
+// X (both orientations, fp32) in registers and reads the other factor of every product from LDS.
+// ---------------------------------------------------------------------------------------------
+constexpr int NS128_LDS_FLOATS = 2 * N128_LDS_FLOATS;
+
+template <int W> __host__ __device__ constexpr int n128_slot(int i, int k) { return i == W ? k : (W + 1) + k; }
+
+template <int OP, int W, class ASrc>
+__device__ __forceinline__ void ns128_run(const ASrc& A, float* Tm, float* X, float* Y, Lane ln, int n_iter, int w)
+{
+    Opnd<OP> At[9];
+    v4f Xn[9], Xt[9];
+#pragma unroll
+    for (int s = 0; s < 9; ++s) {
+        const int i = n128_row<W>(s), j = n128_col<W>(s);
+        At[s] = pack<OP>(A.template get<true>(i, j));
+        v4f x;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = (i == j && 4 * ln.q + r == ln.n) ? 1.f / 128.f : 0.f;
+        Xn[s] = x;
+        Xt[s] = x;
+        lds_tile_write_n(X + tix(i, j) * XPOSE_FLOATS, x, ln);
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < n_iter; ++it) {
+        // Y(i,j) = X(i,j) + sum_k A(i,k) X(k,j) on this wave's rows
+#pragma unroll
+        for (int s = 0; s < 9; ++s) {
+            const int i = n128_row<W>(s), j = n128_col<W>(s);
+            v4f acc = Xn[s];
+#pragma unroll
+            for (int k = 0; k < N128_NB; ++k) {
+                if (k < j || k > i) continue;
+                acc = tn<OP>(At[n128_slot<W>(i, k)], pack<OP>(lds_tile_read_n(X + tix(k, j) * XPOSE_FLOATS, ln)), acc);
+            }
+            lds_tile_write_n(Y + tix(i, j) * XPOSE_FLOATS, acc, ln);
+        }
+        __syncthreads();  // Y complete; nobody reads X from LDS any more in this iteration
+        // X(i,j) <- 2 X(i,j) - sum_k X(i,k) Y(k,j), both orientations; the packed old row first
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int i = half == 0 ? W : 7 - W, s0 = half == 0 ? 0 : W + 1;
+            Opnd<OP> xo[N128_NB];
+#pragma unroll
+            for (int k = 0; k < N128_NB; ++k)
+                if (k <= i) xo[k] = pack<OP>(Xt[s0 + k]);
+#pragma unroll
+            for (int j = 0; j < N128_NB; ++j) {
+                if (j > i) continue;
+                v4f pn = zero4(), pt = zero4();
+#pragma unroll
+                for (int k = 0; k < N128_NB; ++k) {
+                    if (k < j || k > i) continue;
+                    const Opnd<OP> y = pack<OP>(lds_tile_read_n(Y + tix(k, j) * XPOSE_FLOATS, ln));
+                    pn = tn<OP>(xo[k], y, pn);
+                    pt = tn<OP>(y, xo[k], pt);
+                }
+                Xn[s0 + j] = 2.f * Xn[s0 + j] - pn;
+                Xt[s0 + j] = 2.f * Xt[s0 + j] - pt;
+                lds_tile_write_n(X + tix(i, j) * XPOSE_FLOATS, Xn[s0 + j], ln);
+            }
+        }
+        __syncthreads();  // X complete; nobody reads Y any more
+    }
+    n128_store<W>(Tm, Xt, Y + w * STORE_LDS_FLOATS, ln);  // Y is dead: its memory becomes the four store patches
+}
+
+template <int OP>
+__global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt,
+                                                       int n_iter)
+{
+    __shared__ __attribute__((aligned(16))) float XY[NS128_LDS_FLOATS];
+    const int64_t m = blockIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Lane ln = lane_id();
+    GlobalA<N128_NB> src;
+    src.base = static_cast<const char*>(A) + m * 128 * 128 * (in_dt == OP_F32 ? 4 : 2);
+    src.dt = in_dt;
+    src.ln = ln;
+    (void)n_mat;
+    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, T + m * 128 * 128, XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
+}
+
+template <int KD, int OP, int DKS>
+__global__ __launch_bounds__(256) void k_gdn_tri_inv_ns128(const void* __restrict__ K, const float* __restrict__ beta,
+                                                           const float* __restrict__ g, float* __restrict__ T,
+                                                           int64_t n_chunk, ChunkMap map, int H, int d_k, int n_iter)
+{
+    constexpr int C = 128;
+    __shared__ __attribute__((aligned(16))) float XY[NS128_LDS_FLOATS];
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Lane ln = lane_id();
+    GramA<KD, N128_NB, DKS> src;
+    src.ln = ln;
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
+    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
+    src.stage_gate(XY + w * 2 * C);  // a private 2 * C floats inside the (not yet used) X buffer
+    __syncthreads();
+    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, T + m * C * C, XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
+}
+
 template <int OP>
 __global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt)
 {

@@ -294,6 +294,41 @@ def test_newton_schulz(cases, op):
     check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), oracle.tri_inv(A32), TOL[op], "NS stress blocks")
 
 
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+def test_newton_schulz_c128(op, capsys):
+    """Alg. 3 at C = 128 (four wavefronts per matrix, X and Y in LDS): 14 = 2 log2 C iterations reach the
+    tolerance on benign inputs, standalone, fused (scalar gate and none) and with a short last chunk; the
+    iteration count flag is honoured; the stress workload is reported."""
+    inp = si.make_inputs(si.workload(1, Tlen=128 * 3 + 40, H=3, C=128))
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 0, 128)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    check(tri.gdn_chunk_tri_inv_ex(K, beta, g, 128, method=tri.NEWTON_SCHULZ, op_dtype=op), T_ref, TOL[op], "NS C=128 fused")
+    T_ref2 = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], None, 2, 128)
+    check(tri.gdn_chunk_tri_inv_ex(K, beta, None, 128, gate_kind=tri.GATE_NONE, method=tri.NEWTON_SCHULZ, op_dtype=op), T_ref2,
+          TOL[op], "NS C=128 fused, no gate")
+    A = oracle.build_A_ragged(inp["K"], inp["beta"], inp["g"], 0, 128)
+    A32 = torch.from_numpy(A.astype(np.float32))
+    T32 = oracle.tri_inv(A32)
+    check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), T32, TOL[op], "NS C=128 standalone")
+    few = tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op, flags=tri.flag_iters(5)).cpu().numpy()
+    e_few = metrics.forward_errors(T32, few.astype(np.float64))["rel_fro"].max()
+    assert e_few > 1e-1, "five iterations cannot have converged from X0 = I / 128"
+    if op == tri.F32:
+        from oracle import methods
+        low = np.tril(np.ones((128, 128), dtype=bool), -1)
+        want = np.stack([methods.ns(A32[i].numpy().astype(np.float64), m=5) for i in range(3)])
+        assert np.allclose(few[:3][:, low], want[:, low], rtol=2e-4, atol=2e-6)
+    # stress workload: reported, not asserted (X0 = I / C need not converge in 2 log2 C steps when ||A|| is large)
+    st = si.make_inputs(si.workload(4, Tlen=512, H=3))
+    Ts = oracle.gdn_chunk_tri_inv(st["K"], st["beta"], None, 2, 128)
+    Tg = tri.gdn_chunk_tri_inv_ex(st["K"].to(DEV), st["beta"].to(DEV), None, 128, gate_kind=tri.GATE_NONE,
+                                  method=tri.NEWTON_SCHULZ, op_dtype=op)
+    torch.cuda.synchronize()
+    e = metrics.forward_errors(Ts, Tg.cpu().numpy().astype(np.float64))["rel_fro"]
+    with capsys.disabled():
+        print(f"\nnewton_schulz {tri.DTYPE_NAMES[op]} on stress C=128, 14 iterations: rel_fro max {np.nanmax(e):.3e}")
+
+
 def test_newton_schulz_iteration_count(cases):
     """Fewer iterations leave the iteration unconverged (paper Sec. 4.2: 6 iterations are markedly worse than
     12); the error after m iterations follows the fp64 statement of Alg. 3 in exact arithmetic."""
@@ -329,8 +364,10 @@ def test_unbuilt_combinations_report_unsupported(cases):
         with pytest.raises(tri.TriInvError) as e:
             tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), op_dtype=tri.F32, **kw)
         assert e.value.status == -9
-    with pytest.raises(tri.TriInvError) as e:   # Newton-Schulz is not built at C = 128
-        tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.NEWTON_SCHULZ, op_dtype=tri.F32)
+    with pytest.raises(tri.TriInvError) as e:   # Newton-Schulz with the per-channel gate is not built at C = 128
+        tri.gdn_chunk_tri_inv_ex(torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV), torch.zeros(1, 128, 2, device=DEV),
+                                 torch.zeros(1, 128, 2, 128, device=DEV), 128, gate_kind=tri.GATE_PER_CHANNEL,
+                                 method=tri.NEWTON_SCHULZ)
     assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:   # refinement is not built at C = 128
         tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.MIXED, op_dtype=tri.F32, flags=1)
