@@ -33,9 +33,9 @@ METRIC = "64x64 tri-inversions/sec + effective TFLOP/s & GB/s vs roofline; rel e
 MEASURED_TRAFFIC = {(2, 1, 2): 545.4e6, (3, 1, 2): 2149.9e6, (4, 1, 2): 809.9e6}
 
 
-def algorithmic_bytes_per_matrix(w, fused: bool, in_bytes: int = 4) -> int:
+def algorithmic_bytes_per_matrix(w, fused: bool, in_bytes: int = 4, out_bytes: int = 4) -> int:
     C, d = w.C, w.d_k
-    out = 4 * C * C
+    out = out_bytes * C * C
     if not fused:
         return in_bytes * C * (C - 1) // 2 + out          # strictly-lower A in, dense fp32 T out
     kb = 2 if w.k_dtype == "bf16" else 4
@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--method", type=int, default=1, help="0 fwd, 1 block recursive, 2 neumann, 3 mixed, 4 block direct")
     ap.add_argument("--op", type=int, default=2, help="operand type: 0 f32, 1 f16, 2 bf16")
+    ap.add_argument("--out", default="f32", choices=["f32", "f16", "bf16"],
+                    help="element type of T (the contract's fp32, or a 16-bit result: TRIINV_FLAG_OUT_*)")
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -85,6 +87,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    out_torch = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.out]
+    out_bytes = 4 if args.out == "f32" else 2
     w = si.WORKLOADS[args.workload]
     inp = si.make_inputs(w)
     n_mat, C = w.n_mat, w.C
@@ -93,7 +97,7 @@ def main() -> int:
         K = inp["K"].to(dev)
         beta = inp["beta"].to(dev)
         g = None if inp["g"] is None else inp["g"].to(dev)
-        T = torch.empty((n_mat, C, C), dtype=torch.float32, device=dev)
+        T = torch.empty((n_mat, C, C), dtype=out_torch, device=dev)
         sets.append((K, beta, g, T))
     torch.cuda.synchronize()
 
@@ -112,7 +116,7 @@ def main() -> int:
         rows = []
 
         def stats(Tg, Tr, Ar):
-            Tg = Tg.cpu().numpy().astype(np.float64)
+            Tg = Tg.float().cpu().numpy().astype(np.float64)
             e = metrics.forward_errors(Tr, Tg)
             r = metrics.residual(Ar, Tg)
             bad = int((~np.isfinite(e["rel_fro"])).sum())
@@ -192,7 +196,7 @@ def main() -> int:
     wall, avg_kernel_ms = timed(args.method, args.op, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps
     value = n_mat * args.steps / wall
-    bytes_per_launch = algorithmic_bytes_per_matrix(w, fused=True) * n_mat
+    bytes_per_launch = algorithmic_bytes_per_matrix(w, fused=True, out_bytes=out_bytes) * n_mat
     achieved = bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
     flops_inv = C ** 3 / 3.0
     flops_gram = C * C * w.d_k
@@ -231,11 +235,11 @@ def main() -> int:
     rng = np.random.default_rng(12345)
     sel = np.unique(np.concatenate([[0, n_mat - 1], rng.integers(0, n_mat, size=62)])).tolist()
     T_ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, C, sel=sel)
-    T_gpu = sets[(args.steps - 1) % len(sets)][3][sel].cpu().numpy().astype(np.float64)
+    T_gpu = sets[(args.steps - 1) % len(sets)][3][sel].float().cpu().numpy().astype(np.float64)
     err = metrics.forward_errors(T_ref, T_gpu)["rel_fro"]
     A_ref = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, C, sel=sel)
     res = metrics.residual(A_ref, T_gpu)["normalised"]
-    tol = 1e-5 if (args.op == 0 or args.method == 0) else 2e-2
+    tol = (1e-5 if (args.op == 0 or args.method == 0) else 2e-2) + {"f32": 0.0, "f16": 2.0 ** -11, "bf16": 2.0 ** -8}[args.out]
     parity = {"sampled_matrices": len(sel), "rel_fro_max": float(np.max(err)), "residual_max": float(np.max(res)),
               "tolerance": tol, "ok": bool(np.max(err) <= tol and metrics.structure_ok(T_gpu))}
 
@@ -268,7 +272,7 @@ def main() -> int:
         "config": {"workload": f"configs[{w.index}] {w.name}: B={w.B} T={w.Tlen} H={w.H} d_k={w.d_k} C={w.C} "
                                f"-> {n_mat} matrices, fused gdn_chunk_tri_inv_ex",
                    "method": tri.METHOD_NAMES[args.method], "op_dtype": tri.DTYPE_NAMES[args.op],
-                   "k_dtype": w.k_dtype, "buffer_sets": len(sets)},
+                   "k_dtype": w.k_dtype, "out_dtype": args.out, "buffer_sets": len(sets)},
         "effective": {"GBps": achieved, "TFLOPs_inversion": flops_inv * n_mat / (avg_kernel_ms * 1e-3) / 1e12,
                       "TFLOPs_with_gram": (flops_inv + flops_gram) * n_mat / (avg_kernel_ms * 1e-3) / 1e12,
                       "kernel_ms_avg": avg_kernel_ms,
@@ -276,7 +280,7 @@ def main() -> int:
                       "device_copy_same_bytes_GBps": copy_gbps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((w.index, args.method, args.op))},
+                     "traffic": MEASURED_TRAFFIC.get((w.index, args.method, args.op)) if args.out == "f32" else None},
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }

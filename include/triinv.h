@@ -17,8 +17,8 @@
  *     returns at once; the return value reports argument / launch errors only;
  *   - the return value is TRIINV_OK (0) or a negative triinv_status; argument errors are
  *     detected on the host before anything is launched, so a failing call does no GPU work;
- *   - T is always fp32, dense row-major [n_mat][C][C], completely overwritten: exact 0.0f
- *     above the diagonal and exact 1.0f on it;
+ *   - T is dense row-major [n_mat][C][C], fp32 unless a TRIINV_FLAG_OUT_* bit asks for a 16-bit
+ *     result, completely overwritten: exact 0 above the diagonal and exact 1 on it;
  *   - non-finite input values are not errors; they propagate inside their own matrix only.
  */
 #ifndef TRIINV_H
@@ -87,6 +87,11 @@ typedef enum {
                                     method (paper Alg. 6, Eq. 9).  Built for TRIINV_BLOCK_RECURSIVE and
                                     TRIINV_MIXED at C <= 64 (tri_inv and the scalar / no-gate fused
                                     kinds); anything else returns TRIINV_ERR_UNSUPPORTED */
+
+#define TRIINV_FLAG_OUT_F16 0x2u  /* T holds fp16 elements: [n_mat][C][C], 2 bytes each (pass the buffer as float*) */
+#define TRIINV_FLAG_OUT_BF16 0x4u /* T holds bf16 elements.  The fp32 result is rounded to nearest even on the way
+                                     out; the diagonal is still exactly 1, the upper triangle exactly 0.  Not
+                                     built for TRIINV_FWD_SUBST; both flags at once: TRIINV_ERR_BAD_DTYPE */
 
 #define TRIINV_FLAG_MXR_R(r) ((((uint32_t)(r) + 1u) & 7u) << 16) /* refinement steps r = 0..6 inside TRIINV_MIXED
                                                                  (paper Alg. 2); flags without it: r = 1 */

@@ -20,6 +20,8 @@ LIB_PATH = os.path.join(HERE, "libtriinv.so")
 F32, F16, BF16 = 0, 1, 2
 FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED, BLOCK_DIRECT, NEWTON_SCHULZ = 0, 1, 2, 3, 4, 5
 FLAG_REFINE1 = 0x1
+FLAG_OUT_F16 = 0x2
+FLAG_OUT_BF16 = 0x4
 
 
 def flag_mxr_r(r: int) -> int:
@@ -119,11 +121,25 @@ def tri_inv(A: torch.Tensor, T: Optional[torch.Tensor] = None, method: int = BLO
     return T
 
 
-def tri_inv_ex(A: torch.Tensor, T: Optional[torch.Tensor] = None, method: int = BLOCK_RECURSIVE,
-               op_dtype: Optional[int] = None, stream=None, flags: int = 0) -> torch.Tensor:
-    n_mat, C, _ = A.shape
+_OUT_FLAG = {torch.float32: 0, torch.float16: FLAG_OUT_F16, torch.bfloat16: FLAG_OUT_BF16}
+
+
+def _out(T: Optional[torch.Tensor], out_dtype: Optional[torch.dtype], shape, device, flags: int):
+    """The output tensor (allocated if not given) and flags with the TRIINV_FLAG_OUT_* bit of its element type."""
     if T is None:
-        T = torch.empty((n_mat, C, C), dtype=torch.float32, device=A.device)
+        T = torch.empty(shape, dtype=out_dtype or torch.float32, device=device)
+    elif out_dtype is not None and T.dtype != out_dtype:
+        raise TypeError(f"T is {T.dtype}, out_dtype asks for {out_dtype}")
+    if T.dtype not in _OUT_FLAG:
+        raise TypeError(f"unsupported output dtype {T.dtype}")
+    return T, (flags & ~(FLAG_OUT_F16 | FLAG_OUT_BF16)) | _OUT_FLAG[T.dtype]
+
+
+def tri_inv_ex(A: torch.Tensor, T: Optional[torch.Tensor] = None, method: int = BLOCK_RECURSIVE,
+               op_dtype: Optional[int] = None, stream=None, flags: int = 0,
+               out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    n_mat, C, _ = A.shape
+    T, flags = _out(T, out_dtype, (n_mat, C, C), A.device, flags)
     in_dt = dtype_code(A.dtype)
     st = lib().tri_inv_ex(_dev(A, "A"), _dev(T, "T"), n_mat, C, in_dt, method,
                           in_dt if op_dtype is None else op_dtype, _stream_ptr(stream), flags)
@@ -154,10 +170,10 @@ def gdn_chunk_tri_inv(K: torch.Tensor, beta: torch.Tensor, g: torch.Tensor, C: i
 
 def gdn_chunk_tri_inv_ex(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], C: int,
                          T: Optional[torch.Tensor] = None, gate_kind: int = GATE_SCALAR,
-                         method: int = BLOCK_RECURSIVE, op_dtype: int = BF16, stream=None, flags: int = 0) -> torch.Tensor:
+                         method: int = BLOCK_RECURSIVE, op_dtype: int = BF16, stream=None, flags: int = 0,
+                         out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
     B, Tlen, H, d_k = K.shape
-    if T is None:
-        T = torch.empty((_n_mat(K, C), C, C), dtype=torch.float32, device=K.device)
+    T, flags = _out(T, out_dtype, (_n_mat(K, C), C, C), K.device, flags)
     gp = None if g is None else _dev(g, "g")
     st = lib().gdn_chunk_tri_inv_ex(_dev(K, "K"), _dev(beta, "beta"), gp, _dev(T, "T"), B, Tlen, H, d_k, C,
                                     dtype_code(K.dtype), gate_kind, method, op_dtype, _stream_ptr(stream), flags)
@@ -179,7 +195,8 @@ def varlen_chunk_offsets(seqlens, C: int):
 
 def gdn_chunk_tri_inv_varlen(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], seqlens, C: int,
                              T: Optional[torch.Tensor] = None, gate_kind: int = GATE_SCALAR,
-                             method: int = BLOCK_RECURSIVE, op_dtype: int = BF16, stream=None, flags: int = 0) -> torch.Tensor:
+                             method: int = BLOCK_RECURSIVE, op_dtype: int = BF16, stream=None, flags: int = 0,
+                             out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
     """Fused build + invert on packed variable-length sequences: K [total_tokens, H, d_k], beta
     [total_tokens, H], g [total_tokens, H] (or [total_tokens, H, d_k]); seqlens = host sequence of lengths."""
     total, H, d_k = K.shape
@@ -188,8 +205,7 @@ def gdn_chunk_tri_inv_varlen(K: torch.Tensor, beta: torch.Tensor, g: Optional[to
         raise ValueError(f"sequence lengths sum to {cu_s[-1]}, K holds {total} tokens")
     cu_seqlens = torch.tensor(cu_s, dtype=torch.int64, device=K.device)
     cu_chunks = torch.tensor(cu_c, dtype=torch.int64, device=K.device)
-    if T is None:
-        T = torch.empty((cu_c[-1] * H, C, C), dtype=torch.float32, device=K.device)
+    T, flags = _out(T, out_dtype, (cu_c[-1] * H, C, C), K.device, flags)
     gp = None if g is None else _dev(g, "g")
     st = lib().gdn_chunk_tri_inv_varlen(_dev(K, "K"), _dev(beta, "beta"), gp, _dev(T, "T") if T.numel() else None,
                                         cu_seqlens.data_ptr(), cu_chunks.data_ptr(), len(cu_s) - 1, total, cu_c[-1], H, d_k, C,

@@ -19,7 +19,7 @@ bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_
 bool chunk_size_ok(int C) { return C == 16 || C == 32 || C == 64 || C == 128; }
 bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_NEWTON_SCHULZ; }
 
-constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | 0xff00u | 0x70000u;
+constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | TRIINV_FLAG_OUT_F16 | TRIINV_FLAG_OUT_BF16 | 0xff00u | 0x70000u;
 
 int ns_iterations(uint32_t flags, int C)
 {
@@ -38,6 +38,13 @@ int method_count(int method, uint32_t flags, int C)
     return ns_iterations(flags, C);
 }
 uint64_t esize(int d) { return d == TRIINV_F32 ? 4 : 2; }
+
+// Element type of T asked for in flags; -1 when both 16-bit types are asked for at once.
+int out_dtype(uint32_t flags)
+{
+    const bool h = (flags & TRIINV_FLAG_OUT_F16) != 0, b = (flags & TRIINV_FLAG_OUT_BF16) != 0;
+    return (h && b) ? -1 : h ? TRIINV_F16 : b ? TRIINV_BF16 : TRIINV_F32;
+}
 
 int finish(int not_built)
 {
@@ -64,15 +71,18 @@ int launch_fused(const GdnArgs& a, int C, int op_dtype)
 
 // Checks common to both token layouts.  n_tok = number of (token, head) pairs, n_mat = matrices to write.
 int check_fused(const void* K, const float* beta, const float* g, float* T, uint64_t n_tok, int64_t n_mat, int H, int d_k,
-                       int C, int k_dtype, int gate_kind, uint32_t flags)
+                       int C, int k_dtype, int gate_kind, int method, uint32_t flags)
 {
+    const int out_dt = out_dtype(flags);
+    if (out_dt < 0) return TRIINV_ERR_BAD_DTYPE;
     const bool need_g = gate_kind != TRIINV_GATE_NONE;
     if (!K || !beta || !T || (need_g && !g)) return TRIINV_ERR_NULL;
     if (!aligned16(K) || !aligned16(beta) || !aligned16(T) || (need_g && !aligned16(g))) return TRIINV_ERR_ALIGN;
-    const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4;
+    const uint64_t t_bytes = (uint64_t)n_mat * C * C * esize(out_dt);
     if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
+    if (method == TRIINV_FWD_SUBST && out_dt != TRIINV_F32) return TRIINV_ERR_UNSUPPORTED;
     (void)H;
     return TRIINV_OK;
 }
@@ -91,13 +101,16 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     if (n_mat == 0) return TRIINV_OK;
     if (!A || !T) return TRIINV_ERR_NULL;
     if (!aligned16(A) || !aligned16(T)) return TRIINV_ERR_ALIGN;
+    const int out_dt = out_dtype(flags);
+    if (out_dt < 0) return TRIINV_ERR_BAD_DTYPE;
     const uint64_t n_el = (uint64_t)n_mat * C * C;
-    if (overlap(A, n_el * esize(in_dtype), T, n_el * 4)) return TRIINV_ERR_ALIAS;
+    if (overlap(A, n_el * esize(in_dtype), T, n_el * esize(out_dt))) return TRIINV_ERR_ALIAS;
     if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
+    if (method == TRIINV_FWD_SUBST && out_dt != TRIINV_F32) return TRIINV_ERR_UNSUPPORTED;  // stores element by element
     if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
 
     TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0,
-                 method_count(method, flags, C)};
+                 method_count(method, flags, C), out_dt};
     int nb = 1;
 #define TRIINV_PICK_OP(PREFIX, NBV, ARG) \
     (op_dtype == TRIINV_F32 ? PREFIX##NBV##_op0(ARG) : op_dtype == TRIINV_F16 ? PREFIX##NBV##_op1(ARG) : PREFIX##NBV##_op2(ARG))
@@ -139,13 +152,13 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
     if (n_chunk > 0x7fffffffLL / H) return TRIINV_ERR_BAD_SHAPE;
     const int64_t n_mat = n_chunk * H;
     if (n_mat == 0) return TRIINV_OK;
-    const int st = check_fused(K, beta, g, T, (uint64_t)B * Tlen * H, n_mat, H, d_k, C, k_dtype, gate_kind, flags);
+    const int st = check_fused(K, beta, g, T, (uint64_t)B * Tlen * H, n_mat, H, d_k, C, k_dtype, gate_kind, method, flags);
     if (st != TRIINV_OK) return st;
     if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
 
     const ChunkMap map{Tlen, (uint32_t)cps, 0u, nullptr, nullptr};
     GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, T, n_mat, n_chunk, map, H, d_k, k_dtype, gate_kind, method,
-              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, method_count(method, flags, C)};
+              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, method_count(method, flags, C), out_dtype(flags)};
     return launch_fused(a, C, op_dtype);
 }
 
@@ -167,15 +180,15 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
     if (n_mat == 0) return TRIINV_OK;
     if (!cu_seqlens || !cu_chunks) return TRIINV_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(cu_seqlens) & 7u) || (reinterpret_cast<uintptr_t>(cu_chunks) & 7u)) return TRIINV_ERR_ALIGN;
-    const int st = check_fused(K, beta, g, T, (uint64_t)total_tokens * H, n_mat, H, d_k, C, k_dtype, gate_kind, flags);
+    const int st = check_fused(K, beta, g, T, (uint64_t)total_tokens * H, n_mat, H, d_k, C, k_dtype, gate_kind, method, flags);
     if (st != TRIINV_OK) return st;
-    const uint64_t t_bytes = (uint64_t)n_mat * C * C * 4, cu_bytes = (uint64_t)(n_seq + 1) * 8;
+    const uint64_t t_bytes = (uint64_t)n_mat * C * C * esize(out_dtype(flags)), cu_bytes = (uint64_t)(n_seq + 1) * 8;
     if (overlap(cu_seqlens, cu_bytes, T, t_bytes) || overlap(cu_chunks, cu_bytes, T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
 
     const ChunkMap map{0, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
     GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, T, n_mat, total_chunks, map, H, d_k, k_dtype, gate_kind, method,
-              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, method_count(method, flags, C)};
+              static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, method_count(method, flags, C), out_dtype(flags)};
     return launch_fused(a, C, op_dtype);
 }
 

@@ -16,6 +16,7 @@ struct TriInvArgs {
     hipStream_t stream;
     bool refine;  // one iterative-refinement step after the method
     int iters;    // Newton-Schulz iteration count; for the mixed recursion: refinement steps on the 16 x 16 blocks
+    int out_dt;   // element type of T: 0 fp32, 1 fp16, 2 bf16
 };
 
 struct GdnArgs {
@@ -34,6 +35,7 @@ struct GdnArgs {
     hipStream_t stream;
     bool refine;
     int iters;
+    int out_dt;
 };
 
 // Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.

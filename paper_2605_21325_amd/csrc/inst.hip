@@ -28,7 +28,7 @@ constexpr int OP = TRIINV_INST_OP;
 template <int METHOD, bool REFINE = false> static int go_tri(const TriInvArgs& a)
 {
     hipLaunchKernelGGL((k_tri_inv<OP, NB, METHOD, REFINE>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat,
-                       a.in_dt, a.iters);
+                       a.in_dt, a.iters, a.out_dt);
     return 0;
 }
 
@@ -59,14 +59,14 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 #if TRIINV_INST_NB <= 4
         return go_tri<M_NEWTON_SCHULZ>(a);
 #else   // X in both orientations does not fit one wave's registers at C = 128: four waves, X and Y in LDS
-        hipLaunchKernelGGL((k_tri_inv_ns128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.iters);
+        hipLaunchKernelGGL((k_tri_inv_ns128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.iters, a.out_dt);
         return 0;
 #endif
     case M_NEUMANN:
 #if TRIINV_INST_NB <= 4
         return go_tri<M_NEUMANN>(a);
 #else   // C = 128: the one-wave register version would spill; a workgroup of four waves shares Y in LDS
-        hipLaunchKernelGGL((k_tri_inv_neumann128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
+        hipLaunchKernelGGL((k_tri_inv_neumann128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.out_dt);
         return 0;
 #endif
 #endif
@@ -89,7 +89,7 @@ template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(co
 {
     hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
                        dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
-                       a.iters);
+                       a.iters, a.out_dt);
     return 0;
 }
 
@@ -117,7 +117,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
             return 1;  // 128 fp32 channels x 128 rows of keys per wave do not fit the register file
         } else {
             hipLaunchKernelGGL((k_gdn_tri_inv_ns128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K, a.beta,
-                               a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters);
+                               a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
             return 0;
         }
 #endif
@@ -129,7 +129,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
             return 1;  // 128 fp32 channels x 128 rows of keys per wave do not fit the register file
         } else {
             hipLaunchKernelGGL((k_gdn_tri_inv_neumann128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
-                               a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
+                               a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.out_dt);
             return 0;
         }
 #endif
@@ -141,7 +141,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 template <int METHOD> static int go_kda(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
-                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters);
+                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt);
     return 0;
 }
 
@@ -171,7 +171,7 @@ static int kda_method(const GdnArgs& a)
 template <int KD, int METHOD> static int go_any_dk(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_gdn_any_dk_tri_inv<KD, OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
-                       a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
+                       a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.out_dt);
     return 0;
 }
 

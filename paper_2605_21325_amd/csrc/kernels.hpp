@@ -507,9 +507,23 @@ __device__ __forceinline__ void build_A_scalar_any_dk(PreA<NB>& out, const void*
 // forward substitution keep the plain non-temporal hint (partial lines written through measured slower).
 constexpr int CACHE_SC0_SC1_NT = 1 | 2 | 16;  // gfx950 buffer-instruction cache-policy bits: sc0, nt, sc1
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_buffer(float* Tm, int C)
+// One output matrix: its first byte and its element type (OP_F32, or OP_F16 / OP_BF16 when the caller
+// asked for a 16-bit result: the fp32 values are rounded to nearest even on the way out).
+struct Out {
+    void* base;
+    int dt;
+};
+__device__ __forceinline__ Out out_matrix(float* T, int64_t m, int C, int out_dt)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(Tm, 0, C * C * 4, 0x00020000);  // raw buffer, 32-bit data format
+    return Out{reinterpret_cast<char*>(T) + m * C * C * (out_dt == OP_F32 ? 4 : 2), out_dt};
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_buffer(Out Tm, int C)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(Tm.base, 0, C * C * (Tm.dt == OP_F32 ? 4 : 2), 0x00020000);  // raw buffer
+}
+__device__ __forceinline__ void stream_store(v4u v, __amdgpu_buffer_rsrc_t out, int byte_offset)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, out, byte_offset, 0, CACHE_SC0_SC1_NT);
 }
 __device__ __forceinline__ void stream_store(v4f v, __amdgpu_buffer_rsrc_t out, int byte_offset)
 {
@@ -522,7 +536,7 @@ constexpr int STORE_LDS_FLOATS = 16 * STORE_LD;
 
 // One strip: tiles (i, 0..i) in row[0..i], tile j in T orientation when row_is_t(j).
 template <int NB, class RowIsT>
-__device__ __forceinline__ void store_strip(float* Tm, int i, const v4f (&row)[NB], RowIsT row_is_t, float* lds, Lane ln)
+__device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB], RowIsT row_is_t, float* lds, Lane ln)
 {
     constexpr int C = 16 * NB;
     const int lane = 16 * ln.q + ln.n;
@@ -551,21 +565,38 @@ __device__ __forceinline__ void store_strip(float* Tm, int i, const v4f (&row)[N
         }
     }
     wave_lds_sync();
-    // rows 16i .. 16i+15, C floats each: C/4 lanes per row, 256/C rows per instruction
-    constexpr int LPR = C / 4, RPI = 64 / LPR;
+    if (Tm.dt == OP_F32) {
+        // rows 16i .. 16i+15, C floats each: C/4 lanes per row, 256/C rows per instruction
+        constexpr int LPR = C / 4, RPI = 64 / LPR;
 #pragma unroll
-    for (int k = 0; k < 16 / RPI; ++k) {
-        const int rr = RPI * k + lane / LPR, cc = 4 * (lane % LPR);
-        // unconditional read (columns right of the diagonal tile hold stale patch contents), then a select
-        v4f v = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc]);
-        if (cc >= 16 * (i + 1)) v = zero4();
-        stream_store(v, out, ((16 * i + rr) * C + cc) * 4);
+        for (int k = 0; k < 16 / RPI; ++k) {
+            const int rr = RPI * k + lane / LPR, cc = 4 * (lane % LPR);
+            // unconditional read (columns right of the diagonal tile hold stale patch contents), then a select
+            v4f v = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc]);
+            if (cc >= 16 * (i + 1)) v = zero4();
+            stream_store(v, out, ((16 * i + rr) * C + cc) * 4);
+        }
+    } else {
+        // 16-bit result: 8 elements (16 bytes) per lane, C/8 lanes per row
+        constexpr int LPR = C / 8, RPI = 64 / LPR, ITER = RPI >= 16 ? 1 : 16 / RPI;
+#pragma unroll
+        for (int k = 0; k < ITER; ++k) {
+            const int rr = RPI * k + lane / LPR, cc = 8 * (lane % LPR);
+            if (RPI > 16 && rr >= 16) continue;  // C = 16: more lanes than the strip has 16-byte pieces
+            v4f a = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc]);
+            v4f b = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc + 4]);
+            if (cc >= 16 * (i + 1)) a = zero4();
+            if (cc + 4 >= 16 * (i + 1)) b = zero4();
+            const v4u p = Tm.dt == OP_F16 ? v4u{pack2_f16(a[0], a[1]), pack2_f16(a[2], a[3]), pack2_f16(b[0], b[1]), pack2_f16(b[2], b[3])}
+                                          : v4u{pack2_bf16(a[0], a[1]), pack2_bf16(a[2], a[3]), pack2_bf16(b[0], b[1]), pack2_bf16(b[2], b[3])};
+            stream_store(p, out, ((16 * i + rr) * C + cc) * 2);
+        }
     }
     wave_lds_sync();
 }
 
 template <int NB, class IsT>
-__device__ __forceinline__ void store_result(float* Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln)
+__device__ __forceinline__ void store_result(Out Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln)
 {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
@@ -687,14 +718,14 @@ template <int NB> constexpr int gate_lds_floats() { return 2 * 16 * NB; }
 
 // REFINE: one iterative-refinement step after a matrix-product method (C = 64 only).
 template <int OP, int NB, int METHOD, class ASrc, bool REFINE = false>
-__device__ __forceinline__ void invert_and_store(const ASrc& src, float* Tm, float* lds, Lane ln, int aux = 0)
+__device__ __forceinline__ void invert_and_store(const ASrc& src, Out Tm, float* lds, Lane ln, int aux = 0)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     if (METHOD == M_FWD) {
         if constexpr (NB == 8 && !ASrc::kFromMemory)
-            forward_substitution_resident<NB>(src, Tm, lds, ln);
+            forward_substitution_resident<NB>(src, static_cast<float*>(Tm.base), lds, ln);  // fp32 result only (checked by the host)
         else
-            forward_substitution<NB>(src, Tm, lds, ln);
+            forward_substitution<NB>(src, static_cast<float*>(Tm.base), lds, ln);
     } else if (METHOD == M_NEWTON_SCHULZ) {
         v4f Xt[NT];
         newton_schulz<OP, NB>(src, Xt, aux, ln);  // aux = number of iterations
@@ -724,7 +755,7 @@ template <int NB, int METHOD, bool FUSED = false> constexpr int core_lds_floats(
 
 template <int OP, int NB, int METHOD, bool REFINE = false>
 __global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt,
-                                                int aux)
+                                                int aux, int out_dt)
 {
     constexpr int C = 16 * NB;
     __shared__ __attribute__((aligned(16))) float lds[core_lds_floats<NB, METHOD>()];
@@ -735,7 +766,7 @@ __global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, floa
     src.base = static_cast<const char*>(A) + m * C * C * (in_dt == OP_F32 ? 4 : 2);
     src.dt = in_dt;
     src.ln = ln;
-    invert_and_store<OP, NB, METHOD, GlobalA<NB>, REFINE>(src, T + m * C * C, lds, ln, aux);
+    invert_and_store<OP, NB, METHOD, GlobalA<NB>, REFINE>(src, out_matrix(T, m, C, out_dt), lds, ln, aux);
 }
 
 // Workgroup -> matrix map of the fused kernels.  Workgroups are handed to the 8 XCDs round-robin
@@ -768,7 +799,7 @@ __device__ __forceinline__ int64_t fused_matrix_index(int64_t n_chunk, int H, in
 template <int KD, int OP, int NB, int METHOD, int DKS, bool REFINE = false, int WPB = 1>
 __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T,
-                                                          int64_t n_chunk, ChunkMap map, int H, int d_k, int aux)
+                                                          int64_t n_chunk, ChunkMap map, int H, int d_k, int aux, int out_dt)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
@@ -789,14 +820,14 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict
     src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
     src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
     src.stage_gate(lds);
-    invert_and_store<OP, NB, METHOD, GramA<KD, NB, DKS>, REFINE>(src, T + m * C * C, lds, ln, aux);
+    invert_and_store<OP, NB, METHOD, GramA<KD, NB, DKS>, REFINE>(src, out_matrix(T, m, C, out_dt), lds, ln, aux);
 }
 
 // Fused kernel of the scalar / no-gate kinds for head dimensions without a specialised build.
 template <int KD, int OP, int NB, int METHOD>
 __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                            const float* __restrict__ g, float* __restrict__ T,
-                                                           int64_t n_chunk, ChunkMap map, int H, int d_k)
+                                                           int64_t n_chunk, ChunkMap map, int H, int d_k, int out_dt)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
@@ -813,14 +844,14 @@ __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restric
     build_A_scalar_any_dk<KD, NB, METHOD>(src, static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz,
                                           (int64_t)H * d_k, beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, d_k, lds, ln,
                                           pos.valid);
-    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, T + m * C * C, lds, ln, 0);
+    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, out_matrix(T, m, C, out_dt), lds, ln, 0);
 }
 
 // Fused kernel for the per-channel gate: g is [B, Tlen, H, d_k]; the gated keys are rounded to OP.
 template <int OP, int NB, int METHOD, int WPB = 1>
 __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T,
-                                                          int64_t n_chunk, ChunkMap map, int H, int d_k, int k_dt, int aux)
+                                                          int64_t n_chunk, ChunkMap map, int H, int d_k, int k_dt, int aux, int out_dt)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
@@ -839,7 +870,7 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict
     PreA<NB> src;
     build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
                                         beta + tok0 * H + h, H, d_k, lds, ln, pos.valid);
-    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, T + m * C * C, lds, ln, aux);
+    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, out_matrix(T, m, C, out_dt), lds, ln, aux);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -941,7 +972,7 @@ __device__ __forceinline__ void n128_update_x(v4f (&Xt)[9], const float* Y, int 
 }
 
 template <int W>
-__device__ __forceinline__ void n128_store(float* Tm, const v4f (&Xt)[9], float* patch, Lane ln)
+__device__ __forceinline__ void n128_store(Out Tm, const v4f (&Xt)[9], float* patch, Lane ln)
 {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
@@ -963,7 +994,7 @@ __device__ __forceinline__ void n128_store(float* Tm, const v4f (&Xt)[9], float*
     }
 
 template <int OP, class ASrc>
-__device__ __forceinline__ void neumann_c128_workgroup(const ASrc& A, float* Tm, float* Y, Lane ln, int w)
+__device__ __forceinline__ void neumann_c128_workgroup(const ASrc& A, Out Tm, float* Y, Lane ln, int w)
 {
     v4f Xt[9];
     TRIINV_PER_WAVE(w, (n128_init<OP, W>(A, Xt, Y, ln)))
@@ -994,7 +1025,7 @@ constexpr int NS128_LDS_FLOATS = 2 * N128_LDS_FLOATS;
 template <int W> __host__ __device__ constexpr int n128_slot(int i, int k) { return i == W ? k : (W + 1) + k; }
 
 template <int OP, int W, class ASrc>
-__device__ __forceinline__ void ns128_run(const ASrc& A, float* Tm, float* X, float* Y, Lane ln, int n_iter, int w)
+__device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float* Y, Lane ln, int n_iter, int w)
 {
     Opnd<OP> At[9];
     v4f Xn[9], Xt[9];
@@ -1056,7 +1087,7 @@ __device__ __forceinline__ void ns128_run(const ASrc& A, float* Tm, float* X, fl
 
 template <int OP>
 __global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt,
-                                                       int n_iter)
+                                                       int n_iter, int out_dt)
 {
     __shared__ __attribute__((aligned(16))) float XY[NS128_LDS_FLOATS];
     const int64_t m = blockIdx.x;
@@ -1067,13 +1098,13 @@ __global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* __restrict__ 
     src.dt = in_dt;
     src.ln = ln;
     (void)n_mat;
-    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, T + m * 128 * 128, XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
+    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, out_matrix(T, m, 128, out_dt), XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
 }
 
 template <int KD, int OP, int DKS>
 __global__ __launch_bounds__(256) void k_gdn_tri_inv_ns128(const void* __restrict__ K, const float* __restrict__ beta,
                                                            const float* __restrict__ g, float* __restrict__ T,
-                                                           int64_t n_chunk, ChunkMap map, int H, int d_k, int n_iter)
+                                                           int64_t n_chunk, ChunkMap map, int H, int d_k, int n_iter, int out_dt)
 {
     constexpr int C = 128;
     __shared__ __attribute__((aligned(16))) float XY[NS128_LDS_FLOATS];
@@ -1091,11 +1122,11 @@ __global__ __launch_bounds__(256) void k_gdn_tri_inv_ns128(const void* __restric
     src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
     src.stage_gate(XY + w * 2 * C);  // a private 2 * C floats inside the (not yet used) X buffer
     __syncthreads();
-    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, T + m * C * C, XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
+    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, out_matrix(T, m, C, out_dt), XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
 }
 
 template <int OP>
-__global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt)
+__global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt, int out_dt)
 {
     __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
     const int64_t m = blockIdx.x;
@@ -1106,13 +1137,13 @@ __global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* __restri
     src.dt = in_dt;
     src.ln = ln;
     (void)n_mat;
-    neumann_c128_workgroup<OP>(src, T + m * 128 * 128, Y, ln, w);
+    neumann_c128_workgroup<OP>(src, out_matrix(T, m, 128, out_dt), Y, ln, w);
 }
 
 template <int KD, int OP, int DKS>
 __global__ __launch_bounds__(256) void k_gdn_tri_inv_neumann128(const void* __restrict__ K, const float* __restrict__ beta,
                                                                 const float* __restrict__ g, float* __restrict__ T,
-                                                                int64_t n_chunk, ChunkMap map, int H, int d_k)
+                                                                int64_t n_chunk, ChunkMap map, int H, int d_k, int out_dt)
 {
     constexpr int C = 128;
     __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
@@ -1131,7 +1162,7 @@ __global__ __launch_bounds__(256) void k_gdn_tri_inv_neumann128(const void* __re
     // every wave stages beta / g for itself: a private 2 * C floats inside the (not yet used) Y buffer
     src.stage_gate(Y + w * 2 * C);
     __syncthreads();
-    neumann_c128_workgroup<OP>(src, T + m * C * C, Y, ln, w);
+    neumann_c128_workgroup<OP>(src, out_matrix(T, m, C, out_dt), Y, ln, w);
 }
 
 }  // namespace triinv

@@ -360,7 +360,7 @@ def test_unbuilt_combinations_report_unsupported(cases):
     with pytest.raises(tri.TriInvError) as e:
         tri.gdn_chunk_tri_inv_ex(K96, b, b, 64, method=tri.MIXED)
     assert e.value.status == -9
-    for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=2), dict(method=tri.FWD_SUBST, flags=1), dict(method=tri.NEUMANN, flags=1)):
+    for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=8), dict(method=tri.FWD_SUBST, flags=1), dict(method=tri.NEUMANN, flags=1)):
         with pytest.raises(tri.TriInvError) as e:
             tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), op_dtype=tri.F32, **kw)
         assert e.value.status == -9
@@ -575,3 +575,50 @@ def test_small_chunk_sizes_refinement_and_other_head_dimensions(C):
     T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), C, method=tri.MIXED, op_dtype=tri.BF16,
                                  flags=tri.FLAG_REFINE1)
     check(T, T_ref, 2e-2, f"C={C} mixed + refinement")
+
+
+# ------------------------------------------------------------------ 16-bit result
+OUT_U = {torch.float16: 2.0 ** -11, torch.bfloat16: 2.0 ** -8}   # unit roundoff of the result's type
+
+
+@pytest.mark.parametrize("out", [torch.float16, torch.bfloat16], ids=["out_f16", "out_bf16"])
+@pytest.mark.parametrize("C", [16, 32, 64, 128])
+def test_sixteen_bit_result(C, out):
+    """TRIINV_FLAG_OUT_*: the fp32 result rounded to nearest even on the way out; bit-exact against the
+    fp32-output run of the same method rounded by torch; inside tolerance + one rounding against the oracle."""
+    inp = si.make_inputs(si.workload(1, B=2, Tlen=3 * C + 7, H=5, C=C))
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 0, C)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    for method, op in [(tri.BLOCK_RECURSIVE, tri.BF16), (tri.MIXED, tri.F16), (tri.BLOCK_DIRECT, tri.F32), (tri.NEUMANN, tri.F32),
+                       (tri.NEWTON_SCHULZ, tri.F32)]:
+        n_mat = T_ref.shape[0]
+        guard = torch.full((n_mat + 1, C, C), 7.0, device=DEV, dtype=out)
+        tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=guard[:n_mat], method=method, op_dtype=op)
+        T32 = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, method=method, op_dtype=op)
+        torch.cuda.synchronize()
+        assert bool((guard[n_mat] == 7.0).all()), "wrote past the last matrix"
+        assert torch.equal(guard[:n_mat], T32.to(out)), f"C={C} {ids((method, op))}: not the rounded fp32 result"
+        check(guard[:n_mat].float(), T_ref, TOL[op] + OUT_U[out], f"16-bit out C={C} {ids((method, op))}")
+    # standalone entry point and the per-channel gate
+    A32 = torch.from_numpy(oracle.build_A_ragged(inp["K"], inp["beta"], inp["g"], 0, C).astype(np.float32)).to(DEV)
+    Ts = tri.tri_inv_ex(A32, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32, out_dtype=out)
+    assert Ts.dtype == out
+    check(Ts.float(), oracle.tri_inv(A32.cpu()), 1e-5 + OUT_U[out], f"16-bit out standalone C={C}")
+    inp3 = si.make_inputs(si.workload(3, B=1, Tlen=2 * C + 5, H=3, C=C))
+    T3 = tri.gdn_chunk_tri_inv_ex(inp3["K"].to(DEV), inp3["beta"].to(DEV), inp3["g"].to(DEV), C, gate_kind=tri.GATE_PER_CHANNEL,
+                                  out_dtype=out)
+    check(T3.float(), oracle.gdn_chunk_tri_inv_ragged(inp3["K"], inp3["beta"], inp3["g"], 1, C), 2e-2 + OUT_U[out],
+          f"16-bit out per-channel C={C}")
+
+
+def test_sixteen_bit_result_argument_errors():
+    A = torch.zeros(2, 64, 64, device=DEV)
+    with pytest.raises(tri.TriInvError) as e:     # forward substitution stores element by element: fp32 only
+        tri.tri_inv_ex(A, method=tri.FWD_SUBST, out_dtype=torch.bfloat16)
+    assert e.value.status == -9
+    with pytest.raises(tri.TriInvError) as e:     # both output types at once
+        tri.lib()  # loaded
+        T = torch.zeros(2, 64, 64, device=DEV)
+        st = tri.lib().tri_inv_ex(A.data_ptr(), T.data_ptr(), 2, 64, 0, 1, 0, None, 0x2 | 0x4)
+        raise tri.TriInvError(st, "both")
+    assert e.value.status == -3
