@@ -334,6 +334,21 @@ def main() -> int:
                     except tri.TriInvError as e:
                         row["standalone_error"] = str(e)
                 table.append(row)
+                if method == 0 and C == 64 and A32 is not None:
+                    # the same baseline with A broadcast by wavefront shuffles instead of through LDS (standalone only)
+                    Ts = [s[3] for s in sets]
+                    for i in range(3):
+                        tri.tri_inv_ex(A32s[i % len(Ts)], T=Ts[i % len(Ts)], method=0, flags=tri.FLAG_FWD_SHUFFLE)
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for i in range(10):
+                        tri.tri_inv_ex(A32s[i % len(Ts)], T=Ts[i % len(Ts)], method=0, flags=tri.FLAG_FWD_SHUFFLE)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms = e0.elapsed_time(e1) / 10
+                    table.append({"method": "fwd_subst_shuffle", "op": "f32", "standalone_matrices_per_s": n_mat / (ms * 1e-3),
+                                  "standalone_GBps": algorithmic_bytes_per_matrix(w, False) * n_mat / (ms * 1e-3) / 1e9})
         out["methods"] = table
 
     print(json.dumps(out))

@@ -93,6 +93,9 @@ typedef enum {
                                      out; the diagonal is still exactly 1, the upper triangle exactly 0.  Not
                                      built for TRIINV_FWD_SUBST; both flags at once: TRIINV_ERR_BAD_DTYPE */
 
+#define TRIINV_FLAG_FWD_SHUFFLE 0x8u /* tri_inv_ex, TRIINV_FWD_SUBST, C = 64: broadcast the entries of A with wavefront
+                                       shuffles instead of through LDS (the plain shuffle baseline; slower) */
+
 #define TRIINV_FLAG_MXR_R(r) ((((uint32_t)(r) + 1u) & 7u) << 16) /* refinement steps r = 0..6 inside TRIINV_MIXED
                                                                  (paper Alg. 2); flags without it: r = 1 */
 

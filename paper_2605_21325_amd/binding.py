@@ -22,6 +22,7 @@ FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED, BLOCK_DIRECT, NEWTON_SCHULZ = 0, 1, 
 FLAG_REFINE1 = 0x1
 FLAG_OUT_F16 = 0x2
 FLAG_OUT_BF16 = 0x4
+FLAG_FWD_SHUFFLE = 0x8
 
 
 def flag_mxr_r(r: int) -> int:

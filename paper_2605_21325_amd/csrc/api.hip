@@ -19,7 +19,7 @@ bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_
 bool chunk_size_ok(int C) { return C == 16 || C == 32 || C == 64 || C == 128; }
 bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_NEWTON_SCHULZ; }
 
-constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | TRIINV_FLAG_OUT_F16 | TRIINV_FLAG_OUT_BF16 | 0xff00u | 0x70000u;
+constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | TRIINV_FLAG_OUT_F16 | TRIINV_FLAG_OUT_BF16 | TRIINV_FLAG_FWD_SHUFFLE | 0xff00u | 0x70000u;
 
 int ns_iterations(uint32_t flags, int C)
 {
@@ -82,6 +82,7 @@ int check_fused(const void* K, const float* beta, const float* g, float* T, uint
     if (overlap(K, n_tok * d_k * esize(k_dtype), T, t_bytes) || overlap(beta, n_tok * 4, T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
+    if (flags & TRIINV_FLAG_FWD_SHUFFLE) return TRIINV_ERR_UNSUPPORTED;  // a variant of the standalone entry point
     if (method == TRIINV_FWD_SUBST && out_dt != TRIINV_F32) return TRIINV_ERR_UNSUPPORTED;
     (void)H;
     return TRIINV_OK;
@@ -110,7 +111,8 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
 
     TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0,
-                 method_count(method, flags, C), out_dt};
+                 method_count(method, flags, C), out_dt, (flags & TRIINV_FLAG_FWD_SHUFFLE) != 0};
+    if (a.shuffle && method != TRIINV_FWD_SUBST) return TRIINV_ERR_UNSUPPORTED;
     int nb = 1;
 #define TRIINV_PICK_OP(PREFIX, NBV, ARG) \
     (op_dtype == TRIINV_F32 ? PREFIX##NBV##_op0(ARG) : op_dtype == TRIINV_F16 ? PREFIX##NBV##_op1(ARG) : PREFIX##NBV##_op2(ARG))

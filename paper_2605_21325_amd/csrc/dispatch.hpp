@@ -17,6 +17,7 @@ struct TriInvArgs {
     bool refine;  // one iterative-refinement step after the method
     int iters;    // Newton-Schulz iteration count; for the mixed recursion: refinement steps on the 16 x 16 blocks
     int out_dt;   // element type of T: 0 fp32, 1 fp16, 2 bf16
+    bool shuffle; // forward substitution: broadcast A by wavefront shuffles (C = 64)
 };
 
 struct GdnArgs {

@@ -50,7 +50,16 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
     }
     switch (a.method) {
 #if TRIINV_INST_FWD
-    case M_FWD: return go_tri<M_FWD>(a);
+    case M_FWD:
+        if (a.shuffle) {
+#if TRIINV_INST_NB == 4
+            hipLaunchKernelGGL((k_tri_inv_fwd_shuffle64<0>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
+            return 0;
+#else
+            return 1;  // the shuffle variant is built at C = 64
+#endif
+        }
+        return go_tri<M_FWD>(a);
 #else
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);

@@ -667,6 +667,52 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, float* Tm, f
     }
 }
 
+// Forward substitution at C = 64 with the row of A broadcast by wavefront shuffles instead of LDS: lane l
+// holds A[i][l] of every row i (one coalesced 256-byte load per row, all 63 issued up front) and
+// T[:, l]; A[i][j] reaches every lane through a v_readlane of lane j.  One shuffle per multiply-add
+// makes this variant issue about twice the vector instructions of the LDS-broadcast form above
+// (measured: see the benchmark table); it is kept as the plain shuffle baseline.
+__device__ __forceinline__ void forward_substitution_shuffle64(const void* Am, int in_dt, float* Tm, Lane ln)
+{
+    constexpr int C = 64;
+    const int c = 16 * ln.q + ln.n;
+    float a[C];  // a[i] = A[i][c] for c < i, else 0
+#pragma unroll
+    for (int i = 1; i < C; ++i) {
+        float v;
+        if (in_dt == OP_F32) {
+            v = static_cast<const float*>(Am)[i * C + c];
+        } else {
+            const uint16_t u = static_cast<const uint16_t*>(Am)[i * C + c];
+            v = in_dt == OP_F16 ? f16_to_f32(u) : bf16_to_f32(u);
+        }
+        a[i] = c < i ? v : 0.f;
+    }
+    float Tc[C];
+    Tc[0] = c == 0 ? 1.f : 0.f;
+    stream_store(Tc[0], Tm + c);
+#pragma unroll
+    for (int i = 1; i < C; ++i) {
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < i; ++j) {
+            const float aij = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[i]), j));
+            acc += aij * Tc[j];
+        }
+        Tc[i] = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
+        stream_store(Tc[i], Tm + i * C + c);
+    }
+}
+
+template <int UNUSED = 0>  // a template only so that the header may define it in every translation unit
+__global__ __launch_bounds__(64) void k_tri_inv_fwd_shuffle64(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt)
+{
+    const int64_t m = blockIdx.x;
+    if (m >= n_mat) return;
+    forward_substitution_shuffle64(static_cast<const char*>(A) + m * 64 * 64 * (in_dt == OP_F32 ? 4 : 2), in_dt, T + m * 64 * 64,
+                                   lane_id());
+}
+
 // The same substitution with all of A resident in LDS (tile-packed, 1 KB per lower tile): used at
 // C = 128 when the tiles come out of registers (Gram products), so that the key registers and the
 // tile registers are free before the 128 running values of T take theirs.

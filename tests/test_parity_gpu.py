@@ -360,7 +360,7 @@ def test_unbuilt_combinations_report_unsupported(cases):
     with pytest.raises(tri.TriInvError) as e:
         tri.gdn_chunk_tri_inv_ex(K96, b, b, 64, method=tri.MIXED)
     assert e.value.status == -9
-    for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=8), dict(method=tri.FWD_SUBST, flags=1), dict(method=tri.NEUMANN, flags=1)):
+    for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=0x80), dict(method=tri.BLOCK_RECURSIVE, flags=8), dict(method=tri.FWD_SUBST, flags=1), dict(method=tri.NEUMANN, flags=1)):
         with pytest.raises(tri.TriInvError) as e:
             tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), op_dtype=tri.F32, **kw)
         assert e.value.status == -9
@@ -622,3 +622,17 @@ def test_sixteen_bit_result_argument_errors():
         st = tri.lib().tri_inv_ex(A.data_ptr(), T.data_ptr(), 2, 64, 0, 1, 0, None, 0x2 | 0x4)
         raise tri.TriInvError(st, "both")
     assert e.value.status == -3
+
+
+# ------------------------------------------------------------------ forward substitution by wavefront shuffles
+@pytest.mark.parametrize("dt", [torch.float32, torch.float16, torch.bfloat16])
+def test_forward_substitution_shuffle_variant(cases, dt):
+    A = torch.from_numpy(cases[2]["A"].astype(np.float32)).to(dt)
+    T_ref = oracle.tri_inv(A)
+    T = tri.tri_inv_ex(A.to(DEV), method=tri.FWD_SUBST, op_dtype=tri.F32, flags=tri.FLAG_FWD_SHUFFLE)
+    check(T, T_ref, 1e-5, f"fwd shuffle {dt}")
+    junk = si.random_strict_lower(5, 64, 0.2, seed=9)                    # NaN / garbage on and above the diagonal
+    check(tri.tri_inv_ex(junk.to(DEV), method=tri.FWD_SUBST, flags=tri.FLAG_FWD_SHUFFLE), oracle.tri_inv(junk), 1e-5, "fwd shuffle, junk upper")
+    with pytest.raises(tri.TriInvError) as e:
+        tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.FWD_SUBST, flags=tri.FLAG_FWD_SHUFFLE)
+    assert e.value.status == -9
