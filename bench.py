@@ -214,6 +214,19 @@ def main() -> int:
         torch.cuda.synchronize()
         if i >= 5:
             cold_ms.append(a.elapsed_time(b))
+    # the same with the cache cleared by READING 512 MiB instead (the caches then hold clean lines of an unrelated
+    # buffer; after a fill they hold 256 MB of dirty lines whose write-back is charged to the timed launch)
+    cold_clean_ms = []
+    for i in range(25):
+        sink = flush.sum()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        step(i, args.method, args.op)
+        b.record()
+        torch.cuda.synchronize()
+        if i >= 5:
+            cold_clean_ms.append(a.elapsed_time(b))
+    del sink
     # plain device-to-device copy of the same volume, same event timing: the practical HBM ceiling
     src_c = torch.empty(bytes_per_launch // 8, dtype=torch.float32, device=dev).normal_()
     dst_c = torch.empty_like(src_c)
@@ -277,6 +290,8 @@ def main() -> int:
                       "TFLOPs_with_gram": (flops_inv + flops_gram) * n_mat / (avg_kernel_ms * 1e-3) / 1e12,
                       "kernel_ms_avg": avg_kernel_ms,
                       "cold_cache_ms_median": float(np.median(cold_ms)), "cold_cache_ms_min": float(np.min(cold_ms)),
+                      "cold_cache_read_flush_ms_median": float(np.median(cold_clean_ms)),
+                      "cold_cache_read_flush_ms_min": float(np.min(cold_clean_ms)),
                       "device_copy_same_bytes_GBps": copy_gbps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
