@@ -1,8 +1,15 @@
-// Kernels: one 64-lane wavefront (= one workgroup) per chunk matrix.
-//   k_tri_inv      A given in global memory          -> T
-//   k_gdn_tri_inv  K, beta, g -> Gram on MFMA, gate  -> T      (A never leaves the registers)
-// Methods: forward substitution (fp32 VALU, A broadcast through LDS), blocked recursion,
-// Neumann product, mixed recursion (MFMA, see inv_core.hpp).
+// Kernels.  One 64-lane wavefront inverts one chunk matrix (C = 16 * NB) entirely in registers:
+//   k_tri_inv             A given in global memory                          -> T
+//   k_gdn_tri_inv         K, beta, g -> Gram on the matrix cores, scalar gate -> T   (A never leaves the registers;
+//                         four wavefronts = four adjacent heads per workgroup at C <= 64)
+//   k_kda_tri_inv         per-channel gate: gated keys contracted 32 channels at a time
+//   k_gdn_any_dk_tri_inv  head dimensions without a specialised build (channel loop)
+//   k_tri_inv_fwd_shuffle64  forward substitution with wavefront shuffles (baseline variant)
+// and, at C = 128, four wavefronts per matrix with tiles in LDS for the methods whose state does not fit
+// one wavefront: k_*_neumann128 (Neumann product), k_*_ns128 (Newton-Schulz).
+// Methods: forward substitution (fp32 vector arithmetic, A broadcast through LDS), blocked recursion, mixed
+// recursion, blocked recursion from directly solved blocks, Neumann product, Newton-Schulz, refinement
+// (inv_core.hpp).  csrc/chunk_map.hpp says where a chunk's tokens are.
 #pragma once
 #include "chunk_map.hpp"
 #include "inv_core.hpp"
