@@ -46,6 +46,14 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
             if (a.method == M_BLOCK) return go_tri<M_BLOCK, true>(a);
             if (a.method == M_MIXED) return go_tri<M_MIXED, true>(a);
         }
+#if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
+        // C = 128: the method as usual, then the refinement step as a second pass over T, in place (fp32 result only)
+        if ((a.method == M_BLOCK || a.method == M_MIXED) && a.out_dt == OP_F32) {
+            if (a.method == M_BLOCK) go_tri<M_BLOCK>(a); else go_tri<M_MIXED>(a);
+            hipLaunchKernelGGL((k_tri_inv_refine128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
+            return 0;
+        }
+#endif
         return 1;
     }
     switch (a.method) {
@@ -109,6 +117,16 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
             if (a.method == M_BLOCK) return go_gdn<KD, M_BLOCK, DKS, true>(a);
             if (a.method == M_MIXED) return go_gdn<KD, M_MIXED, DKS, true>(a);
         }
+#if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
+        if constexpr (!(KD == OP_F32 && DKS == 8)) {  // (128 fp32 channels x 128 rows of keys per wave do not fit the register file)
+            if ((a.method == M_BLOCK || a.method == M_MIXED) && a.out_dt == OP_F32) {
+                if (a.method == M_BLOCK) go_gdn<KD, M_BLOCK, DKS>(a); else go_gdn<KD, M_MIXED, DKS>(a);
+                hipLaunchKernelGGL((k_gdn_tri_inv_refine128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
+                                   a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
+                return 0;
+            }
+        }
+#endif
         return 1;
     }
     switch (a.method) {

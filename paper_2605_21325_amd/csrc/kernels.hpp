@@ -1138,6 +1138,109 @@ __device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float
     n128_store<W>(Tm, Xt, Y + w * STORE_LDS_FLOATS, ln);  // Y is dead: its memory becomes the four store patches
 }
 
+// ---------------------------------------------------------------------------------------------
+// One step of iterative refinement at C = 128 (paper Alg. 6, Eq. 9, for I + A), as a second pass over
+// a result Y that an earlier kernel left in T (fp32), in place:
+//   R <- I - Y (I + A);   X <- Y + R Y.
+// The same four-wavefront workgroup: Y goes to LDS (36 fp32 tiles, N layout); wave w keeps its tile
+// rows w and 7 - w of Y^T and R^T in registers and forms
+//   R^T(i,j) = [i==j] I - Y^T(i,j) - sum_k A(k,j)^T Y(i,k)^T,     X^T(i,j) = Y^T(i,j) + sum_k Y(k,j)^T R(i,k)^T.
+// A wave reads and writes only its own rows of T in global memory, so the pass is safe in place.
+// ---------------------------------------------------------------------------------------------
+template <int OP, int W, class ASrc>
+__device__ __forceinline__ void refine128_run(const ASrc& A, float* Tm, float* Y, Lane ln, int w)
+{
+    v4f Yt[9];
+#pragma unroll
+    for (int s = 0; s < 9; ++s) {
+        const int i = n128_row<W>(s), j = n128_col<W>(s);
+        // row-major 16-byte pieces = the tile in T orientation: v[r] = Y[16i + n][16j + 4q + r]
+        Yt[s] = *reinterpret_cast<const v4f*>(Tm + (16 * i + ln.n) * 128 + 16 * j + 4 * ln.q);
+        *reinterpret_cast<v4f*>(&Y[tix(i, j) * XPOSE_FLOATS + ln.n * XPOSE_LD + 4 * ln.q]) = Yt[s];
+    }
+    __syncthreads();
+    Opnd<OP> Rt[9];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int i = half == 0 ? W : 7 - W, s0 = half == 0 ? 0 : W + 1;
+        Opnd<OP> yo[N128_NB];
+#pragma unroll
+        for (int k = 0; k < N128_NB; ++k)
+            if (k <= i) yo[k] = pack<OP>(Yt[s0 + k]);
+#pragma unroll
+        for (int j = 0; j < N128_NB; ++j) {
+            if (j > i) continue;
+            v4f acc = zero4();
+#pragma unroll
+            for (int k = 0; k < N128_NB; ++k) {
+                if (k < j || k > i) continue;
+                acc = tn<OP>(pack<OP>(A.template get<false>(k, j)), yo[k], acc);
+            }
+            v4f r;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = ((i == j && 4 * ln.q + e == ln.n) ? 1.f : 0.f) - Yt[s0 + j][e] - acc[e];
+            Rt[s0 + j] = pack<OP>(r);
+        }
+    }
+    v4f Xt[9];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int i = half == 0 ? W : 7 - W, s0 = half == 0 ? 0 : W + 1;
+#pragma unroll
+        for (int j = 0; j < N128_NB; ++j) {
+            if (j > i) continue;
+            v4f acc = Yt[s0 + j];
+#pragma unroll
+            for (int k = 0; k < N128_NB; ++k) {
+                if (k < j || k > i) continue;
+                acc = tn<OP>(pack<OP>(lds_tile_read_n(Y + tix(k, j) * XPOSE_FLOATS, ln)), Rt[s0 + k], acc);
+            }
+            Xt[s0 + j] = acc;
+        }
+    }
+    __syncthreads();  // Y is dead: its memory becomes the four store patches
+    n128_store<W>(Out{Tm, OP_F32}, Xt, Y + w * STORE_LDS_FLOATS, ln);
+}
+
+template <int OP>
+__global__ __launch_bounds__(256) void k_tri_inv_refine128(const void* __restrict__ A, float* T, int64_t n_mat, int in_dt)
+{
+    __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
+    const int64_t m = blockIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Lane ln = lane_id();
+    GlobalA<N128_NB> src;
+    src.base = static_cast<const char*>(A) + m * 128 * 128 * (in_dt == OP_F32 ? 4 : 2);
+    src.dt = in_dt;
+    src.ln = ln;
+    (void)n_mat;
+    TRIINV_PER_WAVE(w, (refine128_run<OP, W>(src, T + m * 128 * 128, Y, ln, w)))
+}
+
+template <int KD, int OP, int DKS>
+__global__ __launch_bounds__(256) void k_gdn_tri_inv_refine128(const void* __restrict__ K, const float* __restrict__ beta,
+                                                               const float* __restrict__ g, float* T, int64_t n_chunk,
+                                                               ChunkMap map, int H, int d_k)
+{
+    constexpr int C = 128;
+    __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Lane ln = lane_id();
+    GramA<KD, N128_NB, DKS> src;
+    src.ln = ln;
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
+    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
+    src.stage_gate(Y + w * 2 * C);  // a private 2 * C floats inside the (not yet used) Y buffer
+    __syncthreads();
+    TRIINV_PER_WAVE(w, (refine128_run<OP, W>(src, T + m * C * C, Y, ln, w)))
+}
+
 template <int OP>
 __global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt,
                                                        int n_iter, int out_dt)

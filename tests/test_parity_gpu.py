@@ -257,6 +257,40 @@ def test_refinement_on_the_stress_blocks():
     assert e1 < e0
 
 
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+def test_refinement_step_c128(op):
+    """Alg. 6 at C = 128 (a second pass over T, in place): inside the tolerance on benign and stress inputs,
+    standalone and fused, with a short last chunk; it repairs the mixed recursion run without its own
+    refinement of the diagonal blocks on the stress input; against the fp64 statement of the step applied
+    to the unrefined GPU result it differs only by the operand rounding."""
+    from oracle import methods
+    inp = si.make_inputs(si.workload(1, Tlen=128 * 2 + 50, H=3, C=128))
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 0, 128)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    for method in (tri.BLOCK_RECURSIVE, tri.MIXED):
+        check(tri.gdn_chunk_tri_inv_ex(K, beta, g, 128, method=method, op_dtype=op, flags=1), T_ref, TOL[op],
+              f"refined C=128 fused {tri.METHOD_NAMES[method]}")
+    st = si.make_inputs(si.workload(4, Tlen=512, H=3))
+    A = oracle.build_A(st["K"], st["beta"], None, 2, 128)
+    A32 = torch.from_numpy(A.astype(np.float32))
+    T32 = oracle.tri_inv(A32)
+    r0 = tri.flag_mxr_r(0)
+    Y = tri.tri_inv_ex(A32.to(DEV), method=tri.MIXED, op_dtype=op, flags=r0)
+    e0 = check(Y, T32, 2e-1, "mixed r=0 stress C=128")
+    X = tri.tri_inv_ex(A32.to(DEV), method=tri.MIXED, op_dtype=op, flags=r0 | 1)
+    e1 = check(X, T32, TOL[op], "mixed r=0 stress C=128 + whole-matrix step")
+    assert e1 <= e0
+    Kd, bd = st["K"].to(DEV), st["beta"].to(DEV)
+    Xf = tri.gdn_chunk_tri_inv_ex(Kd, bd, None, 128, gate_kind=tri.GATE_NONE, method=tri.MIXED, op_dtype=op, flags=r0 | 1)
+    check(Xf, oracle.tri_inv(A), TOL[op], "mixed r=0 stress C=128 + step, fused")
+    # the step itself: fp64 statement of Alg. 6 applied to the unrefined GPU result
+    Yh = Y.cpu().numpy().astype(np.float64)
+    want = np.stack([methods.ir(Yh[m], A32[m].numpy().astype(np.float64)) for m in range(4)])
+    got = X.cpu().numpy().astype(np.float64)[:4]
+    rel = np.linalg.norm(got - want, axis=(1, 2)) / np.linalg.norm(want, axis=(1, 2))
+    assert rel.max() <= {tri.F32: 1e-5, tri.F16: 5e-3, tri.BF16: 2e-2}[op], rel
+
+
 def test_mixed_recursion_refines_its_diagonal_blocks():
     """Paper Alg. 2 / Sec. 4.1: without refinement the mixed recursion loses digits on the stress input;
     one step on the 16 x 16 blocks (the default) brings it to the accuracy of the blocked recursion."""
@@ -369,8 +403,8 @@ def test_unbuilt_combinations_report_unsupported(cases):
                                  torch.zeros(1, 128, 2, 128, device=DEV), 128, gate_kind=tri.GATE_PER_CHANNEL,
                                  method=tri.NEWTON_SCHULZ)
     assert e.value.status == -9
-    with pytest.raises(tri.TriInvError) as e:   # refinement is not built at C = 128
-        tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.MIXED, op_dtype=tri.F32, flags=1)
+    with pytest.raises(tri.TriInvError) as e:   # refinement at C = 128 is a second pass over an fp32 result
+        tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.MIXED, op_dtype=tri.F32, flags=1, out_dtype=torch.bfloat16)
     assert e.value.status == -9
     # per-channel gate + Neumann product at C = 128 is not built
     K = torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV)
