@@ -949,6 +949,11 @@ __device__ __forceinline__ v4f lds_tile_read_t(const float* t, Lane ln)
 {
     return *reinterpret_cast<const v4f*>(&t[ln.n * XPOSE_LD + 4 * ln.q]);
 }
+// registers in N orientation -> the tile stored transposed (read it back in N orientation with lds_tile_read_t)
+__device__ __forceinline__ void lds_tile_write_transposed(float* t, v4f v, Lane ln)
+{
+    *reinterpret_cast<v4f*>(&t[ln.n * XPOSE_LD + 4 * ln.q]) = v;
+}
 __device__ __forceinline__ void lds_tile_write_n(float* t, v4f v, Lane ln)
 {
 #pragma unroll
@@ -1069,8 +1074,9 @@ __device__ __forceinline__ void neumann_c128_workgroup(const ASrc& A, Out Tm, fl
 // ---------------------------------------------------------------------------------------------
 // Newton-Schulz at C = 128 (paper Alg. 3, Eq. 8, for I + A): the same four-wavefront workgroup.
 //   X <- I / C;  n_iter times:  Y <- X + A X;  X <- 2 X - X Y.
-// X and Y live in LDS as 36 fp32 tiles each (N orientation; 92 KB together, one workgroup per compute
-// unit); wave w owns tile rows w and 7 - w: it keeps its rows of A (T orientation, packed operands) and of
+// X and Y live in LDS as 36 fp32 tiles each, stored transposed so that a tile leaves the accumulator
+// layout and comes back as a right factor with one 16-byte access per lane (92 KB together, one workgroup
+// per compute unit); wave w owns tile rows w and 7 - w: it keeps its rows of A (T orientation, packed operands) and of
 // X (both orientations, fp32) in registers and reads the other factor of every product from LDS.
 // ---------------------------------------------------------------------------------------------
 constexpr int NS128_LDS_FLOATS = 2 * N128_LDS_FLOATS;
@@ -1091,7 +1097,7 @@ __device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float
         for (int r = 0; r < 4; ++r) x[r] = (i == j && 4 * ln.q + r == ln.n) ? 1.f / 128.f : 0.f;
         Xn[s] = x;
         Xt[s] = x;
-        lds_tile_write_n(X + tix(i, j) * XPOSE_FLOATS, x, ln);
+        lds_tile_write_transposed(X + tix(i, j) * XPOSE_FLOATS, x, ln);
     }
     __syncthreads();
 #pragma unroll 1
@@ -1104,9 +1110,9 @@ __device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float
 #pragma unroll
             for (int k = 0; k < N128_NB; ++k) {
                 if (k < j || k > i) continue;
-                acc = tn<OP>(At[n128_slot<W>(i, k)], pack<OP>(lds_tile_read_n(X + tix(k, j) * XPOSE_FLOATS, ln)), acc);
+                acc = tn<OP>(At[n128_slot<W>(i, k)], pack<OP>(lds_tile_read_t(X + tix(k, j) * XPOSE_FLOATS, ln)), acc);
             }
-            lds_tile_write_n(Y + tix(i, j) * XPOSE_FLOATS, acc, ln);
+            lds_tile_write_transposed(Y + tix(i, j) * XPOSE_FLOATS, acc, ln);
         }
         __syncthreads();  // Y complete; nobody reads X from LDS any more in this iteration
         // X(i,j) <- 2 X(i,j) - sum_k X(i,k) Y(k,j), both orientations; the packed old row first
@@ -1124,13 +1130,13 @@ __device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float
 #pragma unroll
                 for (int k = 0; k < N128_NB; ++k) {
                     if (k < j || k > i) continue;
-                    const Opnd<OP> y = pack<OP>(lds_tile_read_n(Y + tix(k, j) * XPOSE_FLOATS, ln));
+                    const Opnd<OP> y = pack<OP>(lds_tile_read_t(Y + tix(k, j) * XPOSE_FLOATS, ln));
                     pn = tn<OP>(xo[k], y, pn);
                     pt = tn<OP>(y, xo[k], pt);
                 }
                 Xn[s0 + j] = 2.f * Xn[s0 + j] - pn;
                 Xt[s0 + j] = 2.f * Xt[s0 + j] - pt;
-                lds_tile_write_n(X + tix(i, j) * XPOSE_FLOATS, Xn[s0 + j], ln);
+                lds_tile_write_transposed(X + tix(i, j) * XPOSE_FLOATS, Xn[s0 + j], ln);
             }
         }
         __syncthreads();  // X complete; nobody reads Y any more
