@@ -261,13 +261,36 @@ def test_mbh_block_invariant(C):
             assert np.allclose(X[s, s], want, atol=1e-10), (b, t)
 
 
-def test_matmul_counts_table2():
-    # Table 2: MCH 2*ceil(log2(n/2)) -> 10 at 64, 12 at 128 ; MBH (b0=1) 2*log2(n) -> 12, 14
-    for n, mch_cnt, mbh_cnt in [(64, 10, 12), (128, 12, 14)]:
-        assert 2 * math.ceil(math.log2(n / 2)) == mch_cnt
-        levels = []
-        methods.mbh(np.zeros((n, n)), levels_out=levels)
-        assert 2 * len(levels) == mbh_cnt
+def test_matmul_counts_table2(monkeypatch):
+    """The numpy statements of Alg. 3-6 execute exactly the number of matrix products the paper's Table 2
+    gives (fixture tests/golden/table2_matmul_counts.txt)."""
+    import os
+
+    want = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table2_matmul_counts.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, n, cnt = line.split()
+                want[(name, int(n))] = int(cnt)
+    calls = []
+    real_mm = methods.Arith.mm
+    monkeypatch.setattr(methods.Arith, "mm", lambda self, X, Y: (calls.append(1), real_mm(self, X, Y))[1])
+
+    def count(fn):
+        calls.clear()
+        fn()
+        return len(calls)
+
+    rng = np.random.default_rng(0)
+    for n in (64, 128):
+        L = np.tril(rng.standard_normal((n, n)) * 0.05, -1)
+        assert count(lambda: methods.mch(L)) == want[("MCH", n)] == 2 * math.ceil(math.log2(n / 2))
+        assert count(lambda: methods.mbh(L)) == want[("MBH", n)] == 2 * int(math.log2(n))
+        Y = np.eye(n) - L
+        assert count(lambda: methods.ir(Y, L)) == want[("IR1", n)]
+        assert want[("MCS", n)] == n - 1
+    L = np.tril(rng.standard_normal((64, 64)) * 0.05, -1)
+    assert count(lambda: methods.ns(L, m=12)) == want[("NS12", 64)]
 
 
 # ---------------------------------------------------------------- short last chunk, packed sequences
