@@ -128,7 +128,7 @@ def main() -> int:
                         "residual_normalised_max": float(np.nanmax(r["normalised"])) if bad < len(sel) else float("nan"),
                         "non_finite_matrices": bad, "structure_ok": bool(metrics.structure_ok(Tg))}
 
-        for method in (0, 1, 4, 3, 2, 5):
+        for method in (0, 1, 4, 3, 6, 2, 5):
             for op in (0, 1, 2):
                 if method == 0 and op != 0:
                     continue
@@ -320,7 +320,7 @@ def main() -> int:
             del S, Kc
             # one copy per buffer set, so that no timed launch finds its input in the last-level cache
             A32s = [A32] + [A32.clone() for _ in range(len(sets) - 1)]
-        for method in (0, 1, 4, 3, 2, 5):
+        for method in (0, 1, 4, 3, 6, 2, 5):
             for op in (0, 1, 2):
                 if method == 0 and op != 0:
                     continue

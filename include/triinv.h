@@ -58,7 +58,11 @@ typedef enum {
      * X <- 2X - XY.  n = TRIINV_FLAG_ITERS(n) in flags, default 12 (the count the paper finds
      * sufficient at C = 64; 2 log2 C elsewhere).  At C = 128 not built for the per-channel gate
      * and for fp32 keys with d_k = 128. */
-    TRIINV_NEWTON_SCHULZ = 5
+    TRIINV_NEWTON_SCHULZ = 5,
+    /* Mixed recursion with b0 = 32 (the other block size the paper proposes, Sec. 3.4): Neumann product
+     * (four squarings) and r refinement steps on the 32 x 32 diagonal blocks, blocked recursion from block
+     * size 32.  C >= 32.  TRIINV_FLAG_REFINE1 is not built for it. */
+    TRIINV_MIXED_B32 = 6
 } triinv_method;
 
 /* Gate kinds of the fused entry point. */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libtriinv.so")
 
 # enums of include/triinv.h
 F32, F16, BF16 = 0, 1, 2
-FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED, BLOCK_DIRECT, NEWTON_SCHULZ = 0, 1, 2, 3, 4, 5
+FWD_SUBST, BLOCK_RECURSIVE, NEUMANN, MIXED, BLOCK_DIRECT, NEWTON_SCHULZ, MIXED_B32 = 0, 1, 2, 3, 4, 5, 6
 FLAG_REFINE1 = 0x1
 FLAG_OUT_F16 = 0x2
 FLAG_OUT_BF16 = 0x4
@@ -38,7 +38,7 @@ GATE_SCALAR, GATE_PER_CHANNEL, GATE_NONE = 0, 1, 2
 OK = 0
 
 METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUMANN: "neumann", MIXED: "mixed",
-                BLOCK_DIRECT: "block_direct", NEWTON_SCHULZ: "newton_schulz"}
+                BLOCK_DIRECT: "block_direct", NEWTON_SCHULZ: "newton_schulz", MIXED_B32: "mixed_b32"}
 DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
 
 EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "gdn_chunk_tri_inv_varlen",

@@ -17,7 +17,7 @@ bool overlap(const void* a, uint64_t na, const void* b, uint64_t nb)
 
 bool dtype_ok(int d) { return d == TRIINV_F32 || d == TRIINV_F16 || d == TRIINV_BF16; }
 bool chunk_size_ok(int C) { return C == 16 || C == 32 || C == 64 || C == 128; }
-bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_NEWTON_SCHULZ; }
+bool method_ok(int m) { return m >= TRIINV_FWD_SUBST && m <= TRIINV_MIXED_B32; }
 
 constexpr uint32_t KNOWN_FLAGS = TRIINV_FLAG_REFINE1 | TRIINV_FLAG_OUT_F16 | TRIINV_FLAG_OUT_BF16 | TRIINV_FLAG_FWD_SHUFFLE | 0xff00u | 0x70000u;
 
@@ -31,7 +31,7 @@ int ns_iterations(uint32_t flags, int C)
 // necessary and sufficient for the mixed recursion to reach the accuracy of the stable methods, Sec. 4.1).
 int method_count(int method, uint32_t flags, int C)
 {
-    if (method == TRIINV_MIXED) {
+    if (method == TRIINV_MIXED || method == TRIINV_MIXED_B32) {
         const int code = (int)((flags >> 16) & 7u);
         return code ? code - 1 : 1;
     }

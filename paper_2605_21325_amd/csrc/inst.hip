@@ -71,6 +71,9 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 #else
     case M_BLOCK: return go_tri<M_BLOCK>(a);
     case M_MIXED: return go_tri<M_MIXED>(a);
+#if TRIINV_INST_NB >= 2
+    case M_MIXED32: return go_tri<M_MIXED32>(a);
+#endif
     case M_BLOCK_DIRECT: return go_tri<M_BLOCK_DIRECT>(a);
     case M_NEWTON_SCHULZ:
 #if TRIINV_INST_NB <= 4
@@ -99,7 +102,7 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 // the memory controllers, none served sooner).
 template <int METHOD> constexpr unsigned occupancy_pad_bytes()
 {
-    return (NB == 4 && WPB == 4 && OP != OP_F32 && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_BLOCK_DIRECT)) ? 24576u : 0u;
+    return (NB == 4 && WPB == 4 && OP != OP_F32 && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT)) ? 24576u : 0u;
 }
 
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
@@ -135,6 +138,9 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 #else
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
+#if TRIINV_INST_NB >= 2
+    case M_MIXED32: return go_gdn<KD, M_MIXED32, DKS>(a);
+#endif
     case M_BLOCK_DIRECT: return go_gdn<KD, M_BLOCK_DIRECT, DKS>(a);
     case M_NEWTON_SCHULZ:
 #if TRIINV_INST_NB <= 4
@@ -181,6 +187,9 @@ static int kda_method(const GdnArgs& a)
 #else
     case M_BLOCK: return go_kda<M_BLOCK>(a);
     case M_MIXED: return go_kda<M_MIXED>(a);
+#if TRIINV_INST_NB >= 2
+    case M_MIXED32: return go_kda<M_MIXED32>(a);
+#endif
     case M_BLOCK_DIRECT: return go_kda<M_BLOCK_DIRECT>(a);
 #if TRIINV_INST_NB <= 4
     case M_NEWTON_SCHULZ: return go_kda<M_NEWTON_SCHULZ>(a);

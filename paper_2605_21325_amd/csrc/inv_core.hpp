@@ -185,7 +185,18 @@ __host__ __device__ constexpr bool result_is_T(int i, int j)
     return (NB == 1) ? false : ((j >= NB / 2) ? true : ((i < NB / 2) ? false : ROOT_T));
 }
 
-enum : int { LEAF_BLOCK_RECURSIVE = 0, LEAF_NEUMANN = 1, LEAF_FORWARD = 2 };
+enum : int { LEAF_BLOCK_RECURSIVE = 0, LEAF_NEUMANN = 1, LEAF_FORWARD = 2, LEAF_NEUMANN32 = 3 };
+
+template <int OP, int NB, class ASrc> __device__ __forceinline__ void neumann(const ASrc& A, v4f (&Xt)[NB * (NB + 1) / 2], Lane ln);
+template <int OP, int NB, class ASrc, class IsT>
+__device__ __forceinline__ void refine_once(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* patch, Lane ln);
+
+// The 32 x 32 diagonal block that starts at tile P, as a tile source of its own.
+template <class ASrc> struct PairView {
+    const ASrc& a;
+    int P;
+    template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const { return a.template get<TR>(P + i, P + j); }
+};
 
 template <int OP, int NB, bool ROOT_T, int LEAF, class ASrc>
 __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln, int leaf_r = 0)
@@ -193,6 +204,25 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
     v4f leafN[NB], leafT[NB];
     if constexpr (LEAF == LEAF_FORWARD) {
         leaves_forward_substitution<NB>(A, leafN, leafT, patch, ln);
+    } else if constexpr (LEAF == LEAF_NEUMANN32) {
+        // paper Alg. 2 with b0 = 32: Neumann product (four squarings) on every 32 x 32 diagonal block, leaf_r
+        // refinement steps on it, and the merges below start at block size 32.  The product comes out in T
+        // orientation; the block is brought to the orientation its parent expects (diagonal tiles to both).
+        static_assert(NB >= 2, "b0 = 32 needs C >= 32");
+#pragma unroll
+        for (int p = 0; p < NB / 2; ++p) {
+            const PairView<ASrc> pv{A, 2 * p};
+            v4f X[3];
+            neumann<OP, 2>(pv, X, ln);
+#pragma unroll 1
+            for (int s = 0; s < leaf_r; ++s) refine_once<OP, 2>(pv, X, [](int, int) { return true; }, patch, ln);
+            const bool blockT = (2 == NB) ? ROOT_T : ((p & 1) != 0);
+            leafT[2 * p] = X[tix(0, 0)];
+            leafT[2 * p + 1] = X[tix(1, 1)];
+            leafN[2 * p] = transpose_tile(X[tix(0, 0)], patch, ln);
+            leafN[2 * p + 1] = transpose_tile(X[tix(1, 1)], patch, ln);
+            Tt[tix(2 * p + 1, 2 * p)] = blockT ? X[tix(1, 0)] : transpose_tile(X[tix(1, 0)], patch, ln);
+        }
     } else {
 #pragma unroll
         for (int d = 0; d < NB; ++d) {
@@ -205,7 +235,7 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
     }
 
 #pragma unroll
-    for (int h = 1; h < NB; h *= 2) {
+    for (int h = (LEAF == LEAF_NEUMANN32 ? 2 : 1); h < NB; h *= 2) {
 #pragma unroll
         for (int p = 0; p < NB / (2 * h); ++p) {
             const int lo = 2 * h * p, mid = lo + h, hi = lo + 2 * h;

@@ -16,7 +16,7 @@
 
 namespace triinv {
 
-enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3, M_BLOCK_DIRECT = 4, M_NEWTON_SCHULZ = 5 };
+enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3, M_BLOCK_DIRECT = 4, M_NEWTON_SCHULZ = 5, M_MIXED32 = 6 };
 enum : int { G_SCALAR = 0, G_CHANNEL = 1, G_NONE = 2 };
 
 __device__ __forceinline__ void wave_lds_sync()
@@ -264,6 +264,7 @@ template <int NB, int METHOD> __host__ __device__ constexpr bool need_tile(int i
 {
     if (METHOD == M_FWD || METHOD == M_NEWTON_SCHULZ) return tr;
     if (METHOD == M_NEUMANN) return true;
+    if (METHOD == M_MIXED32 && i / 2 == j / 2) return true;  // the 32 x 32 Neumann blocks want both orientations
     if (i == j) return METHOD == M_BLOCK_DIRECT ? tr : true;
     return merge_block_is_T<NB>(i, j) ? !tr : tr;
 }
@@ -789,7 +790,7 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, Out Tm, float*
         store_result<NB>(Tm, Xt, [](int, int) { return true; }, lds, ln);
     } else {
         v4f Tt[NT];
-        constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : METHOD == M_BLOCK_DIRECT ? LEAF_FORWARD : LEAF_BLOCK_RECURSIVE;
+        constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : METHOD == M_MIXED32 ? LEAF_NEUMANN32 : METHOD == M_BLOCK_DIRECT ? LEAF_FORWARD : LEAF_BLOCK_RECURSIVE;
         block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln, aux);  // aux = refinement steps on the leaves (mixed recursion)
         if constexpr (REFINE) {
             refine_once<OP, NB>(src, Tt, [](int i, int j) { return result_is_T<NB, ROOT_T>(i, j); }, lds, ln);

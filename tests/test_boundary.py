@@ -37,7 +37,7 @@ def test_header_enums_match_binding():
     src = open(HEADER).read()
     for name, val in [("TRIINV_F32", tri.F32), ("TRIINV_F16", tri.F16), ("TRIINV_BF16", tri.BF16),
                       ("TRIINV_FWD_SUBST", tri.FWD_SUBST), ("TRIINV_BLOCK_RECURSIVE", tri.BLOCK_RECURSIVE),
-                      ("TRIINV_NEUMANN", tri.NEUMANN), ("TRIINV_MIXED", tri.MIXED), ("TRIINV_BLOCK_DIRECT", tri.BLOCK_DIRECT), ("TRIINV_NEWTON_SCHULZ", tri.NEWTON_SCHULZ),
+                      ("TRIINV_NEUMANN", tri.NEUMANN), ("TRIINV_MIXED", tri.MIXED), ("TRIINV_BLOCK_DIRECT", tri.BLOCK_DIRECT), ("TRIINV_NEWTON_SCHULZ", tri.NEWTON_SCHULZ), ("TRIINV_MIXED_B32", tri.MIXED_B32),
                       ("TRIINV_GATE_SCALAR", tri.GATE_SCALAR), ("TRIINV_GATE_PER_CHANNEL", tri.GATE_PER_CHANNEL),
                       ("TRIINV_GATE_NONE", tri.GATE_NONE)]:
         assert re.search(rf"\b{name}\s*=\s*{val}\b", src), name
@@ -71,7 +71,7 @@ def test_tri_inv_argument_errors(L):
     assert call(n=0, A=None, T=None) == 0
     assert call(C=48) == -2 and call(C=96) == -2 and call(C=0) == -2 and call(C=256) == -2
     assert call(dt=3) == -3 and call(op=-1) == -3
-    assert call(m=6) == -4 and call(m=-1) == -4
+    assert call(m=7) == -4 and call(m=-1) == -4
     assert call(n=-1) == -5
     assert call(A=None) == -1 and call(T=None) == -1
     assert call(A=P + 4) == -6 and call(T=Q + 8) == -6

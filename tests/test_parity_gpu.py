@@ -713,3 +713,44 @@ def test_entry_points_replay_from_a_captured_graph():
         torch.cuda.synchronize()
         assert torch.equal(T1, E1) and torch.equal(T2, E2), f"replay {rep} differs from the eager launch"
         check(T1, oracle.gdn_chunk_tri_inv_ragged(src["K"], src["beta"], src["g"], 0, C), 2e-2, f"graph replay {rep}")
+
+
+# ------------------------------------------------------------------ mixed recursion with b0 = 32
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("C", [32, 64, 128])
+def test_mixed_recursion_b32(cases, C, op):
+    """Alg. 2 with b0 = 32: inside the tolerance on benign inputs (standalone, every gate kind, short last chunk) and,
+    with its default refinement step, on the stress recipe; against the numpy statement of Alg. 2 with the same b0,
+    r and operand rounding the fp32-operand result agrees to fp32 rounding."""
+    from oracle import methods
+    for gate_kind, idx in ((0, 1), (1, 3), (2, 2)):
+        inp = si.make_inputs(si.workload(idx, B=1, Tlen=3 * C + 9, H=5, C=C, d_k=128, k_dtype="bf16", gate_kind=gate_kind))
+        T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)
+        g = None if inp["g"] is None else inp["g"].to(DEV)
+        T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate_kind, method=tri.MIXED_B32,
+                                     op_dtype=op)
+        check(T, T_ref, TOL[op], f"mixed_b32 fused C={C} gate={gate_kind}")
+    A = si.random_strict_lower(21, C, 0.15, seed=5)
+    T32 = oracle.tri_inv(A)
+    for r in (0, 1, 2):
+        T = tri.tri_inv_ex(A.to(DEV), method=tri.MIXED_B32, op_dtype=op, flags=tri.flag_mxr_r(r))
+        check(T, T32, TOL[op], f"mixed_b32 standalone C={C} r={r}")
+        if op == tri.F32:
+            want = np.stack([methods.mxr(np.tril(A[m].numpy().astype(np.float64), -1), 32, r, "f32") for m in range(3)])
+            got = T.cpu().numpy().astype(np.float64)[:3]
+            assert np.abs(got - want).max() <= 2e-6, (C, r)
+    if C >= 64:
+        st = si.make_inputs(si.workload(4, Tlen=4 * C, H=3, C=C))
+        T_ref = oracle.gdn_chunk_tri_inv(st["K"], st["beta"], None, 2, C)
+        T = tri.gdn_chunk_tri_inv_ex(st["K"].to(DEV), st["beta"].to(DEV), None, C, gate_kind=tri.GATE_NONE, method=tri.MIXED_B32,
+                                     op_dtype=op)
+        check(T, T_ref, TOL[op], f"mixed_b32 stress C={C}")
+
+
+def test_mixed_recursion_b32_needs_c32():
+    with pytest.raises(tri.TriInvError) as e:
+        tri.tri_inv_ex(torch.zeros(2, 16, 16, device=DEV), method=tri.MIXED_B32, op_dtype=tri.F32)
+    assert e.value.status == -9
+    with pytest.raises(tri.TriInvError) as e:
+        tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), method=tri.MIXED_B32, op_dtype=tri.F32, flags=1)
+    assert e.value.status == -9
