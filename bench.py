@@ -57,6 +57,7 @@ def main() -> int:
     ap.add_argument("--op", type=int, default=2, help="operand type: 0 f32, 1 f16, 2 bf16")
     ap.add_argument("--out", default="f32", choices=["f32", "f16", "bf16"],
                     help="element type of T (the contract's fp32, or a 16-bit result: TRIINV_FLAG_OUT_*)")
+    ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk size C (16, 32, 64, 128)")
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -90,6 +91,8 @@ def main() -> int:
     out_torch = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.out]
     out_bytes = 4 if args.out == "f32" else 2
     w = si.WORKLOADS[args.workload]
+    if args.chunk:
+        w = si.workload(args.workload, C=args.chunk)
     inp = si.make_inputs(w)
     n_mat, C = w.n_mat, w.C
     sets = []
