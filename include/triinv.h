@@ -156,9 +156,12 @@ int gdn_chunk_tri_inv(const void* K, const float* beta, const float* g, float* T
  * gdn_chunk_tri_inv_ex: as gdn_chunk_tri_inv, with
  *   k_dtype    triinv_dtype of K.  The Gram products <k_i, k_j> use the stored key values as
  *              matrix-core operands (exact products, fp32 accumulation) for the scalar and
- *              no-gate kinds.  For the per-channel gate the gated keys k*exp(+-(g - g_mid)) are
- *              rounded to op_dtype (g_mid = the chunk's middle row), so the in-chunk range of g
- *              must stay below ~80 (fp32, bf16 operands) or ~10 (fp16 operands).
+ *              no-gate kinds.  For the per-channel gate the gated keys k*exp(+-(g - a)) are rounded
+ *              to op_dtype, a = an anchor row of g.  C <= 64: one anchor per 16 rows, so only the
+ *              fall of g within any 16 consecutive tokens must stay below ~80 (fp32, bf16 operands)
+ *              or ~10 (fp16 operands), however strong the decay over the whole chunk is (g is taken
+ *              to fall along the chunk, as a cumulative log-decay does).  C = 128: one anchor, the
+ *              chunk's middle row, and the bound applies to the fall of g over the whole chunk.
  *   gate_kind  triinv_gate (KDA row of Table 1 for TRIINV_GATE_PER_CHANNEL).
  *   method, op_dtype, hip_stream, flags: as in tri_inv_ex.
  */

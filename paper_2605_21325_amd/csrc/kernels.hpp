@@ -351,8 +351,13 @@ template <bool K16> __device__ __forceinline__ void widen_key8(const RawKey8<K16
 }
 
 // Per-channel gate (paper Table 1, KDA row): A_ij = beta_i sum_c k_ic k_jc exp(g_ic - g_jc)
-//   = beta_i [(K * exp(G - a)) (K * exp(a - G))^T]_ij   for any per-channel anchor a;
-// a is row C/2 of the chunk's G, so both gated factors stay within exp(+-half the chunk's decay).
+//   = beta_i [(K * exp(G - a)) (K * exp(a - G))^T]_ij   for any per-channel anchor a.
+// C <= 64: one anchor per 16-row tile row I, a_I = the first row of that tile row of G: for a tile (I, J),
+// J <= I, the left factor k_i exp(g_i - a_I) has an exponent within the decay of 16 tokens and <= 0, the
+// right factor k_j exp(a_I - g_j) an exponent <= 0 for J < I and within the decay of 16 tokens for J = I
+// (log-decays only fall along a chunk), so neither factor can overflow however strong the decay over the
+// whole chunk is; the price is a right factor per (I, J) instead of per J (1.75x the exponentials at C = 64).
+// C = 128 (no registers for that): a single anchor, row C/2, both factors within exp(+-half the chunk's decay).
 // The gated keys are rounded to OPG and contracted on the matrix cores, 32 channels per step,
 // accumulating every tile the method needs; nothing but K, G, beta is read, nothing stored.
 // One iteration covers one whole 128-byte line of keys per row (64 channels of 16-bit keys, i.e.
@@ -391,6 +396,49 @@ __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void*
         for (int t = 0; t < STEPS; ++t) {
             if (s0 + t >= d_k / 32) break;
             const int ch = 32 * (s0 + t) + 8 * ln.q;
+            if constexpr (GATED && NB <= 4) {
+                // gate rows and tile-row anchors of this k-step, all loads first
+                v4f G[NB][2], An[NB][2];
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const int64_t off = (int64_t)rowc[i] * row_stride + ch;
+                    G[i][0] = *reinterpret_cast<const v4f*>(gc + off);
+                    G[i][1] = *reinterpret_cast<const v4f*>(gc + off + 4);
+                    const int ar = 16 * i < valid ? 16 * i : valid - 1;
+                    An[i][0] = *reinterpret_cast<const v4f*>(gc + (int64_t)ar * row_stride + ch);
+                    An[i][1] = *reinterpret_cast<const v4f*>(gc + (int64_t)ar * row_stride + ch + 4);
+                }
+                float kv[NB][8];
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    widen_key8<K16>(raw[t][i], is_f16, kv[i]);
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) kv[i][r] *= keep[i];
+                }
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    float up[8];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        const float d = (G[i][r / 4][r % 4] - An[i][r / 4][r % 4]) * LOG2E;
+                        up[r] = kv[i][r] * __builtin_amdgcn_exp2f(d);
+                    }
+                    const GOp<OPG> ppi = gpack<OPG>(up);
+#pragma unroll
+                    for (int j = 0; j <= i; ++j) {
+                        float dn[8];
+#pragma unroll
+                        for (int r = 0; r < 8; ++r) {
+                            const float d = (An[i][r / 4][r % 4] - G[j][r / 4][r % 4]) * LOG2E;
+                            dn[r] = kv[j][r] * __builtin_amdgcn_exp2f(d);
+                        }
+                        const GOp<OPG> pmj = gpack<OPG>(dn);
+                        if (need_tile<NB, METHOD>(i, j, false)) out.n[tix(i, j)] = gstep<OPG>(ppi, pmj, out.n[tix(i, j)]);
+                        if (need_tile<NB, METHOD>(i, j, true)) out.t[tix(i, j)] = gstep<OPG>(pmj, ppi, out.t[tix(i, j)]);
+                    }
+                }
+                continue;
+            }
             GOp<OPG> pp[NB], pm[NB];
             if constexpr (GATED) {
                 const v4f a0 = *reinterpret_cast<const v4f*>(gc + (int64_t)anchor * row_stride + ch);

@@ -754,3 +754,22 @@ def test_mixed_recursion_b32_needs_c32():
     with pytest.raises(tri.TriInvError) as e:
         tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), method=tri.MIXED_B32, op_dtype=tri.F32, flags=1)
     assert e.value.status == -9
+
+
+# ------------------------------------------------------------------ per-channel gate with a strong decay
+@pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("C", [16, 32, 64])
+def test_per_channel_gate_with_a_strong_decay(C, op):
+    """g falls by ~2.4 per token (~150 over a chunk of 64): exp(+-(g - one anchor per chunk)) would overflow
+    fp32; with one anchor per 16 rows every exponent stays small and the result is inside the tolerance."""
+    inp = si.make_inputs(si.workload(3, B=1, Tlen=4 * C + 5, H=3, C=C, rate_scale=3.0))
+    g0 = inp["g"][0]
+    half = max(float((g0[c0:c0 + C] - g0[min(c0 + C // 2, g0.shape[0] - 1)]).abs().max()) for c0 in range(0, g0.shape[0], C))
+    in16 = max(float((g0[t0] - g0[t0:min(t0 + 16, (t0 // C + 1) * C)]).abs().max()) for t0 in range(0, g0.shape[0], 16))
+    assert in16 < 85.0, in16                      # what the tile-row anchors need
+    assert C < 64 or half > 89.0, half            # exp(g - g_mid) with one anchor per chunk overflows fp32 here
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 1, C)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    for method in (tri.BLOCK_RECURSIVE, tri.FWD_SUBST, tri.MIXED_B32 if C >= 32 else tri.MIXED, tri.NEUMANN):
+        T = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
+        check(T, T_ref, TOL[op] if method != tri.FWD_SUBST or op == tri.F32 else 2e-2, f"strong decay C={C} {tri.METHOD_NAMES[method]}")
