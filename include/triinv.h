@@ -171,6 +171,21 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
                          void* hip_stream, uint32_t flags);
 
 /*
+ * gdn_chunk_build_A: the first half of the fused operation alone -- the chunk matrices A of paper Sec. 1
+ * Eq. 3 / Table 1 written out, for callers that keep the two steps apart (A then goes to tri_inv).
+ *   A   device, [n_mat][C][C], fp32 (or fp16 / bf16 with TRIINV_FLAG_OUT_F16 / OUT_BF16): the entries
+ *       with i > j, exact zeros on and above the diagonal; n_mat and the matrix order as in
+ *       gdn_chunk_tri_inv; a short last chunk has zero rows and columns for its padding.
+ *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
+ *   op_dtype  only used by the per-channel gate (type its gated keys are rounded to); otherwise the Gram
+ *             products use the stored key values exactly and accumulate in fp32.
+ *   flags     TRIINV_FLAG_OUT_* only.
+ */
+int gdn_chunk_build_A(const void* K, const float* beta, const float* g, float* A,
+                      int B, int64_t Tlen, int H, int d_k, int C,
+                      int k_dtype, int gate_kind, int op_dtype, void* hip_stream, uint32_t flags);
+
+/*
  * gdn_chunk_tri_inv_varlen: the fused operation on sequences of different lengths packed back to
  * back (the layout serving frameworks use for batched prefill; paper Sec. 1 chunking applied to each
  * sequence on its own).

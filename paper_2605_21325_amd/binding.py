@@ -41,7 +41,7 @@ METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUM
                 BLOCK_DIRECT: "block_direct", NEWTON_SCHULZ: "newton_schulz", MIXED_B32: "mixed_b32"}
 DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
 
-EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "gdn_chunk_tri_inv_varlen",
+EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "gdn_chunk_tri_inv_varlen", "gdn_chunk_build_A",
            "triinv_status_string", "triinv_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.gdn_chunk_tri_inv_ex.restype = i32
         L.gdn_chunk_tri_inv_varlen.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i32, i32, i32, vp, u32]
         L.gdn_chunk_tri_inv_varlen.restype = i32
+        L.gdn_chunk_build_A.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, vp, u32]
+        L.gdn_chunk_build_A.restype = i32
         L.triinv_status_string.argtypes = [i32]
         L.triinv_status_string.restype = ctypes.c_char_p
         L.triinv_version.argtypes = []
@@ -215,3 +217,17 @@ def gdn_chunk_tri_inv_varlen(K: torch.Tensor, beta: torch.Tensor, g: Optional[to
         raise TriInvError(st, "gdn_chunk_tri_inv_varlen")
     T._triinv_keepalive = (cu_seqlens, cu_chunks)  # the launch is asynchronous: the offsets live as long as the result
     return T
+
+
+def gdn_chunk_build_A(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], C: int,
+                      A: Optional[torch.Tensor] = None, gate_kind: int = GATE_SCALAR, op_dtype: int = BF16, stream=None,
+                      out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    """The chunk matrices A alone ([n_mat, C, C], strictly lower triangular), from K [B, Tlen, H, d_k], beta, g."""
+    B, Tlen, H, d_k = K.shape
+    A, flags = _out(A, out_dtype, (_n_mat(K, C), C, C), K.device, 0)
+    gp = None if g is None else _dev(g, "g")
+    st = lib().gdn_chunk_build_A(_dev(K, "K"), _dev(beta, "beta"), gp, _dev(A, "A") if A.numel() else None, B, Tlen, H, d_k, C,
+                                 dtype_code(K.dtype), gate_kind, op_dtype, _stream_ptr(stream), flags)
+    if st != OK:
+        raise TriInvError(st, "gdn_chunk_build_A")
+    return A

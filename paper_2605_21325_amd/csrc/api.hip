@@ -164,6 +164,29 @@ int gdn_chunk_tri_inv_ex(const void* K, const float* beta, const float* g, float
     return launch_fused(a, C, op_dtype);
 }
 
+int gdn_chunk_build_A(const void* K, const float* beta, const float* g, float* A, int B, int64_t Tlen, int H, int d_k, int C,
+                      int k_dtype, int gate_kind, int op_dtype, void* hip_stream, uint32_t flags)
+{
+    if (!chunk_size_ok(C)) return TRIINV_ERR_BAD_C;
+    if (!dtype_ok(k_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
+    if (gate_kind < TRIINV_GATE_SCALAR || gate_kind > TRIINV_GATE_NONE) return TRIINV_ERR_BAD_METHOD;
+    if (B <= 0 || H <= 0 || d_k <= 0 || Tlen < 0 || d_k % 32 != 0 || d_k > 256) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t cps = (Tlen + C - 1) / C;
+    if (cps > 0x7fffffffLL / B) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t n_chunk = (int64_t)B * cps;
+    if (n_chunk > 0x7fffffffLL / H) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t n_mat = n_chunk * H;
+    if (n_mat == 0) return TRIINV_OK;
+    if (flags & ~(uint32_t)(TRIINV_FLAG_OUT_F16 | TRIINV_FLAG_OUT_BF16)) return TRIINV_ERR_UNSUPPORTED;
+    const int st = check_fused(K, beta, g, A, (uint64_t)B * Tlen * H, n_mat, H, d_k, C, k_dtype, gate_kind, TRIINV_BLOCK_RECURSIVE, flags);
+    if (st != TRIINV_OK) return st;
+    const ChunkMap map{Tlen, (uint32_t)cps, 0u, nullptr, nullptr};
+    GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, A, n_mat, n_chunk, map, H, d_k, k_dtype, gate_kind, 100 /* M_BUILD_A */,
+              static_cast<hipStream_t>(hip_stream), false, 0, out_dtype(flags)};
+    // only the per-channel gate rounds anything to op_dtype (its gated keys); otherwise the keys' own values are the operands
+    return launch_fused(a, C, gate_kind == TRIINV_GATE_PER_CHANNEL ? op_dtype : TRIINV_F32);
+}
+
 int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, float* T, const int64_t* cu_seqlens,
                              const int64_t* cu_chunks, int n_seq, int64_t total_tokens, int64_t total_chunks, int H, int d_k,
                              int C, int k_dtype, int gate_kind, int method, int op_dtype, void* hip_stream, uint32_t flags)

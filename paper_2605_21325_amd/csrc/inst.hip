@@ -136,6 +136,7 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 #if TRIINV_INST_FWD
     case M_FWD: return go_gdn<KD, M_FWD, DKS>(a);
 #else
+    case M_BUILD_A: return go_gdn<KD, M_BUILD_A, DKS>(a);
     case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS>(a);
     case M_MIXED: return go_gdn<KD, M_MIXED, DKS>(a);
 #if TRIINV_INST_NB >= 2
@@ -185,6 +186,7 @@ static int kda_method(const GdnArgs& a)
 #if TRIINV_INST_FWD
     case M_FWD: return go_kda<M_FWD>(a);
 #else
+    case M_BUILD_A: return go_kda<M_BUILD_A>(a);
     case M_BLOCK: return go_kda<M_BLOCK>(a);
     case M_MIXED: return go_kda<M_MIXED>(a);
 #if TRIINV_INST_NB >= 2
@@ -218,6 +220,7 @@ template <int KD> static int any_dk_method(const GdnArgs& a)
 #if TRIINV_INST_FWD
     case M_FWD: return go_any_dk<KD, M_FWD>(a);
 #else
+    case M_BUILD_A: return go_any_dk<KD, M_BUILD_A>(a);
     case M_BLOCK: return go_any_dk<KD, M_BLOCK>(a);
     case M_BLOCK_DIRECT: return go_any_dk<KD, M_BLOCK_DIRECT>(a);
 #endif

@@ -16,7 +16,8 @@
 
 namespace triinv {
 
-enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3, M_BLOCK_DIRECT = 4, M_NEWTON_SCHULZ = 5, M_MIXED32 = 6 };
+enum : int { M_FWD = 0, M_BLOCK = 1, M_NEUMANN = 2, M_MIXED = 3, M_BLOCK_DIRECT = 4, M_NEWTON_SCHULZ = 5, M_MIXED32 = 6,
+             M_BUILD_A = 100 /* no inversion: the chunk matrix A itself is written (not a triinv_method) */ };
 enum : int { G_SCALAR = 0, G_CHANNEL = 1, G_NONE = 2 };
 
 __device__ __forceinline__ void wave_lds_sync()
@@ -262,7 +263,7 @@ template <int NB> __host__ __device__ constexpr bool merge_block_is_T(int i, int
 
 template <int NB, int METHOD> __host__ __device__ constexpr bool need_tile(int i, int j, bool tr)
 {
-    if (METHOD == M_FWD || METHOD == M_NEWTON_SCHULZ) return tr;
+    if (METHOD == M_FWD || METHOD == M_NEWTON_SCHULZ || METHOD == M_BUILD_A) return tr;
     if (METHOD == M_NEUMANN) return true;
     if (METHOD == M_MIXED32 && i / 2 == j / 2) return true;  // the 32 x 32 Neumann blocks want both orientations
     if (i == j) return METHOD == M_BLOCK_DIRECT ? tr : true;
@@ -592,7 +593,8 @@ constexpr int STORE_LDS_FLOATS = 16 * STORE_LD;
 
 // One strip: tiles (i, 0..i) in row[0..i], tile j in T orientation when row_is_t(j).
 template <int NB, class RowIsT>
-__device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB], RowIsT row_is_t, float* lds, Lane ln)
+__device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB], RowIsT row_is_t, float* lds, Lane ln,
+                                            float diag = 1.f)
 {
     constexpr int C = 16 * NB;
     const int lane = 16 * ln.q + ln.n;
@@ -606,7 +608,7 @@ __device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB],
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int rr = ln.n, cc = 4 * ln.q + r;
-                    v[r] = (rr == cc) ? 1.f : ((rr > cc) ? v[r] : 0.f);
+                    v[r] = (rr == cc) ? diag : ((rr > cc) ? v[r] : 0.f);
                 }
             }
             *reinterpret_cast<v4f*>(&lds[ln.n * STORE_LD + 16 * j + 4 * ln.q]) = v;
@@ -615,7 +617,7 @@ __device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB],
             for (int r = 0; r < 4; ++r) {
                 const int rr = 4 * ln.q + r, cc = ln.n;
                 float x = v[r];
-                if (i == j) x = (rr == cc) ? 1.f : ((rr > cc) ? x : 0.f);
+                if (i == j) x = (rr == cc) ? diag : ((rr > cc) ? x : 0.f);
                 lds[rr * STORE_LD + 16 * j + cc] = x;
             }
         }
@@ -652,14 +654,15 @@ __device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB],
 }
 
 template <int NB, class IsT>
-__device__ __forceinline__ void store_result(Out Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln)
+__device__ __forceinline__ void store_result(Out Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln,
+                                             float diag = 1.f)
 {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         v4f row[NB];
 #pragma unroll
         for (int j = 0; j <= i; ++j) row[j] = Tt[tix(i, j)];
-        store_strip<NB>(Tm, i, row, [&](int j) { return is_t(i, j); }, lds, ln);
+        store_strip<NB>(Tm, i, row, [&](int j) { return is_t(i, j); }, lds, ln, diag);
     }
 }
 
@@ -823,6 +826,17 @@ template <int OP, int NB, int METHOD, class ASrc, bool REFINE = false>
 __device__ __forceinline__ void invert_and_store(const ASrc& src, Out Tm, float* lds, Lane ln, int aux = 0)
 {
     constexpr int NT = NB * (NB + 1) / 2;
+    if constexpr (METHOD == M_BUILD_A) {
+        // the strictly-lower chunk matrix itself (zero diagonal), strip by strip: at most NB tiles alive at a time
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            v4f row[NB];
+#pragma unroll
+            for (int j = 0; j <= i; ++j) row[j] = src.template get<true>(i, j);
+            store_strip<NB>(Tm, i, row, [](int) { return true; }, lds, ln, 0.f);
+        }
+        return;
+    }
     if (METHOD == M_FWD) {
         if constexpr (NB == 8 && !ASrc::kFromMemory)
             forward_substitution_resident<NB>(src, static_cast<float*>(Tm.base), lds, ln);  // fp32 result only (checked by the host)

@@ -773,3 +773,36 @@ def test_per_channel_gate_with_a_strong_decay(C, op):
     for method in (tri.BLOCK_RECURSIVE, tri.FWD_SUBST, tri.MIXED_B32 if C >= 32 else tri.MIXED, tri.NEUMANN):
         T = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
         check(T, T_ref, TOL[op] if method != tri.FWD_SUBST or op == tri.F32 else 2e-2, f"strong decay C={C} {tri.METHOD_NAMES[method]}")
+
+
+# ------------------------------------------------------------------ the chunk matrices alone
+@pytest.mark.parametrize("gate_kind", [0, 1, 2])
+@pytest.mark.parametrize("C", [16, 32, 64, 128])
+def test_build_A_alone(C, gate_kind):
+    """gdn_chunk_build_A against the oracle's fp64 A (scalar / no gate: exact products of the stored keys, fp32
+    accumulation and gate: 1e-6; per-channel gate: gated keys rounded to the operand type), exact zeros on and
+    above the diagonal, and A -> tri_inv agrees with the fused entry point."""
+    idx = {0: 1, 1: 3, 2: 2}[gate_kind]
+    for d_k in (128, 96):
+        inp = si.make_inputs(si.workload(idx, B=2, Tlen=3 * C + 11, H=3, C=C, d_k=d_k, k_dtype="bf16", gate_kind=gate_kind))
+        A_ref = oracle.build_A_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)
+        K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+        g = None if inp["g"] is None else inp["g"].to(DEV)
+        for op, tol in ((tri.F32, 1e-6), (tri.BF16, 1e-6 if gate_kind != 1 else 1e-2)):
+            A = tri.gdn_chunk_build_A(K, beta, g, C, gate_kind=gate_kind, op_dtype=op)
+            torch.cuda.synchronize()
+            Ah = A.cpu().numpy().astype(np.float64)
+            assert np.array_equal(np.triu(Ah), np.zeros_like(Ah)), "entries on or above the diagonal"
+            num = np.linalg.norm(Ah - A_ref, axis=(1, 2))
+            den = np.maximum(np.linalg.norm(A_ref, axis=(1, 2)), 1e-30)
+            assert (num / den).max() <= tol, (C, gate_kind, d_k, op, (num / den).max())
+        A16 = tri.gdn_chunk_build_A(K, beta, g, C, gate_kind=gate_kind, op_dtype=tri.F32, out_dtype=torch.bfloat16)
+        A32 = tri.gdn_chunk_build_A(K, beta, g, C, gate_kind=gate_kind, op_dtype=tri.F32)
+        torch.cuda.synchronize()
+        assert torch.equal(A16, A32.to(torch.bfloat16))
+        if d_k == 128:
+            T_two = tri.tri_inv_ex(A32, method=tri.BLOCK_DIRECT, op_dtype=tri.F32)
+            T_one = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=gate_kind, method=tri.BLOCK_DIRECT, op_dtype=tri.F32)
+            check(T_two, oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C), 1e-5, "A then tri_inv")
+            torch.cuda.synchronize()
+            assert float((T_two - T_one).abs().max()) <= 1e-5
