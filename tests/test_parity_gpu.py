@@ -451,6 +451,38 @@ def test_full_size_workload_sampled(idx, mo):
     assert float(T.abs().max()) <= 1.0 + (1e-4 if op == tri.F32 else 5e-2)
 
 
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_full_size_workload_every_matrix_by_properties(idx):
+    """Properties that hold at any size, checked on EVERY matrix of the full-size launch: the residual
+    ||(I + A) T - I||_F (A written by gdn_chunk_build_A, which its own test pins to the oracle; products in fp64 on
+    the device) and, for the scalar gate, the similarity T_gated = T_ungated * exp(g_i - g_j) (follows from
+    A_gated = Gamma A Gamma^-1, paper Table 1)."""
+    w = si.WORKLOADS[idx]
+    inp = si.make_inputs(w)
+    K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    C = w.C
+    A = tri.gdn_chunk_build_A(K, beta, g, C, gate_kind=w.gate_kind, op_dtype=tri.F32)
+    eye = torch.eye(C, device=DEV, dtype=torch.float64)
+    for method, op, tol in [(tri.BLOCK_DIRECT, tri.F32, 2e-6), (tri.BLOCK_RECURSIVE, tri.BF16, 2e-3)]:
+        T = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=w.gate_kind, method=method, op_dtype=op)
+        worst = 0.0
+        for m0 in range(0, w.n_mat, 4096):        # in slabs, fp64 on the device
+            Ts = T[m0:m0 + 4096].double()
+            M = A[m0:m0 + 4096].double() + eye
+            R = torch.bmm(M, Ts) - eye
+            nrm = torch.linalg.matrix_norm(R) / (torch.linalg.matrix_norm(M) * torch.linalg.matrix_norm(Ts))
+            assert bool(torch.isfinite(nrm).all())
+            worst = max(worst, float(nrm.max()))
+        assert worst <= tol, (idx, tri.METHOD_NAMES[method], worst)
+    if w.gate_kind == tri.GATE_SCALAR:
+        Tg = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_SCALAR, method=tri.BLOCK_DIRECT, op_dtype=tri.F32)
+        Tu = tri.gdn_chunk_tri_inv_ex(K, beta, None, C, gate_kind=tri.GATE_NONE, method=tri.BLOCK_DIRECT, op_dtype=tri.F32)
+        gg = g.reshape(w.B, w.Tlen // C, C, w.H).permute(0, 1, 3, 2).reshape(-1, C).double()
+        sim = Tu.double() * torch.tril(torch.exp(gg[:, :, None] - gg[:, None, :]))
+        assert float((Tg.double() - sim).abs().max()) <= 2e-6
+
+
 def test_neumann_on_the_stress_input_is_reported_not_asserted(cases, capsys):
     """C = 64 sub-blocks of the stress recipe: large ||A||, the repeated squaring overflows or
     cancels (paper Sec. 3.2, Sec. 4.1).  The library must return whatever the algorithm yields."""
