@@ -172,16 +172,22 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
     }
 }
 
-template <int METHOD> static int go_kda(const GdnArgs& a)
+template <int METHOD, bool REFINE = false> static int go_kda(const GdnArgs& a)
 {
-    hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
+    hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB, REFINE>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
                        a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt);
     return 0;
 }
 
 static int kda_method(const GdnArgs& a)
 {
-    if (a.refine) return 1;
+    if (a.refine) {
+        if constexpr (HAS_REFINE) {
+            if (a.method == M_BLOCK) return go_kda<M_BLOCK, true>(a);
+            if (a.method == M_MIXED) return go_kda<M_MIXED, true>(a);
+        }
+        return 1;
+    }
     switch (a.method) {
 #if TRIINV_INST_FWD
     case M_FWD: return go_kda<M_FWD>(a);

@@ -261,8 +261,11 @@ template <int NB> __host__ __device__ constexpr bool merge_block_is_T(int i, int
     return (2 * h == NB) ? ROOT_T : (((i / (2 * h)) & 1) != 0);
 }
 
+constexpr int WITH_REFINE = 1000;  // METHOD + WITH_REFINE: the tiles of METHOD plus every tile in N orientation (Alg. 6's Y A)
+
 template <int NB, int METHOD> __host__ __device__ constexpr bool need_tile(int i, int j, bool tr)
 {
+    if constexpr (METHOD >= WITH_REFINE) return !tr || need_tile<NB, METHOD - WITH_REFINE>(i, j, tr);
     if (METHOD == M_FWD || METHOD == M_NEWTON_SCHULZ || METHOD == M_BUILD_A) return tr;
     if (METHOD == M_NEUMANN) return true;
     if (METHOD == M_MIXED32 && i / 2 == j / 2) return true;  // the 32 x 32 Neumann blocks want both orientations
@@ -964,7 +967,7 @@ __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restric
 }
 
 // Fused kernel for the per-channel gate: g is [B, Tlen, H, d_k]; the gated keys are rounded to OP.
-template <int OP, int NB, int METHOD, int WPB = 1>
+template <int OP, int NB, int METHOD, int WPB = 1, bool REFINE = false>
 __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T,
                                                           int64_t n_chunk, ChunkMap map, int H, int d_k, int k_dt, int aux, int out_dt)
@@ -984,9 +987,10 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict
     const int64_t esz = (k_dt == OP_F32) ? 4 : 2;
     const int64_t e0 = (tok0 * H + h) * (int64_t)d_k;  // element offset of (token 0, head h, channel 0)
     PreA<NB> src;
-    build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
-                                        beta + tok0 * H + h, H, d_k, lds, ln, pos.valid);
-    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, out_matrix(T, m, C, out_dt), lds, ln, aux);
+    build_A_per_channel<OP, NB, REFINE ? METHOD + WITH_REFINE : METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0,
+                                                                        (int64_t)H * d_k, beta + tok0 * H + h, H, d_k, lds, ln,
+                                                                        pos.valid);
+    invert_and_store<OP, NB, METHOD, PreA<NB>, REFINE>(src, out_matrix(T, m, C, out_dt), lds, ln, aux);
 }
 
 // ---------------------------------------------------------------------------------------------

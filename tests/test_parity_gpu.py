@@ -244,6 +244,18 @@ def test_refinement_step_recovers_digits(cases):
                 assert e1 <= 2.5 * e0 + 1e-7 and f1 <= 2.5 * e0 + 1e-7, (idx, method, op, e0, e1, f1)
 
 
+def test_refinement_step_with_the_per_channel_gate(cases):
+    c = cases[3]
+    w, inp = c["w"], c["inp"]
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    for method in (tri.MIXED, tri.BLOCK_RECURSIVE):
+        for op in (tri.F32, tri.F16, tri.BF16):
+            e0 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=1, method=method, op_dtype=op), c["T"], TOL[op], "per-channel")
+            e1 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=1, method=method, op_dtype=op, flags=1), c["T"], TOL[op],
+                       "per-channel, refined")
+            assert e1 <= 2.5 * e0 + 1e-7, (method, op, e0, e1)
+
+
 def test_refinement_on_the_stress_blocks():
     # C = 64 blocks of the stress recipe: mixed recursion with bf16 operands, before and after one step
     inp = si.make_inputs(si.workload(4, Tlen=512, H=3, C=64))
