@@ -357,3 +357,90 @@ def test_packed_sequences_are_chunked_one_by_one():
     assert np.array_equal(T[c0 * H + h][5:, 5:], np.eye(C - 5))
     # the one-token sequence: A = 0, T = I
     assert np.array_equal(T[1 * H + 0], np.eye(C))
+
+
+# ---------------------------------------------------------------- residual identities of the iterations
+def test_refinement_step_squares_the_left_residual():
+    # Eq. 9: with R = I - Y (I + L), the refined X = Y + R Y has I - X (I + L) = R^2 exactly;
+    # the mirrored update Y + Y R does not (Y is a generic lower-triangular matrix here, so it
+    # does not commute with I + L)
+    rng = np.random.default_rng(11)
+    C = 24
+    L = np.tril(rng.normal(size=(C, C)) * 0.3, -1)
+    M = np.eye(C) + L
+    Y = np.linalg.inv(M) + 0.05 * np.tril(rng.normal(size=(C, C)))
+    R = np.eye(C) - Y @ M
+    X = methods.ir(Y, L)
+    assert np.allclose(np.eye(C) - X @ M, R @ R, atol=1e-12)
+    assert not np.allclose(np.eye(C) - (Y + Y @ R) @ M, R @ R, atol=1e-6)
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 5])
+def test_newton_schulz_squares_the_right_residual(m):
+    # Eq. 8: X <- X (2 I - A X) gives I - A X_m = (I - A X_0)^(2^m) for any start X_0
+    rng = np.random.default_rng(12 + m)
+    C = 16
+    L = np.tril(rng.normal(size=(C, C)) * 0.3, -1)
+    A = np.eye(C) + L
+    X0 = np.linalg.inv(A) + 0.02 * rng.normal(size=(C, C))
+    want = np.linalg.matrix_power(np.eye(C) - A @ X0, 2 ** m)
+    assert np.allclose(np.eye(C) - A @ methods.ns(L, m=m, X0=X0), want, atol=1e-12)
+
+
+def test_newton_schulz_default_start_is_identity_over_n():
+    # Alg. 3 starts from X_0 = I / n: one iteration from it is (2 I - A / n) / n
+    C = 8
+    L = np.tril(np.arange(C * C, dtype=np.float64).reshape(C, C) / 50.0, -1)
+    A = np.eye(C) + L
+    assert np.allclose(methods.ns(L, m=1), (2 * np.eye(C) - A / C) / C, atol=1e-15)
+
+
+# ---------------------------------------------------------------- error measures on hand-computed cases
+def test_error_measures_by_hand():
+    # T_ref = [[1,0],[2,1]], T_hat = [[1,0],[2.5,1]]: diff has the single entry 0.5
+    T_ref = np.array([[[1.0, 0.0], [2.0, 1.0]]])
+    T_hat = np.array([[[1.0, 0.0], [2.5, 1.0]]])
+    e = metrics.forward_errors(T_ref, T_hat)
+    assert e["rel_fro"][0] == pytest.approx(0.5 / math.sqrt(6.0), rel=1e-15)
+    assert e["max_abs"][0] == 0.5
+    assert e["max_rel"][0] == 0.25
+    # (I + A) T_hat - I with A = [[0,0],[-2,0]] is [[0,0],[0.5,0]]
+    A = np.array([[[0.0, 7.0], [-2.0, 9.0]]])          # diagonal and upper part are not read
+    r = metrics.residual(A, T_hat)
+    assert r["abs"][0] == pytest.approx(0.5, rel=1e-15)
+    assert r["normalised"][0] == pytest.approx(0.5 / (math.sqrt(6.0) * math.sqrt(8.25)), rel=1e-15)
+    assert metrics.structure_ok(T_hat)
+    assert not metrics.structure_ok(np.array([[[1.0, 1e-30], [2.0, 1.0]]]))
+    assert not metrics.structure_ok(np.array([[[1.0, 0.0], [2.0, 1.0 + 2.0 ** -40]]]))
+    s = metrics.summarise(np.array([1.0, 3.0, np.nan]))
+    assert s["non_finite"] == 1 and s["max"] == np.inf
+
+
+def test_max_rel_looks_at_the_lower_triangle_only():
+    T_ref = np.array([[[1.0, 0.0], [4.0, 1.0]]])
+    T_hat = np.array([[[1.0, 3.0], [5.0, 1.0]]])
+    assert metrics.forward_errors(T_ref, T_hat)["max_rel"][0] == 0.25
+
+
+# ---------------------------------------------------------------- operand rounding of the emulated precisions
+def test_operand_rounding_is_to_nearest_even():
+    # bf16 keeps 8 significant bits (spacing 2^-7 in [1, 2)), fp16 keeps 11 (spacing 2^-10)
+    u = 2.0 ** -7
+    x = np.array([1.0, 1 + u / 2, 1 + 3 * u / 2, 1 + u / 2 + 2.0 ** -20, 1 + 0.49 * u, -1 - 3 * u / 2, 3.0e38])
+    want = np.array([1.0, 1.0, 1 + 2 * u, 1 + u, 1.0, -1 - 2 * u, 2.0 ** 127 * (1 + 98 / 128)])
+    assert np.array_equal(methods.round_bf16(x), want)
+    assert np.array_equal(methods.round_bf16(x), torch.tensor(x, dtype=torch.float32).bfloat16().double().numpy())
+    h = 2.0 ** -10
+    xh = np.array([1.0, 1 + h / 2, 1 + 3 * h / 2, 1 + 0.51 * h, 65520.0])
+    assert np.array_equal(methods.round_f16(xh), np.array([1.0, 1.0, 1 + 2 * h, 1 + h, np.inf]))
+    assert methods.round_f32(np.array([1 + 2.0 ** -24]))[0] == 1.0
+    assert methods.round_f32(np.array([1 + 3 * 2.0 ** -24]))[0] == 1 + 2.0 ** -22
+
+
+def test_emulated_product_rounds_operands_then_accumulates_exactly():
+    # bf16 operands: 1 + 2^-8 becomes 1 before the product; the fp32 accumulator keeps 2^-20
+    ar = methods.Arith("bf16")
+    X = np.array([[1 + 2.0 ** -8, 2.0 ** -10]])
+    Y = np.array([[1.0], [2.0 ** -10]])
+    assert ar.mm(X, Y)[0, 0] == 1.0 + 2.0 ** -20
+    assert methods.Arith(None).mm(X, Y)[0, 0] == (1 + 2.0 ** -8) + 2.0 ** -20
