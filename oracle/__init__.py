@@ -185,3 +185,31 @@ def gdn_chunk_tri_inv_varlen(K, beta, g, seqlens, gate_kind: int, C: int, n_thre
         t0 += n
     H = K.shape[1]
     return np.concatenate(out, axis=0) if out else np.empty((0, C, C), dtype=np.float64)
+
+
+def gdn_chunk_tri_solve(K, beta, g, X, row_scale, gate_kind: int, C: int, n_threads: int = 0) -> np.ndarray:
+    """W = (I + A)^{-1} diag(s) X chunk by chunk, in fp64 (the chunk-local solve in which the layer uses the
+    inverse, paper Sec. 1 Eq. 3 and Sec. 5.2): X [B, Tlen, H, d_x] stored values widened exactly, s = row_scale
+    [B, Tlen, H] or None (all ones).  Row-oriented forward substitution on the right-hand sides themselves,
+        W_i = s_i X_i - sum_{j < i} A_ij W_j     within each chunk,
+    so the inverse is never formed.  Any Tlen: a short last chunk is the leading block (see _pad_to_chunks).
+    Returns W [B, Tlen, H, d_x]."""
+    import torch
+
+    A = build_A_ragged(K, beta, g, gate_kind, C, n_threads=n_threads)          # [B * n_chunk * H, C, C]
+    Xf = torch.as_tensor(X).cpu().to(torch.float64).numpy()
+    B, Tlen, H, d_x = Xf.shape
+    if row_scale is not None:
+        Xf = Xf * torch.as_tensor(row_scale).cpu().to(torch.float64).numpy()[..., None]
+    n_chunk = -(-Tlen // C)
+    A = A.reshape(B, n_chunk, H, C, C)
+    W = np.zeros((B, Tlen, H, d_x), dtype=np.float64)
+    for c in range(n_chunk):
+        t0 = c * C
+        rows = min(C, Tlen - t0)
+        for i in range(rows):
+            acc = Xf[:, t0 + i].copy()                                          # [B, H, d_x]
+            for j in range(i):
+                acc -= A[:, c, :, i, j][..., None] * W[:, t0 + j]
+            W[:, t0 + i] = acc
+    return W

@@ -444,3 +444,71 @@ def test_emulated_product_rounds_operands_then_accumulates_exactly():
     Y = np.array([[1.0], [2.0 ** -10]])
     assert ar.mm(X, Y)[0, 0] == 1.0 + 2.0 ** -20
     assert methods.Arith(None).mm(X, Y)[0, 0] == (1 + 2.0 ** -8) + 2.0 ** -20
+
+
+# ---------------------------------------------------------------- chunk-local solve W = (I + A)^{-1} diag(s) X
+def _solve_case(seed, B=2, Tlen=96, H=3, d_k=32, d_x=24, gate_kind=0):
+    rng = np.random.default_rng(seed)
+    K = rng.normal(size=(B, Tlen, H, d_k)).astype(np.float32)
+    K /= np.linalg.norm(K, axis=-1, keepdims=True)
+    beta = rng.uniform(0.1, 1.0, size=(B, Tlen, H)).astype(np.float32)
+    shape = (B, Tlen, H, d_k) if gate_kind == 1 else (B, Tlen, H)
+    g = None if gate_kind == 2 else np.cumsum(-rng.uniform(0.0, 0.1, size=shape), axis=1).astype(np.float32)
+    X = rng.normal(size=(B, Tlen, H, d_x)).astype(np.float32)
+    s = rng.uniform(0.5, 1.5, size=(B, Tlen, H)).astype(np.float32)
+    return K, beta, g, X, s
+
+
+@pytest.mark.parametrize("gate_kind,Tlen,C", [(0, 96, 32), (1, 64, 16), (2, 100, 32), (0, 37, 64)])
+def test_chunk_solve_against_library_triangular_solve(gate_kind, Tlen, C):
+    K, beta, g, X, s = _solve_case(21 + gate_kind, Tlen=Tlen, gate_kind=gate_kind)
+    W = oracle.gdn_chunk_tri_solve(K, beta, g, X, s, gate_kind, C)
+    B, _, H, d_x = X.shape
+    for b in range(B):
+        for h in range(H):
+            for t0 in range(0, Tlen, C):
+                t1 = min(Tlen, t0 + C)
+                # the short block's own matrix from an explicit double loop
+                n = t1 - t0
+                A = np.zeros((n, n))
+                for i in range(n):
+                    for j in range(i):
+                        k_i, k_j = K[b, t0 + i, h].astype(np.float64), K[b, t0 + j, h].astype(np.float64)
+                        if gate_kind == 0:
+                            w = math.exp(float(g[b, t0 + i, h]) - float(g[b, t0 + j, h])) * (k_i @ k_j)
+                        elif gate_kind == 1:
+                            w = float(np.sum(k_i * k_j * np.exp(g[b, t0 + i, h].astype(np.float64) - g[b, t0 + j, h].astype(np.float64))))
+                        else:
+                            w = k_i @ k_j
+                        A[i, j] = float(beta[b, t0 + i, h]) * w
+                rhs = s[b, t0:t1, h, None].astype(np.float64) * X[b, t0:t1, h].astype(np.float64)
+                want = scipy.linalg.solve_triangular(np.eye(n) + A, rhs, lower=True, unit_diagonal=True)
+                assert np.allclose(W[b, t0:t1, h], want, rtol=1e-11, atol=1e-12), (b, h, t0)
+
+
+def test_chunk_solve_is_the_inverse_applied():
+    K, beta, g, X, s = _solve_case(31, Tlen=128)
+    C = 64
+    W = oracle.gdn_chunk_tri_solve(K, beta, g, X, s, 0, C)
+    T = oracle.gdn_chunk_tri_inv(K, beta, g, 0, C).reshape(2, 2, 3, C, C)        # [B, chunk, H, C, C]
+    sX = (s[..., None].astype(np.float64) * X).reshape(2, 2, C, 3, -1)           # [B, chunk, C, H, d_x]
+    want = np.einsum("bchij,bcjhx->bcihx", T, sX).reshape(W.shape)
+    assert np.allclose(W, want, rtol=1e-11, atol=1e-12)
+    # no scale = scale of ones
+    assert np.array_equal(oracle.gdn_chunk_tri_solve(K, beta, g, X, None, 0, C),
+                          oracle.gdn_chunk_tri_solve(K, beta, g, X, np.ones_like(s), 0, C))
+
+
+def test_chunk_solve_closed_form_differences():
+    # all keys equal and of unit length, beta = 1, no gate: I + A is the lower-triangular all-ones matrix,
+    # whose inverse takes first differences within each chunk: W_0 = X_0, W_i = X_i - X_{i-1}
+    B, Tlen, H, d_k, d_x, C = 1, 48, 2, 8, 5, 16
+    K = np.zeros((B, Tlen, H, d_k), dtype=np.float32)
+    K[..., 3] = 1.0
+    beta = np.ones((B, Tlen, H), dtype=np.float32)
+    X = np.random.default_rng(7).normal(size=(B, Tlen, H, d_x)).astype(np.float32)
+    W = oracle.gdn_chunk_tri_solve(K, beta, None, X, None, 2, C)
+    want = X.astype(np.float64).copy()
+    want[:, 1:] -= X[:, :-1]
+    want[:, ::C] = X[:, ::C]
+    assert np.allclose(W, want, atol=1e-13)
