@@ -61,6 +61,8 @@ def main() -> int:
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--solve", type=int, default=0, metavar="D_X",
+                    help="also time gdn_chunk_tri_solve (the inverse applied to D_X right-hand-side columns instead of stored)")
     ap.add_argument("--accuracy", action="store_true",
                     help="instead of timing: error and residual of every method / operand type against the oracle on "
                          "sampled matrices of the full-size workload, fused entry point and (scalar / no gate) standalone")
@@ -304,6 +306,46 @@ def main() -> int:
     }
     if copy_ref is not None:
         out["copy_ref"] = copy_ref
+
+    if args.solve and C <= 64:
+        # W = (I + A)^{-1} diag(s) X with X, W [B, Tlen, H, d_x] in the operand type: same rotation over buffer sets
+        d_x = args.solve
+        xdt = {0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[args.op]
+        rhs = si.make_rhs(w, d_x, xdt)
+        Xs = [rhs["X"].to(dev) for _ in sets]
+        Ws = [torch.empty_like(x) for x in Xs]
+        scale = rhs["row_scale"].to(dev)
+
+        def solve_step(i):
+            K, beta, g, _ = sets[i % len(sets)]
+            tri.gdn_chunk_tri_solve(K, beta, g, Xs[i % len(sets)], C, row_scale=scale, W=Ws[i % len(sets)], gate_kind=w.gate_kind,
+                                    method=args.method)
+
+        for i in range(args.warmup):
+            solve_step(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            solve_step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        esz = 4 if args.op == 0 else 2
+        # inputs of the fused kernel (everything but T) + the row scale + X in + W out
+        bpm = algorithmic_bytes_per_matrix(w, True) - 4 * C * C + 4 * C + 2 * C * d_x * esz
+        # sampled check against the oracle: the first and the last batch entry's rows
+        b_sel = sorted({0, w.B - 1})
+        W_ref = oracle.gdn_chunk_tri_solve(inp["K"][b_sel], inp["beta"][b_sel], None if inp["g"] is None else inp["g"][b_sel],
+                                           rhs["X"][b_sel], rhs["row_scale"][b_sel], w.gate_kind, C)
+        W_gpu = Ws[(args.steps - 1) % len(sets)][b_sel].float().cpu().numpy().astype(np.float64)
+        rel = float((np.sqrt(((W_gpu - W_ref) ** 2).sum(axis=(1, 3))) / np.sqrt((W_ref ** 2).sum(axis=(1, 3)))).max())
+        out["solve"] = {"entry": "gdn_chunk_tri_solve", "d_x": d_x, "x_dtype": tri.DTYPE_NAMES[args.op], "kernel_ms_avg": ms,
+                        "matrices_per_s": n_mat / (ms * 1e-3), "algorithmic_bytes_per_matrix": bpm,
+                        "GBps": bpm * n_mat / (ms * 1e-3) / 1e9, "hbm_frac": bpm * n_mat / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "rel_fro_max_sampled": rel, "tolerance": 1e-5 if args.op == 0 else 2e-2,
+                        "ok": bool(rel <= (1e-5 if args.op == 0 else 2e-2))}
+        del Xs, Ws
 
     if args.table:
         table = []

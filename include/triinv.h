@@ -79,9 +79,9 @@ typedef enum {
     TRIINV_ERR_BAD_DTYPE = -3,   /* unknown in_dtype / k_dtype / op_dtype */
     TRIINV_ERR_BAD_METHOD = -4,  /* unknown method or gate kind */
     TRIINV_ERR_BAD_SHAPE = -5,   /* n_mat < 0; B, H, d_k <= 0; Tlen < 0; d_k % 32 != 0; d_k > 256; more than 2^31 - 1 matrices;
-                                    inconsistent varlen totals */
+                                    inconsistent varlen totals; d_x not a multiple of 8 in [8, 512] */
     TRIINV_ERR_ALIGN = -6,       /* a pointer is not 16-byte aligned */
-    TRIINV_ERR_ALIAS = -7,       /* T overlaps an input buffer */
+    TRIINV_ERR_ALIAS = -7,       /* T (or W) overlaps an input buffer */
     TRIINV_ERR_LAUNCH = -8,      /* the HIP runtime refused the launch */
     TRIINV_ERR_UNSUPPORTED = -9  /* valid arguments, but this combination is not built */
 } triinv_status;
@@ -209,6 +209,34 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
                              int64_t total_tokens, int64_t total_chunks, int H, int d_k, int C,
                              int k_dtype, int gate_kind, int method, int op_dtype,
                              void* hip_stream, uint32_t flags);
+
+/*
+ * gdn_chunk_tri_solve: the fused operation with the inverse applied instead of stored,
+ *     W = (I + A)^{-1} diag(s) X      chunk by chunk,
+ * the form in which the layer consumes the inverse (paper Sec. 1 Eq. 3; direction of the fused layer
+ * kernel of Sec. 5.2): A is built from K, beta, g and inverted in registers exactly as in
+ * gdn_chunk_tri_inv_ex, the columns of the inverse are scaled by s in fp32, rounded to op_dtype and
+ * multiplied into the chunk's rows of X on the matrix cores (fp32 accumulation).  Neither A nor the
+ * inverse goes to memory.
+ *   X          device, [B][Tlen][H][d_x], stored in op_dtype (fp32, fp16 or bf16), 16-byte aligned;
+ *              d_x a multiple of 8, 8 <= d_x <= 512.  Read only.
+ *   row_scale  device, fp32 [B][Tlen][H], or NULL for s = 1 (e.g. beta itself, or beta * exp(g)).
+ *   W          device, [B][Tlen][H][d_x], same element type as X, 16-byte aligned; written by the
+ *              call (rows of a short last chunk's padding do not exist and are not written).  Must
+ *              not overlap X.  Caller-owned.
+ *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
+ *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R); C in {16, 32, 64};
+ *              d_k = 64 or 128 for the scalar / no-gate kinds, any supported d_k for the per-channel
+ *              gate.  Anything else returns TRIINV_ERR_UNSUPPORTED.
+ *   flags      TRIINV_FLAG_MXR_R only.
+ * Accuracy: that of the method's inverse (see tri_inv_ex) plus one rounding of the scaled inverse
+ * and of W to op_dtype.
+ */
+int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g,
+                        const void* X, const float* row_scale, void* W,
+                        int B, int64_t Tlen, int H, int d_k, int d_x, int C,
+                        int k_dtype, int gate_kind, int method, int op_dtype,
+                        void* hip_stream, uint32_t flags);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* triinv_status_string(int status);

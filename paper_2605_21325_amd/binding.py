@@ -42,7 +42,7 @@ METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUM
 DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
 
 EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "gdn_chunk_tri_inv_varlen", "gdn_chunk_build_A",
-           "triinv_status_string", "triinv_version")
+           "gdn_chunk_tri_solve", "triinv_status_string", "triinv_version")
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.gdn_chunk_tri_inv_varlen.restype = i32
         L.gdn_chunk_build_A.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, vp, u32]
         L.gdn_chunk_build_A.restype = i32
+        L.gdn_chunk_tri_solve.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, i32, i32, vp, u32]
+        L.gdn_chunk_tri_solve.restype = i32
         L.triinv_status_string.argtypes = [i32]
         L.triinv_status_string.restype = ctypes.c_char_p
         L.triinv_version.argtypes = []
@@ -231,3 +233,26 @@ def gdn_chunk_build_A(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Ten
     if st != OK:
         raise TriInvError(st, "gdn_chunk_build_A")
     return A
+
+
+def gdn_chunk_tri_solve(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], X: torch.Tensor, C: int,
+                        row_scale: Optional[torch.Tensor] = None, W: Optional[torch.Tensor] = None,
+                        gate_kind: int = GATE_SCALAR, method: int = BLOCK_RECURSIVE, stream=None, flags: int = 0) -> torch.Tensor:
+    """W = (I + A)^{-1} diag(row_scale) X chunk by chunk: K [B, Tlen, H, d_k], X and W [B, Tlen, H, d_x]; the element type
+    of X is the operand type of every product."""
+    B, Tlen, H, d_k = K.shape
+    d_x = X.shape[-1]
+    if tuple(X.shape[:3]) != (B, Tlen, H):
+        raise ValueError("X must be [B, Tlen, H, d_x]")
+    if W is None:
+        W = torch.empty_like(X)
+    elif W.shape != X.shape or W.dtype != X.dtype:
+        raise ValueError("W must have the shape and element type of X")
+    gp = None if g is None else _dev(g, "g")
+    sp = None if row_scale is None else _dev(row_scale, "row_scale")
+    st = lib().gdn_chunk_tri_solve(_dev(K, "K"), _dev(beta, "beta"), gp, _dev(X, "X") if X.numel() else None, sp,
+                                   _dev(W, "W") if W.numel() else None, B, Tlen, H, d_k, d_x, C, dtype_code(K.dtype), gate_kind,
+                                   method, dtype_code(X.dtype), _stream_ptr(stream), flags)
+    if st != OK:
+        raise TriInvError(st, "gdn_chunk_tri_solve")
+    return W

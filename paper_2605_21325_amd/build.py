@@ -34,6 +34,9 @@ UNITS = [
 ] + [
     (f"inst_nb{nb}_op{op}", "inst.hip", [f"-DTRIINV_INST_NB={nb}", f"-DTRIINV_INST_OP={op}"])
     for nb in (8, 4, 2, 1) for op in (0, 1, 2)
+] + [
+    (f"solve_nb{nb}_op{op}", "solve.hip", [f"-DTRIINV_INST_NB={nb}", f"-DTRIINV_INST_OP={op}"])
+    for nb in (4, 2, 1) for op in (0, 1, 2)
 ] + [("api", "api.hip", [])]
 
 

@@ -39,6 +39,15 @@ struct GdnArgs {
     int out_dt;
 };
 
+// gdn_chunk_tri_solve: the fused arguments (T unused) plus the right-hand sides.
+struct SolveArgs {
+    GdnArgs f;
+    const void* X;       // [tokens][H][d_x], element type = operand type
+    const float* scale;  // [tokens][H] or null
+    void* W;             // [tokens][H][d_x]
+    int d_x;
+};
+
 // Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.
 #define TRIINV_DECL(NB, OP)                                  \
     int launch_tri_inv_nb##NB##_op##OP(const TriInvArgs& a); \
@@ -57,6 +66,14 @@ TRIINV_DECL(8, 0)
 TRIINV_DECL(8, 1)
 TRIINV_DECL(8, 2)
 #undef TRIINV_DECL
+#define TRIINV_DECL_SOLVE(NB) \
+    int launch_solve_nb##NB##_op0(const SolveArgs& a); \
+    int launch_solve_nb##NB##_op1(const SolveArgs& a); \
+    int launch_solve_nb##NB##_op2(const SolveArgs& a);
+TRIINV_DECL_SOLVE(1)
+TRIINV_DECL_SOLVE(2)
+TRIINV_DECL_SOLVE(4)
+#undef TRIINV_DECL_SOLVE
 int launch_tri_inv_nb1_op0_fwd(const TriInvArgs& a);
 int launch_tri_inv_nb2_op0_fwd(const TriInvArgs& a);
 int launch_tri_inv_nb4_op0_fwd(const TriInvArgs& a);

@@ -1,0 +1,75 @@
+// Instantiations of the apply-instead-of-store kernels (solve.hpp) for one (C = 16 * TRIINV_INST_NB,
+// operand type TRIINV_INST_OP) pair: blocked and mixed recursion, C <= 64.
+#include "dispatch.hpp"
+#include "solve.hpp"
+
+#ifndef TRIINV_INST_NB
+#error "compile with -DTRIINV_INST_NB=1|2|4 -DTRIINV_INST_OP=0|1|2"
+#endif
+
+namespace triinv {
+
+#define CAT_(a, b, c, d) a##b##c##d
+#define CAT(a, b, c, d) CAT_(a, b, c, d)
+
+constexpr int NB = TRIINV_INST_NB;
+constexpr int OP = TRIINV_INST_OP;
+constexpr int WPB = 4;  // four adjacent heads per workgroup, as in the storing kernels
+
+// Two wavefronts per SIMD for the 16-bit-operand kernels at C = 64 (see the storing kernels: they are bound
+// by the memory system and measured slower with more wavefronts resident).
+constexpr unsigned PAD = (NB == 4 && OP != OP_F32) ? 24576u : 0u;
+
+#ifndef TRIINV_SOLVE_XPOS
+#define TRIINV_SOLVE_XPOS 1
+#endif
+constexpr int XPOS = TRIINV_SOLVE_XPOS;
+
+static RhsArgs rhs_of(const SolveArgs& a) { return RhsArgs{a.X, a.scale, a.W, a.d_x}; }
+
+template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
+{
+    const GdnArgs& f = a.f;
+    hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS>), dim3((unsigned)((f.n_mat + WPB - 1) / WPB)), dim3(64 * WPB),
+                       PAD, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+    return 0;
+}
+
+template <int KD, int DKS> static int gdn_method(const SolveArgs& a)
+{
+    if (a.f.method == M_BLOCK) return go_gdn<KD, M_BLOCK, DKS>(a);
+    if (a.f.method == M_MIXED) return go_gdn<KD, M_MIXED, DKS>(a);
+    return 1;
+}
+
+template <int METHOD> static int go_kda(const SolveArgs& a)
+{
+    const GdnArgs& f = a.f;
+    hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB>), dim3((unsigned)((f.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
+                       f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.k_dt, f.iters);
+    return 0;
+}
+
+int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a)
+{
+    const GdnArgs& f = a.f;
+    if (f.refine) return 1;
+    if (f.gate == G_CHANNEL) {
+        if (f.method == M_BLOCK) return go_kda<M_BLOCK>(a);
+        if (f.method == M_MIXED) return go_kda<M_MIXED>(a);
+        return 1;
+    }
+    if (f.k_dt == OP_F32) {
+        if (f.d_k == 64) return gdn_method<OP_F32, 4>(a);
+        if (f.d_k == 128) return gdn_method<OP_F32, 8>(a);
+    } else if (f.k_dt == OP_BF16) {
+        if (f.d_k == 64) return gdn_method<OP_BF16, 2>(a);
+        if (f.d_k == 128) return gdn_method<OP_BF16, 4>(a);
+    } else {
+        if (f.d_k == 64) return gdn_method<OP_F16, 2>(a);
+        if (f.d_k == 128) return gdn_method<OP_F16, 4>(a);
+    }
+    return 1;
+}
+
+}  // namespace triinv

@@ -1,0 +1,264 @@
+// The inverse applied instead of stored:  W = (I + A)^{-1} diag(s) X  for one chunk (paper Sec. 1 Eq. 3;
+// direction of the fused layer kernel of Sec. 5.2).  After the blocked / mixed recursion the tiles of the
+// inverse sit in one wavefront's registers; they are brought to T orientation (the left-factor form of
+// tn()), their columns scaled by s, rounded to the operand type, and multiplied into the chunk's rows of
+// X on the matrix cores.  Neither A nor the inverse goes to memory.
+//
+// Column map of X and W.  The matrix-core column index n of a tile is free to stand for any memory
+// column as long as the result is stored under the same map, so lane (q, n) owns the EIGHT CONSECUTIVE
+// memory columns 128 gi + 8n .. 8n + 7 of a 128-column group gi and column tile c of the group takes
+// column 8n + c from every lane.  One 16-byte load per (row, lane) then feeds eight tiles, one 16-byte
+// store per (row, lane) takes one result from each of eight accumulator tiles, every memory instruction
+// moves whole 256-byte row segments (16 lanes x 16 B, four rows per instruction), and neither X nor W
+// passes through LDS.  Lanes whose columns lie beyond d_x compute on a clamped address and store nothing.
+#pragma once
+#include "kernels.hpp"
+
+namespace triinv {
+
+struct RhsArgs {
+    const void* X;       // [tokens][H][d_x], element type = operand type
+    const float* scale;  // [tokens][H] or null
+    void* W;             // [tokens][H][d_x]
+    int d_x;
+};
+
+// Eight consecutive columns of one row of X as stored.
+template <int OP> struct XRow8;
+template <> struct XRow8<OP_F32> { v4f a, b; };
+template <> struct XRow8<OP_F16> { v4u u; };
+template <> struct XRow8<OP_BF16> { v4u u; };
+
+template <int OP> __device__ __forceinline__ XRow8<OP> load_x8(const char* p)
+{
+    if constexpr (OP == OP_F32) {
+        return {*reinterpret_cast<const v4f*>(p), *reinterpret_cast<const v4f*>(p + 16)};
+    } else {
+        return {*reinterpret_cast<const v4u*>(p)};
+    }
+}
+
+// Column tile c of a 16-row tile row of X as a matrix-core operand: rows 4q + r (r = 0..3) of this lane's column 8n + c.
+template <int OP> __device__ __forceinline__ Opnd<OP> x_operand(const XRow8<OP> (&row)[4], int c)
+{
+    if constexpr (OP == OP_F32) {
+        v4f v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = c < 4 ? row[r].a[c & 3] : row[r].b[c & 3];
+        return {v};
+    } else {
+        const int d = c >> 1;
+        uint32_t lo, hi;
+        if (c & 1) {  // upper halves of the dwords
+            lo = (row[0].u[d] >> 16) | (row[1].u[d] & 0xffff0000u);
+            hi = (row[2].u[d] >> 16) | (row[3].u[d] & 0xffff0000u);
+        } else {
+            lo = (row[0].u[d] & 0xffffu) | (row[1].u[d] << 16);
+            hi = (row[2].u[d] & 0xffffu) | (row[3].u[d] << 16);
+        }
+        Opnd<OP> o;
+        o.x = __builtin_bit_cast(decltype(o.x), v2u{lo, hi});
+        return o;
+    }
+}
+
+// The right-hand sides of one chunk and head.
+template <int OP, int NB> struct RhsX {
+    static constexpr int ESZ = OP == OP_F32 ? 4 : 2;
+    const char* xc;      // element (chunk row 0, this head, column 0) of X
+    char* wc;            // the same element of W
+    int64_t row_bytes;   // H * d_x * ESZ
+    int d_x, valid;
+    Lane ln;
+    v4f s_q[NB];         // s of rows 16 j + 4 q + r
+    XRow8<OP> raw[NB][4];
+
+    // first token of the chunk tok0, head h; starts the loads of s
+    __device__ __forceinline__ void init(const RhsArgs& a, int64_t tok0, int h, int H, int valid_, Lane ln_)
+    {
+        ln = ln_;
+        d_x = a.d_x;
+        valid = valid_;
+        row_bytes = (int64_t)H * d_x * ESZ;
+        const int64_t e0 = (tok0 * H + h) * (int64_t)d_x * ESZ;
+        xc = static_cast<const char*>(a.X) + e0;
+        wc = static_cast<char*>(a.W) + e0;
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * j + 4 * ln.q + r;
+                const int rc = row < valid ? row : valid - 1;
+                s_q[j][r] = a.scale ? a.scale[(tok0 + rc) * H + h] : 1.f;
+            }
+    }
+
+    __device__ __forceinline__ bool active(int gi) const { return 128 * gi + 8 * ln.n < d_x; }
+
+    // loads of column group gi: rows beyond the chunk's last token read that token (they only meet zero columns of the inverse)
+    __device__ __forceinline__ void issue(int gi)
+    {
+        const int col = active(gi) ? 128 * gi + 8 * ln.n : 0;
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * j + 4 * ln.q + r;
+                const int rc = row < valid ? row : valid - 1;
+                raw[j][r] = load_x8<OP>(xc + rc * row_bytes + col * ESZ);
+            }
+    }
+
+    // rows 16 i + 4 q + r of the result, eight columns per lane: acc[c][r]
+    __device__ __forceinline__ void store(int gi, int i, const v4f (&acc)[8])
+    {
+        if (!active(gi)) return;
+        const int col = 128 * gi + 8 * ln.n;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = 16 * i + 4 * ln.q + r;
+            if (row >= valid) continue;
+            char* p = wc + row * row_bytes + col * ESZ;
+            if constexpr (OP == OP_F32) {
+                __builtin_nontemporal_store(v4f{acc[0][r], acc[1][r], acc[2][r], acc[3][r]}, reinterpret_cast<v4f*>(p));
+                __builtin_nontemporal_store(v4f{acc[4][r], acc[5][r], acc[6][r], acc[7][r]}, reinterpret_cast<v4f*>(p + 16));
+            } else if constexpr (OP == OP_F16) {
+                __builtin_nontemporal_store(v4u{pack2_f16(acc[0][r], acc[1][r]), pack2_f16(acc[2][r], acc[3][r]),
+                                                pack2_f16(acc[4][r], acc[5][r]), pack2_f16(acc[6][r], acc[7][r])},
+                                            reinterpret_cast<v4u*>(p));
+            } else {
+                __builtin_nontemporal_store(v4u{pack2_bf16(acc[0][r], acc[1][r]), pack2_bf16(acc[2][r], acc[3][r]),
+                                                pack2_bf16(acc[4][r], acc[5][r]), pack2_bf16(acc[6][r], acc[7][r])},
+                                            reinterpret_cast<v4u*>(p));
+            }
+        }
+    }
+};
+
+// Recursion (blocked, or mixed with aux refinement steps on the leaves), then W = T diag(s) X.
+// ISSUE_X: start the loads of X's first column group here, after the recursion (otherwise the caller has
+// called x.issue(0)).  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
+template <int OP, int NB, int METHOD, bool ISSUE_X, class ASrc>
+__device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& x, float* lds, Lane ln, int aux)
+{
+    static_assert(METHOD == M_BLOCK || METHOD == M_MIXED, "built for the blocked and the mixed recursion");
+    constexpr int NT = NB * (NB + 1) / 2;
+    Opnd<OP> Top[NT];
+    {
+        v4f Tt[NT];
+        constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE;
+        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln, aux);
+        if constexpr (ISSUE_X) x.issue(0);
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                v4f t = Tt[tix(i, j)];
+                if (!result_is_T<NB, ROOT_T>(i, j)) t = transpose_tile(t, lds, ln);
+                // t[r] = T[16 i + n][16 j + 4 q + r]: exact unit diagonal, zeros above it, column scale
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int rr = ln.n, cc = 4 * ln.q + r;
+                    float v = t[r];
+                    if (i == j) v = (rr == cc) ? 1.f : ((rr > cc) ? v : 0.f);
+                    t[r] = v * x.s_q[j][r];
+                }
+                Top[tix(i, j)] = pack<OP>(t);
+            }
+    }
+    const int n_group = (x.d_x + 127) / 128;
+    for (int gi = 0;;) {
+        Opnd<OP> xo[NB][8];
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) xo[j][c] = x_operand<OP>(x.raw[j], c);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            v4f acc[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[c] = zero4();
+#pragma unroll
+            for (int j = 0; j <= i; ++j)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[c] = tn<OP>(Top[tix(i, j)], xo[j][c], acc[c]);
+            x.store(gi, i, acc);
+        }
+        if (++gi >= n_group) break;
+        x.issue(gi);
+    }
+}
+
+// XPOS: where X's first loads are issued -- 1: between the Gram products and the recursion, 2: after the recursion.
+template <int KD, int OP, int NB, int METHOD, int DKS, int WPB, int XPOS>
+__global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
+                                                            const float* __restrict__ g, RhsArgs rhs, int64_t n_chunk, ChunkMap map,
+                                                            int H, int d_k, int aux)
+{
+    constexpr int C = 16 * NB;
+    constexpr int CORE = core_lds_floats<NB, METHOD, true>();
+    constexpr int GATE = gate_lds_floats<NB>();
+    constexpr int PER_WAVE = CORE > GATE ? CORE : GATE;
+    __shared__ __attribute__((aligned(16))) float lds_all[WPB * PER_WAVE];
+    float* lds = lds_all + ((WPB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * PER_WAVE;
+    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H);  // chunk id * H + h
+    if (m < 0) return;
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
+    const Lane ln = lane_id();
+    GramA<KD, NB, DKS> src;
+    src.ln = ln;
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
+    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
+    RhsX<OP, NB> x;
+    x.init(rhs, tok0, h, H, pos.valid, ln);
+    src.stage_gate(lds);
+    if constexpr (XPOS == 1) {
+        // every tile of A first (the key registers are free afterwards), then X's loads, then the recursion
+        PreA<NB> pre;
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                if (need_tile<NB, METHOD>(i, j, false)) pre.n[tix(i, j)] = src.template get<false>(i, j);
+                if (need_tile<NB, METHOD>(i, j, true)) pre.t[tix(i, j)] = src.template get<true>(i, j);
+            }
+        x.issue(0);
+        invert_and_apply<OP, NB, METHOD, false>(pre, x, lds, ln, aux);
+    } else {
+        invert_and_apply<OP, NB, METHOD, true>(src, x, lds, ln, aux);
+    }
+}
+
+template <int OP, int NB, int METHOD, int WPB>
+__global__ __launch_bounds__(64 * WPB) void k_kda_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
+                                                            const float* __restrict__ g, RhsArgs rhs, int64_t n_chunk, ChunkMap map,
+                                                            int H, int d_k, int k_dt, int aux)
+{
+    constexpr int C = 16 * NB;
+    constexpr int CORE = core_lds_floats<NB, METHOD, true>();
+    constexpr int PER_WAVE = CORE > C ? CORE : C;
+    __shared__ __attribute__((aligned(16))) float lds_all[WPB * PER_WAVE];
+    float* lds = lds_all + ((WPB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * PER_WAVE;
+    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H);
+    if (m < 0) return;
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
+    const Lane ln = lane_id();
+    const int64_t esz = (k_dt == OP_F32) ? 4 : 2;
+    const int64_t e0 = (tok0 * H + h) * (int64_t)d_k;
+    PreA<NB> src;
+    build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
+                                        beta + tok0 * H + h, H, d_k, lds, ln, pos.valid);
+    RhsX<OP, NB> x;  // after the Gram passes, which need the registers
+    x.init(rhs, tok0, h, H, pos.valid, ln);
+    x.issue(0);
+    invert_and_apply<OP, NB, METHOD, false>(src, x, lds, ln, aux);
+}
+
+}  // namespace triinv

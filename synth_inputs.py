@@ -138,3 +138,14 @@ def random_strict_lower(n_mat: int, C: int, scale: float, seed: int, garbage_upp
     else:
         A = torch.where(lower, A, torch.zeros(()))
     return A.contiguous()
+
+
+def make_rhs(w: Workload, d_x: int, dtype: torch.dtype = torch.bfloat16, seed_offset: int = 0) -> dict:
+    """Right-hand sides for the chunk-local solve on workload `w`: X [B, Tlen, H, d_x] ~ N(0, 1) (the layer's
+    value / key rows), stored in `dtype`, and a positive per-token row scale [B, Tlen, H] in (0, 1) (a beta-like
+    factor), from a generator of their own so that make_inputs' draws are unchanged."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(SEED_BASE + 100 + w.index + 1000003 * seed_offset)
+    X = torch.randn(w.B, w.Tlen, w.H, d_x, generator=gen, dtype=torch.float32).to(dtype)
+    s = torch.sigmoid(torch.randn(w.B, w.Tlen, w.H, generator=gen, dtype=torch.float32))
+    return {"X": X.contiguous(), "row_scale": s.contiguous()}

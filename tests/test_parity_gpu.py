@@ -850,3 +850,102 @@ def test_build_A_alone(C, gate_kind):
             check(T_two, oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C), 1e-5, "A then tri_inv")
             torch.cuda.synchronize()
             assert float((T_two - T_one).abs().max()) <= 1e-5
+
+
+# ------------------------------------------------------------------ the inverse applied: W = (I + A)^{-1} diag(s) X
+XDT = {tri.F32: torch.float32, tri.F16: torch.float16, tri.BF16: torch.bfloat16}
+# fp32: products and sums in fp32 throughout; 16-bit: the inverse's tolerance plus one rounding of the scaled inverse
+# and one of W to the 16-bit type (2^-9 each for bf16) -- still inside 2e-2
+SOLVE_TOL = {tri.F32: 1e-5, tri.F16: 2e-2, tri.BF16: 2e-2}
+
+
+def check_solve(W_gpu, W_ref, tol, what):
+    torch.cuda.synchronize()
+    Wg = W_gpu.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(Wg).all(), f"{what}: non-finite output"
+    B, Tlen, H, d_x = Wg.shape
+    # relative Frobenius error per (batch, head) over all of that head's rows
+    num = np.sqrt(((Wg - W_ref) ** 2).sum(axis=(1, 3)))
+    den = np.sqrt((W_ref ** 2).sum(axis=(1, 3)))
+    err = (num / den).max()
+    assert err <= tol, f"{what}: rel_fro max {err:.3e} > {tol}"
+    return err
+
+
+def solve_case(idx, d_x, op, **kw):
+    w = si.workload(idx, **kw)
+    inp = si.make_inputs(w)
+    rhs = si.make_rhs(w, d_x, XDT[op])
+    return w, inp, rhs
+
+
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("method", [tri.BLOCK_RECURSIVE, tri.MIXED], ids=lambda m: tri.METHOD_NAMES[m])
+@pytest.mark.parametrize("idx,kw", [(0, {}), (1, dict(Tlen=512)), (2, dict(B=2, Tlen=256, H=5)), (3, dict(B=1, Tlen=256, H=3))])
+def test_solve_matches_oracle(idx, kw, method, op):
+    w, inp, rhs = solve_case(idx, 128, op, **kw)
+    W_ref = oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], rhs["row_scale"], w.gate_kind, w.C)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    W = tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), g, rhs["X"].to(DEV), w.C,
+                                row_scale=rhs["row_scale"].to(DEV), gate_kind=w.gate_kind, method=method)
+    check_solve(W, W_ref, SOLVE_TOL[op], f"cfg{idx} {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}")
+
+
+@pytest.mark.parametrize("d_x", [8, 64, 72, 128, 200, 256, 512])
+@pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+def test_solve_column_counts(d_x, op):
+    # part of a 128-column group, exactly one, several, and a last group that is not full
+    w, inp, rhs = solve_case(1, d_x, op, Tlen=192, H=4)
+    W_ref = oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], None, w.gate_kind, w.C)
+    W = torch.full(rhs["X"].shape, float("nan"), dtype=XDT[op], device=DEV)
+    tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), rhs["X"].to(DEV), w.C, W=W)
+    check_solve(W, W_ref, SOLVE_TOL[op], f"d_x={d_x}")          # every element written (no NaN left), none beyond
+
+
+@pytest.mark.parametrize("C", [16, 32, 64])
+@pytest.mark.parametrize("Tlen", [1, 50, 64, 150])
+@pytest.mark.parametrize("gate_kind", [tri.GATE_SCALAR, tri.GATE_PER_CHANNEL, tri.GATE_NONE])
+def test_solve_chunk_sizes_and_short_last_chunk(C, Tlen, gate_kind):
+    idx = {tri.GATE_SCALAR: 1, tri.GATE_PER_CHANNEL: 3, tri.GATE_NONE: 4}[gate_kind]
+    w, inp, rhs = solve_case(idx, 64, tri.BF16, B=2, Tlen=Tlen, H=3, C=C)
+    W_ref = oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], rhs["row_scale"], gate_kind, C)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    # W sits inside a larger allocation filled with a sentinel: nothing outside [B, Tlen, H, d_x] may be touched
+    pad = 4096
+    buf = torch.full((pad + rhs["X"].numel() + pad,), -7.0, dtype=torch.bfloat16, device=DEV)
+    W = buf[pad:pad + rhs["X"].numel()].view(rhs["X"].shape)
+    tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), g, rhs["X"].to(DEV), C, row_scale=rhs["row_scale"].to(DEV),
+                            W=W, gate_kind=gate_kind)
+    check_solve(W, W_ref, 2e-2, f"C={C} Tlen={Tlen} gate={gate_kind}")
+    assert (buf[:pad] == -7.0).all() and (buf[pad + rhs["X"].numel():] == -7.0).all()
+
+
+def test_solve_agrees_with_the_stored_inverse_applied_in_fp32():
+    # the same inverse, written out by gdn_chunk_tri_inv_ex and applied by torch in fp32: the two paths differ by
+    # the rounding of the scaled inverse and of W only
+    w, inp, rhs = solve_case(1, 128, tri.BF16, Tlen=256, H=4)
+    K, beta, g, X, s = (inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), rhs["X"].to(DEV), rhs["row_scale"].to(DEV))
+    W = tri.gdn_chunk_tri_solve(K, beta, g, X, w.C, row_scale=s).float()
+    T = tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C).view(1, 4, 4, 64, 64)                 # [B, chunk, H, C, C]
+    sX = (s[..., None] * X.float()).view(1, 4, 64, 4, 128)                               # [B, chunk, C, H, d_x]
+    want = torch.einsum("bchij,bcjhx->bcihx", T, sX).reshape(W.shape)
+    rel = ((W - want).norm() / want.norm()).item()
+    assert rel < 6e-3, rel
+
+
+def test_solve_rejects_what_it_does_not_build():
+    w, inp, rhs = solve_case(1, 128, tri.BF16, Tlen=128, H=2)
+    K, beta, g, X = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), rhs["X"].to(DEV)
+    for kwargs in (dict(method=tri.NEUMANN), dict(method=tri.FWD_SUBST), dict(flags=tri.FLAG_REFINE1)):
+        with pytest.raises(tri.TriInvError) as e:
+            tri.gdn_chunk_tri_solve(K, beta, g, X, 64, **kwargs)
+        assert e.value.status == -9
+    with pytest.raises(tri.TriInvError) as e:
+        tri.gdn_chunk_tri_solve(K, beta, g, X, 128)
+    assert e.value.status == -9
+    with pytest.raises(tri.TriInvError) as e:                                           # in place
+        tri.gdn_chunk_tri_solve(K, beta, g, X, 64, W=X)
+    assert e.value.status == -7
+    with pytest.raises(tri.TriInvError) as e:                                           # d_x not a multiple of 8
+        tri.gdn_chunk_tri_solve(K, beta, g, X[..., :60].contiguous(), 64)
+    assert e.value.status == -5
