@@ -307,7 +307,7 @@ def main() -> int:
     if copy_ref is not None:
         out["copy_ref"] = copy_ref
 
-    if args.solve and C <= 64:
+    if args.solve:
         # W = (I + A)^{-1} diag(s) X with X, W [B, Tlen, H, d_x] in the operand type: same rotation over buffer sets
         d_x = args.solve
         xdt = {0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[args.op]

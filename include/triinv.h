@@ -225,9 +225,9 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
  *              call (rows of a short last chunk's padding do not exist and are not written).  Must
  *              not overlap X.  Caller-owned.
  *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
- *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R); C in {16, 32, 64};
- *              d_k = 64 or 128 for the scalar / no-gate kinds, any supported d_k for the per-channel
- *              gate.  Anything else returns TRIINV_ERR_UNSUPPORTED.
+ *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R); d_k = 64 or 128 for the
+ *              scalar / no-gate kinds; the per-channel gate at C <= 64 only, with any supported d_k.
+ *              Anything else returns TRIINV_ERR_UNSUPPORTED.
  *   flags      TRIINV_FLAG_MXR_R only.
  * Accuracy: that of the method's inverse (see tri_inv_ex) plus one rounding of the scaled inverse
  * and of W to op_dtype.

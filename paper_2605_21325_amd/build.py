@@ -36,7 +36,7 @@ UNITS = [
     for nb in (8, 4, 2, 1) for op in (0, 1, 2)
 ] + [
     (f"solve_nb{nb}_op{op}", "solve.hip", [f"-DTRIINV_INST_NB={nb}", f"-DTRIINV_INST_OP={op}"])
-    for nb in (4, 2, 1) for op in (0, 1, 2)
+    for nb in (8, 4, 2, 1) for op in (0, 1, 2)
 ] + [("api", "api.hip", [])]
 
 

@@ -244,7 +244,7 @@ int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g, const 
         (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), W, w_bytes)))
         return TRIINV_ERR_ALIAS;
     if (flags & ~0x70000u) return TRIINV_ERR_UNSUPPORTED;  // TRIINV_FLAG_MXR_R only
-    if (C == 128 || (method != TRIINV_BLOCK_RECURSIVE && method != TRIINV_MIXED)) return TRIINV_ERR_UNSUPPORTED;
+    if (method != TRIINV_BLOCK_RECURSIVE && method != TRIINV_MIXED) return TRIINV_ERR_UNSUPPORTED;
 
     const ChunkMap map{Tlen, (uint32_t)cps, 0u, nullptr, nullptr};
     SolveArgs a{GdnArgs{K, beta, need_g ? g : nullptr, nullptr, n_mat, n_chunk, map, H, d_k, k_dtype, gate_kind, method,
@@ -253,7 +253,7 @@ int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g, const 
     int nb = 1;
 #define TRIINV_PICK_OP(NBV) \
     (op_dtype == TRIINV_F32 ? launch_solve_nb##NBV##_op0(a) : op_dtype == TRIINV_F16 ? launch_solve_nb##NBV##_op1(a) : launch_solve_nb##NBV##_op2(a))
-    nb = C == 16 ? TRIINV_PICK_OP(1) : C == 32 ? TRIINV_PICK_OP(2) : TRIINV_PICK_OP(4);
+    nb = C == 16 ? TRIINV_PICK_OP(1) : C == 32 ? TRIINV_PICK_OP(2) : C == 64 ? TRIINV_PICK_OP(4) : TRIINV_PICK_OP(8);
 #undef TRIINV_PICK_OP
     return finish(nb);
 }

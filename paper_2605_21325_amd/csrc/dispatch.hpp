@@ -73,6 +73,7 @@ TRIINV_DECL(8, 2)
 TRIINV_DECL_SOLVE(1)
 TRIINV_DECL_SOLVE(2)
 TRIINV_DECL_SOLVE(4)
+TRIINV_DECL_SOLVE(8)
 #undef TRIINV_DECL_SOLVE
 int launch_tri_inv_nb1_op0_fwd(const TriInvArgs& a);
 int launch_tri_inv_nb2_op0_fwd(const TriInvArgs& a);

@@ -1,10 +1,10 @@
 // Instantiations of the apply-instead-of-store kernels (solve.hpp) for one (C = 16 * TRIINV_INST_NB,
-// operand type TRIINV_INST_OP) pair: blocked and mixed recursion, C <= 64.
+// operand type TRIINV_INST_OP) pair: blocked and mixed recursion.
 #include "dispatch.hpp"
 #include "solve.hpp"
 
 #ifndef TRIINV_INST_NB
-#error "compile with -DTRIINV_INST_NB=1|2|4 -DTRIINV_INST_OP=0|1|2"
+#error "compile with -DTRIINV_INST_NB=1|2|4|8 -DTRIINV_INST_OP=0|1|2"
 #endif
 
 namespace triinv {
@@ -14,16 +14,15 @@ namespace triinv {
 
 constexpr int NB = TRIINV_INST_NB;
 constexpr int OP = TRIINV_INST_OP;
-constexpr int WPB = 4;  // four adjacent heads per workgroup, as in the storing kernels
+constexpr int WPB = NB <= 4 ? 4 : 1;  // four adjacent heads per workgroup at C <= 64, as in the storing kernels
 
 // Two wavefronts per SIMD for the 16-bit-operand kernels at C = 64 (see the storing kernels: they are bound
 // by the memory system and measured slower with more wavefronts resident).
 constexpr unsigned PAD = (NB == 4 && OP != OP_F32) ? 24576u : 0u;
 
-#ifndef TRIINV_SOLVE_XPOS
-#define TRIINV_SOLVE_XPOS 1
-#endif
-constexpr int XPOS = TRIINV_SOLVE_XPOS;
+// X's first loads: between the Gram products and the recursion at C <= 64 (the keys' registers are free by then);
+// after the recursion at C = 128, whose tiles and keys fill the register file (measured equal at C = 64).
+constexpr int XPOS = NB <= 4 ? 1 : 3;
 
 static RhsArgs rhs_of(const SolveArgs& a) { return RhsArgs{a.X, a.scale, a.W, a.d_x}; }
 
@@ -55,9 +54,11 @@ int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a
     const GdnArgs& f = a.f;
     if (f.refine) return 1;
     if (f.gate == G_CHANNEL) {
+#if TRIINV_INST_NB <= 4
         if (f.method == M_BLOCK) return go_kda<M_BLOCK>(a);
         if (f.method == M_MIXED) return go_kda<M_MIXED>(a);
-        return 1;
+#endif
+        return 1;  // C = 128: the per-channel Gram passes and the right-hand sides do not fit one wavefront's registers
     }
     if (f.k_dt == OP_F32) {
         if (f.d_k == 64) return gdn_method<OP_F32, 4>(a);

@@ -5,12 +5,13 @@
 // X on the matrix cores.  Neither A nor the inverse goes to memory.
 //
 // Column map of X and W.  The matrix-core column index n of a tile is free to stand for any memory
-// column as long as the result is stored under the same map, so lane (q, n) owns the EIGHT CONSECUTIVE
-// memory columns 128 gi + 8n .. 8n + 7 of a 128-column group gi and column tile c of the group takes
-// column 8n + c from every lane.  One 16-byte load per (row, lane) then feeds eight tiles, one 16-byte
-// store per (row, lane) takes one result from each of eight accumulator tiles, every memory instruction
-// moves whole 256-byte row segments (16 lanes x 16 B, four rows per instruction), and neither X nor W
-// passes through LDS.  Lanes whose columns lie beyond d_x compute on a clamped address and store nothing.
+// column as long as the result is stored under the same map, so lane (q, n) owns the VEC CONSECUTIVE
+// memory columns that fill 16 bytes (VEC = 8 for 16-bit elements, 4 for fp32): columns GW gi + VEC n ..
+// + VEC - 1 of column group gi (GW = 16 VEC columns wide), and column tile c of the group takes column
+// VEC n + c from every lane.  One 16-byte load per (row, lane) then feeds VEC tiles, one 16-byte store
+// per (row, lane) takes one result from each of VEC accumulator tiles, every memory instruction moves
+// whole 256-byte row segments (16 lanes x 16 B, four rows per instruction), and neither X nor W passes
+// through LDS.  Lanes whose columns lie beyond d_x compute on a clamped address and store nothing.
 #pragma once
 #include "kernels.hpp"
 
@@ -23,29 +24,26 @@ struct RhsArgs {
     int d_x;
 };
 
-// Eight consecutive columns of one row of X as stored.
-template <int OP> struct XRow8;
-template <> struct XRow8<OP_F32> { v4f a, b; };
-template <> struct XRow8<OP_F16> { v4u u; };
-template <> struct XRow8<OP_BF16> { v4u u; };
+// Sixteen bytes of one row of X as stored: VEC consecutive columns.
+template <int OP> struct XRow;
+template <> struct XRow<OP_F32> { v4f f; };
+template <> struct XRow<OP_F16> { v4u u; };
+template <> struct XRow<OP_BF16> { v4u u; };
 
-template <int OP> __device__ __forceinline__ XRow8<OP> load_x8(const char* p)
+template <int OP> __device__ __forceinline__ XRow<OP> load_x(const char* p)
 {
     if constexpr (OP == OP_F32) {
-        return {*reinterpret_cast<const v4f*>(p), *reinterpret_cast<const v4f*>(p + 16)};
+        return {*reinterpret_cast<const v4f*>(p)};
     } else {
         return {*reinterpret_cast<const v4u*>(p)};
     }
 }
 
-// Column tile c of a 16-row tile row of X as a matrix-core operand: rows 4q + r (r = 0..3) of this lane's column 8n + c.
-template <int OP> __device__ __forceinline__ Opnd<OP> x_operand(const XRow8<OP> (&row)[4], int c)
+// Column tile c of a 16-row tile row of X as a matrix-core operand: rows 4q + r (r = 0..3) of this lane's column VEC n + c.
+template <int OP> __device__ __forceinline__ Opnd<OP> x_operand(const XRow<OP> (&row)[4], int c)
 {
     if constexpr (OP == OP_F32) {
-        v4f v;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = c < 4 ? row[r].a[c & 3] : row[r].b[c & 3];
-        return {v};
+        return {v4f{row[0].f[c], row[1].f[c], row[2].f[c], row[3].f[c]}};
     } else {
         const int d = c >> 1;
         uint32_t lo, hi;
@@ -65,13 +63,15 @@ template <int OP> __device__ __forceinline__ Opnd<OP> x_operand(const XRow8<OP> 
 // The right-hand sides of one chunk and head.
 template <int OP, int NB> struct RhsX {
     static constexpr int ESZ = OP == OP_F32 ? 4 : 2;
+    static constexpr int VEC = 16 / ESZ;  // columns per lane
+    static constexpr int GW = 16 * VEC;   // columns per group
     const char* xc;      // element (chunk row 0, this head, column 0) of X
     char* wc;            // the same element of W
     int64_t row_bytes;   // H * d_x * ESZ
     int d_x, valid;
     Lane ln;
     v4f s_q[NB];         // s of rows 16 j + 4 q + r
-    XRow8<OP> raw[NB][4];
+    XRow<OP> raw[NB][4];
 
     // first token of the chunk tok0, head h; starts the loads of s
     __device__ __forceinline__ void init(const RhsArgs& a, int64_t tok0, int h, int H, int valid_, Lane ln_)
@@ -93,27 +93,30 @@ template <int OP, int NB> struct RhsX {
             }
     }
 
-    __device__ __forceinline__ bool active(int gi) const { return 128 * gi + 8 * ln.n < d_x; }
+    __device__ __forceinline__ bool active(int gi) const { return GW * gi + VEC * ln.n < d_x; }
+    __device__ __forceinline__ int n_group() const { return (d_x + GW - 1) / GW; }
 
     // loads of column group gi: rows beyond the chunk's last token read that token (they only meet zero columns of the inverse)
-    __device__ __forceinline__ void issue(int gi)
+    // (tile rows j0 .. j1 - 1 only: the caller may split the loads around other work)
+    __device__ __forceinline__ void issue(int gi, int j0 = 0, int j1 = NB)
     {
-        const int col = active(gi) ? 128 * gi + 8 * ln.n : 0;
+        const int col = active(gi) ? GW * gi + VEC * ln.n : 0;
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
+                if (j < j0 || j >= j1) continue;
                 const int row = 16 * j + 4 * ln.q + r;
                 const int rc = row < valid ? row : valid - 1;
-                raw[j][r] = load_x8<OP>(xc + rc * row_bytes + col * ESZ);
+                raw[j][r] = load_x<OP>(xc + rc * row_bytes + col * ESZ);
             }
     }
 
-    // rows 16 i + 4 q + r of the result, eight columns per lane: acc[c][r]
-    __device__ __forceinline__ void store(int gi, int i, const v4f (&acc)[8])
+    // rows 16 i + 4 q + r of the result, VEC columns per lane: acc[c][r]
+    __device__ __forceinline__ void store(int gi, int i, const v4f (&acc)[VEC])
     {
         if (!active(gi)) return;
-        const int col = 128 * gi + 8 * ln.n;
+        const int col = GW * gi + VEC * ln.n;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = 16 * i + 4 * ln.q + r;
@@ -121,7 +124,6 @@ template <int OP, int NB> struct RhsX {
             char* p = wc + row * row_bytes + col * ESZ;
             if constexpr (OP == OP_F32) {
                 __builtin_nontemporal_store(v4f{acc[0][r], acc[1][r], acc[2][r], acc[3][r]}, reinterpret_cast<v4f*>(p));
-                __builtin_nontemporal_store(v4f{acc[4][r], acc[5][r], acc[6][r], acc[7][r]}, reinterpret_cast<v4f*>(p + 16));
             } else if constexpr (OP == OP_F16) {
                 __builtin_nontemporal_store(v4u{pack2_f16(acc[0][r], acc[1][r]), pack2_f16(acc[2][r], acc[3][r]),
                                                 pack2_f16(acc[4][r], acc[5][r]), pack2_f16(acc[6][r], acc[7][r])},
@@ -136,9 +138,9 @@ template <int OP, int NB> struct RhsX {
 };
 
 // Recursion (blocked, or mixed with aux refinement steps on the leaves), then W = T diag(s) X.
-// ISSUE_X: start the loads of X's first column group here, after the recursion (otherwise the caller has
-// called x.issue(0)).  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
-template <int OP, int NB, int METHOD, bool ISSUE_X, class ASrc>
+// ISSUE_FROM: the loads of tile rows ISSUE_FROM .. NB - 1 of X's first column group start here, after the
+// recursion (the caller has issued the rows before).  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
+template <int OP, int NB, int METHOD, int ISSUE_FROM, class ASrc>
 __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& x, float* lds, Lane ln, int aux)
 {
     static_assert(METHOD == M_BLOCK || METHOD == M_MIXED, "built for the blocked and the mixed recursion");
@@ -148,7 +150,7 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
         v4f Tt[NT];
         constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE;
         block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln, aux);
-        if constexpr (ISSUE_X) x.issue(0);
+        if constexpr (ISSUE_FROM < NB) x.issue(0, ISSUE_FROM, NB);
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -166,22 +168,23 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
                 Top[tix(i, j)] = pack<OP>(t);
             }
     }
-    const int n_group = (x.d_x + 127) / 128;
+    constexpr int VEC = RhsX<OP, NB>::VEC;
+    const int n_group = x.n_group();
     for (int gi = 0;;) {
-        Opnd<OP> xo[NB][8];
+        Opnd<OP> xo[NB][VEC];
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int c = 0; c < 8; ++c) xo[j][c] = x_operand<OP>(x.raw[j], c);
+            for (int c = 0; c < VEC; ++c) xo[j][c] = x_operand<OP>(x.raw[j], c);
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            v4f acc[8];
+            v4f acc[VEC];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) acc[c] = zero4();
+            for (int c = 0; c < VEC; ++c) acc[c] = zero4();
 #pragma unroll
             for (int j = 0; j <= i; ++j)
 #pragma unroll
-                for (int c = 0; c < 8; ++c) acc[c] = tn<OP>(Top[tix(i, j)], xo[j][c], acc[c]);
+                for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(Top[tix(i, j)], xo[j][c], acc[c]);
             x.store(gi, i, acc);
         }
         if (++gi >= n_group) break;
@@ -189,7 +192,8 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
     }
 }
 
-// XPOS: where X's first loads are issued -- 1: between the Gram products and the recursion, 2: after the recursion.
+// XPOS: where X's first loads are issued -- 1: between the Gram products and the recursion, 2: after the recursion,
+// 3: half before the recursion (with the keys still in registers), half after it.
 template <int KD, int OP, int NB, int METHOD, int DKS, int WPB, int XPOS>
 __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
                                                             const float* __restrict__ g, RhsArgs rhs, int64_t n_chunk, ChunkMap map,
@@ -227,9 +231,16 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
                 if (need_tile<NB, METHOD>(i, j, true)) pre.t[tix(i, j)] = src.template get<true>(i, j);
             }
         x.issue(0);
-        invert_and_apply<OP, NB, METHOD, false>(pre, x, lds, ln, aux);
+        invert_and_apply<OP, NB, METHOD, NB>(pre, x, lds, ln, aux);
+    } else if constexpr (XPOS == 2) {
+        invert_and_apply<OP, NB, METHOD, 0>(src, x, lds, ln, aux);
     } else {
-        invert_and_apply<OP, NB, METHOD, true>(src, x, lds, ln, aux);
+        // the first tile rows of X before the recursion (as many as the registers beside the keys allow), the rest
+        // after it: the first strips are multiplied and stored while the later rows' loads are still in flight
+        constexpr int KEY_REGS = NB * DKS * 4;
+        constexpr int EARLY = KEY_REGS <= 64 ? NB / 2 : KEY_REGS <= 128 ? NB / 4 : 0;
+        x.issue(0, 0, EARLY);
+        invert_and_apply<OP, NB, METHOD, EARLY>(src, x, lds, ln, aux);
     }
 }
 
@@ -258,7 +269,7 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_solve(const void* __restri
     RhsX<OP, NB> x;  // after the Gram passes, which need the registers
     x.init(rhs, tok0, h, H, pos.valid, ln);
     x.issue(0);
-    invert_and_apply<OP, NB, METHOD, false>(src, x, lds, ln, aux);
+    invert_and_apply<OP, NB, METHOD, NB>(src, x, lds, ln, aux);
 }
 
 }  // namespace triinv

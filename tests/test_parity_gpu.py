@@ -891,6 +891,21 @@ def test_solve_matches_oracle(idx, kw, method, op):
     check_solve(W, W_ref, SOLVE_TOL[op], f"cfg{idx} {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}")
 
 
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("method", [tri.BLOCK_RECURSIVE, tri.MIXED], ids=lambda m: tri.METHOD_NAMES[m])
+@pytest.mark.parametrize("Tlen", [512, 300])
+def test_solve_c128_stress_recipe(Tlen, method, op):
+    # the C = 128 stress recipe (large growth in the inverse), full and short last chunk, scalar-gated variant included
+    for idx, kw in ((4, dict(Tlen=Tlen, H=3)), (1, dict(Tlen=Tlen, H=3, C=128))):
+        w, inp, rhs = solve_case(idx, 128, op, **kw)
+        W_ref = oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], rhs["row_scale"], w.gate_kind, w.C)
+        g = None if inp["g"] is None else inp["g"].to(DEV)
+        W = torch.full(rhs["X"].shape, float("nan"), dtype=XDT[op], device=DEV)
+        tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), g, rhs["X"].to(DEV), w.C, row_scale=rhs["row_scale"].to(DEV),
+                                W=W, gate_kind=w.gate_kind, method=method)
+        check_solve(W, W_ref, SOLVE_TOL[op], f"C=128 cfg{idx} Tlen={Tlen} {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}")
+
+
 @pytest.mark.parametrize("d_x", [8, 64, 72, 128, 200, 256, 512])
 @pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
 def test_solve_column_counts(d_x, op):
@@ -940,8 +955,10 @@ def test_solve_rejects_what_it_does_not_build():
         with pytest.raises(tri.TriInvError) as e:
             tri.gdn_chunk_tri_solve(K, beta, g, X, 64, **kwargs)
         assert e.value.status == -9
-    with pytest.raises(tri.TriInvError) as e:
-        tri.gdn_chunk_tri_solve(K, beta, g, X, 128)
+    w3, inp3, rhs3 = solve_case(3, 128, tri.BF16, B=1, Tlen=128, H=2)
+    with pytest.raises(tri.TriInvError) as e:                                           # per-channel gate at C = 128
+        tri.gdn_chunk_tri_solve(inp3["K"].to(DEV), inp3["beta"].to(DEV), inp3["g"].to(DEV), rhs3["X"].to(DEV), 128,
+                                gate_kind=tri.GATE_PER_CHANNEL)
     assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:                                           # in place
         tri.gdn_chunk_tri_solve(K, beta, g, X, 64, W=X)
