@@ -238,6 +238,20 @@ int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g,
                         int k_dtype, int gate_kind, int method, int op_dtype,
                         void* hip_stream, uint32_t flags);
 
+/*
+ * gdn_chunk_tri_solve_varlen: gdn_chunk_tri_solve on sequences of different lengths packed back to back
+ * (paper Sec. 1 chunking applied to each sequence on its own).  K, beta, g as in
+ * gdn_chunk_tri_inv_varlen; X, W device, [total_tokens][H][d_x]; row_scale device fp32 [total_tokens][H]
+ * or NULL; cu_seqlens, cu_chunks, n_seq, total_tokens, total_chunks as in gdn_chunk_tri_inv_varlen
+ * (trusted in the same way; must not overlap W).  Everything else as in gdn_chunk_tri_solve.
+ */
+int gdn_chunk_tri_solve_varlen(const void* K, const float* beta, const float* g,
+                               const void* X, const float* row_scale, void* W,
+                               const int64_t* cu_seqlens, const int64_t* cu_chunks, int n_seq,
+                               int64_t total_tokens, int64_t total_chunks, int H, int d_k, int d_x, int C,
+                               int k_dtype, int gate_kind, int method, int op_dtype,
+                               void* hip_stream, uint32_t flags);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* triinv_status_string(int status);
 

@@ -213,3 +213,23 @@ def gdn_chunk_tri_solve(K, beta, g, X, row_scale, gate_kind: int, C: int, n_thre
                 acc -= A[:, c, :, i, j][..., None] * W[:, t0 + j]
             W[:, t0 + i] = acc
     return W
+
+
+def gdn_chunk_tri_solve_varlen(K, beta, g, X, row_scale, seqlens, gate_kind: int, C: int, n_threads: int = 0) -> np.ndarray:
+    """gdn_chunk_tri_solve on packed sequences (K [total, H, d_k], X [total, H, d_x], ...): every sequence is chunked on
+    its own.  Returns W [total, H, d_x]."""
+    import torch
+
+    X = torch.as_tensor(X)
+    W = np.zeros(tuple(X.shape), dtype=np.float64)
+    t0 = 0
+    for n in seqlens:
+        n = int(n)
+        if n > 0:
+            sl = slice(t0, t0 + n)
+            W[sl] = gdn_chunk_tri_solve(torch.as_tensor(K)[sl][None], torch.as_tensor(beta)[sl][None],
+                                        None if g is None else torch.as_tensor(g)[sl][None], X[sl][None],
+                                        None if row_scale is None else torch.as_tensor(row_scale)[sl][None], gate_kind, C,
+                                        n_threads=n_threads)[0]
+        t0 += n
+    return W

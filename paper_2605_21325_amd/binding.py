@@ -42,7 +42,7 @@ METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUM
 DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
 
 EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "gdn_chunk_tri_inv_varlen", "gdn_chunk_build_A",
-           "gdn_chunk_tri_solve", "triinv_status_string", "triinv_version")
+           "gdn_chunk_tri_solve", "gdn_chunk_tri_solve_varlen", "triinv_status_string", "triinv_version")
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.gdn_chunk_build_A.restype = i32
         L.gdn_chunk_tri_solve.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, i32, i32, vp, u32]
         L.gdn_chunk_tri_solve.restype = i32
+        L.gdn_chunk_tri_solve_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i32, i32, i32, i32, vp, u32]
+        L.gdn_chunk_tri_solve_varlen.restype = i32
         L.triinv_status_string.argtypes = [i32]
         L.triinv_status_string.restype = ctypes.c_char_p
         L.triinv_version.argtypes = []
@@ -255,4 +257,33 @@ def gdn_chunk_tri_solve(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.T
                                    method, dtype_code(X.dtype), _stream_ptr(stream), flags)
     if st != OK:
         raise TriInvError(st, "gdn_chunk_tri_solve")
+    return W
+
+
+def gdn_chunk_tri_solve_varlen(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], X: torch.Tensor, seqlens, C: int,
+                               row_scale: Optional[torch.Tensor] = None, W: Optional[torch.Tensor] = None,
+                               gate_kind: int = GATE_SCALAR, method: int = BLOCK_RECURSIVE, stream=None, flags: int = 0) -> torch.Tensor:
+    """gdn_chunk_tri_solve on packed sequences: K [total, H, d_k], X and W [total, H, d_x]; seqlens = host sequence of lengths."""
+    total, H, d_k = K.shape
+    d_x = X.shape[-1]
+    if tuple(X.shape[:2]) != (total, H):
+        raise ValueError("X must be [total_tokens, H, d_x]")
+    cu_s, cu_c = varlen_chunk_offsets(seqlens, C)
+    if cu_s[-1] != total:
+        raise ValueError(f"sequence lengths sum to {cu_s[-1]}, K holds {total} tokens")
+    cu_seqlens = torch.tensor(cu_s, dtype=torch.int64, device=K.device)
+    cu_chunks = torch.tensor(cu_c, dtype=torch.int64, device=K.device)
+    if W is None:
+        W = torch.empty_like(X)
+    elif W.shape != X.shape or W.dtype != X.dtype:
+        raise ValueError("W must have the shape and element type of X")
+    gp = None if g is None else _dev(g, "g")
+    sp = None if row_scale is None else _dev(row_scale, "row_scale")
+    st = lib().gdn_chunk_tri_solve_varlen(_dev(K, "K"), _dev(beta, "beta"), gp, _dev(X, "X") if X.numel() else None, sp,
+                                          _dev(W, "W") if W.numel() else None, cu_seqlens.data_ptr(), cu_chunks.data_ptr(),
+                                          len(cu_s) - 1, total, cu_c[-1], H, d_k, d_x, C, dtype_code(K.dtype), gate_kind, method,
+                                          dtype_code(X.dtype), _stream_ptr(stream), flags)
+    if st != OK:
+        raise TriInvError(st, "gdn_chunk_tri_solve_varlen")
+    W._triinv_keepalive = (cu_seqlens, cu_chunks)  # the launch is asynchronous: the offsets live as long as the result
     return W

@@ -512,3 +512,24 @@ def test_chunk_solve_closed_form_differences():
     want[:, 1:] -= X[:, :-1]
     want[:, ::C] = X[:, ::C]
     assert np.allclose(W, want, atol=1e-13)
+
+
+def test_chunk_solve_packed_sequences_are_solved_one_by_one():
+    # packed [total, H, ...] tensors: each sequence's result equals the fixed-layout result of that sequence alone,
+    # and a chunk never reaches across a sequence boundary (first differences restart at every sequence and chunk)
+    H, d_k, d_x, C = 2, 8, 3, 16
+    seqlens = [20, 0, 5, 33]
+    total = sum(seqlens)
+    K = np.zeros((total, H, d_k), dtype=np.float32)
+    K[..., 0] = 1.0
+    beta = np.ones((total, H), dtype=np.float32)
+    X = np.random.default_rng(3).normal(size=(total, H, d_x)).astype(np.float32)
+    W = oracle.gdn_chunk_tri_solve_varlen(K, beta, None, X, None, seqlens, 2, C)
+    want = X.astype(np.float64).copy()
+    want[1:] -= X[:-1]
+    t0 = 0
+    for n in seqlens:
+        for c0 in range(0, n, C):
+            want[t0 + c0] = X[t0 + c0]
+        t0 += n
+    assert np.allclose(W, want, atol=1e-13)

@@ -966,3 +966,41 @@ def test_solve_rejects_what_it_does_not_build():
     with pytest.raises(tri.TriInvError) as e:                                           # d_x not a multiple of 8
         tri.gdn_chunk_tri_solve(K, beta, g, X[..., :60].contiguous(), 64)
     assert e.value.status == -5
+
+
+@pytest.mark.parametrize("gate_kind", [0, 1, 2])
+@pytest.mark.parametrize("C", [32, 64, 128])
+def test_solve_packed_variable_length_sequences(C, gate_kind):
+    if C == 128 and gate_kind == 1:
+        pytest.skip("the per-channel gate of the applied-inverse kernels is built at C <= 64")
+    H, d_k, d_x = 3, 128, 72
+    seqlens = [C, 1, 0, 2 * C + 5, C - 1, 3 * C, 0, 17]
+    total = sum(seqlens)
+    idx = {0: 1, 1: 3, 2: 4}[gate_kind]
+    w = si.workload(idx, B=1, Tlen=total, H=H, C=C, d_k=d_k, k_dtype="bf16")
+    inp = si.make_inputs(w)
+    rhs = si.make_rhs(w, d_x, torch.bfloat16)
+    K, beta, X, s = inp["K"][0].contiguous(), inp["beta"][0].contiguous(), rhs["X"][0].contiguous(), rhs["row_scale"][0].contiguous()
+    g = None
+    if gate_kind != 2:
+        gen = torch.Generator().manual_seed(11)
+        shape = (total, H) if gate_kind == 0 else (total, H, d_k)
+        rate = -0.05 * torch.nn.functional.softplus(torch.randn(*shape, generator=gen))
+        g, t0 = torch.zeros(shape), 0
+        for n in seqlens:
+            for c0 in range(0, n, C):
+                m = min(C, n - c0)
+                g[t0 + c0:t0 + c0 + m] = torch.cumsum(rate[t0 + c0:t0 + c0 + m], 0)
+            t0 += n
+    W_ref = oracle.gdn_chunk_tri_solve_varlen(K, beta, g, X, s, seqlens, gate_kind, C)
+    W = torch.full(X.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+    tri.gdn_chunk_tri_solve_varlen(K.to(DEV), beta.to(DEV), None if g is None else g.to(DEV), X.to(DEV), seqlens, C,
+                                   row_scale=s.to(DEV), W=W, gate_kind=gate_kind)
+    check_solve(W[None], W_ref[None], 2e-2, f"solve varlen C={C} gate={gate_kind}")
+
+
+def test_solve_packed_sequences_with_no_tokens_are_a_no_op():
+    K = torch.zeros((0, 2, 128), dtype=torch.bfloat16, device=DEV)
+    X = torch.zeros((0, 2, 64), dtype=torch.bfloat16, device=DEV)
+    W = tri.gdn_chunk_tri_solve_varlen(K, torch.zeros((0, 2), device=DEV), None, X, [0, 0], 64, gate_kind=tri.GATE_NONE)
+    assert W.shape == X.shape
