@@ -154,7 +154,30 @@ def main() -> int:
                     except tri.TriInvError as e:
                         row["standalone"] = {"error": str(e)}
                     rows.append(row)
-        print(json.dumps({"accuracy": rows, "sampled_matrices": len(sel),
+        # the inverse applied to right-hand sides: W = (I + A)^{-1} diag(s) X, first batch entry, against the oracle's solve
+        solve_rows = []
+        d_x = 128
+        for op in (0, 1, 2):
+            xdt = {0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[op]
+            rhs = si.make_rhs(w, d_x, xdt)
+            X1, s1 = rhs["X"][:1].contiguous(), rhs["row_scale"][:1].contiguous()
+            W_ref = oracle.gdn_chunk_tri_solve(inp["K"][:1], inp["beta"][:1], None if inp["g"] is None else inp["g"][:1], X1, s1,
+                                               w.gate_kind, C)
+            den = np.sqrt((W_ref ** 2).sum(axis=(1, 3)))
+            for method in (1, 3):
+                row = {"method": tri.METHOD_NAMES[method], "op": tri.DTYPE_NAMES[op]}
+                try:
+                    Wg = tri.gdn_chunk_tri_solve(K[:1].contiguous(), beta[:1].contiguous(), None if g is None else g[:1].contiguous(),
+                                                 X1.to(dev), C, row_scale=s1.to(dev), gate_kind=w.gate_kind, method=method)
+                    torch.cuda.synchronize()
+                    Wg = Wg.float().cpu().numpy().astype(np.float64)
+                    rel = np.sqrt(((Wg - W_ref) ** 2).sum(axis=(1, 3))) / den          # per head
+                    row.update({"rel_fro_max": float(rel.max()), "rel_fro_median": float(np.median(rel)),
+                                "max_abs": float(np.abs(Wg - W_ref).max()), "non_finite": int((~np.isfinite(Wg)).sum())})
+                except tri.TriInvError as e:
+                    row["error"] = str(e)
+                solve_rows.append(row)
+        print(json.dumps({"accuracy": rows, "solve_accuracy": solve_rows, "solve_d_x": d_x, "sampled_matrices": len(sel),
                           "workload": f"configs[{w.index}] {w.name}: B={w.B} T={w.Tlen} H={w.H} d_k={w.d_k} C={w.C} -> {n_mat} matrices",
                           "tolerances": {"f32": 1e-5, "f16": 2e-2, "bf16": 2e-2},
                           "note": "fused: against the oracle on the stored keys; standalone: A built by the oracle in fp64, "

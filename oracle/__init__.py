@@ -203,16 +203,17 @@ def gdn_chunk_tri_solve(K, beta, g, X, row_scale, gate_kind: int, C: int, n_thre
         Xf = Xf * torch.as_tensor(row_scale).cpu().to(torch.float64).numpy()[..., None]
     n_chunk = -(-Tlen // C)
     A = A.reshape(B, n_chunk, H, C, C)
-    W = np.zeros((B, Tlen, H, d_x), dtype=np.float64)
-    for c in range(n_chunk):
-        t0 = c * C
-        rows = min(C, Tlen - t0)
-        for i in range(rows):
-            acc = Xf[:, t0 + i].copy()                                          # [B, H, d_x]
-            for j in range(i):
-                acc -= A[:, c, :, i, j][..., None] * W[:, t0 + j]
-            W[:, t0 + i] = acc
-    return W
+    # all chunks side by side: rows beyond Tlen are padding (zero right-hand side, identity rows of I + A), cut off below
+    R = np.zeros((B, n_chunk * C, H, d_x), dtype=np.float64)
+    R[:, :Tlen] = Xf
+    R = R.reshape(B, n_chunk, C, H, d_x)
+    W = np.zeros_like(R)
+    for i in range(C):
+        acc = R[:, :, i].copy()                                                 # [B, n_chunk, H, d_x]
+        for j in range(i):
+            acc -= A[:, :, :, i, j][..., None] * W[:, :, j]
+        W[:, :, i] = acc
+    return W.reshape(B, n_chunk * C, H, d_x)[:, :Tlen].copy()
 
 
 def gdn_chunk_tri_solve_varlen(K, beta, g, X, row_scale, seqlens, gate_kind: int, C: int, n_threads: int = 0) -> np.ndarray:

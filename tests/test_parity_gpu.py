@@ -730,32 +730,43 @@ def test_entry_points_replay_from_a_captured_graph():
     n_mat = A.shape[0]
     T1 = torch.empty((n_mat, C, C), device=DEV)
     T2 = torch.empty((n_mat, C, C), device=DEV)
+    rhs = [si.make_rhs(i["workload"], 64, torch.bfloat16, seed_offset=k) for k, i in enumerate(inps)]
+    X, sc = rhs[0]["X"].to(DEV).clone(), rhs[0]["row_scale"].to(DEV).clone()
+    W = torch.empty_like(X)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):      # warm-up on the side stream, as graph capture asks for
         tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=T1)
         tri.tri_inv_ex(A, T=T2, method=tri.BLOCK_DIRECT, op_dtype=tri.F32)
+        tri.gdn_chunk_tri_solve(K, beta, g, X, C, row_scale=sc, W=W)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=T1)
         tri.tri_inv_ex(A, T=T2, method=tri.BLOCK_DIRECT, op_dtype=tri.F32)
+        tri.gdn_chunk_tri_solve(K, beta, g, X, C, row_scale=sc, W=W)
     for rep in range(6):
         src = inps[rep % 3]
         K.copy_(src["K"].to(DEV))
         beta.copy_(src["beta"].to(DEV))
         g.copy_(src["g"].to(DEV))
         A.copy_(A_in[rep % 3].to(DEV))
+        X.copy_(rhs[rep % 3]["X"].to(DEV))
+        sc.copy_(rhs[rep % 3]["row_scale"].to(DEV))
         T1.fill_(7.0)
         T2.fill_(7.0)
+        W.fill_(7.0)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         E1 = tri.gdn_chunk_tri_inv_ex(K, beta, g, C)
         E2 = tri.tri_inv_ex(A, method=tri.BLOCK_DIRECT, op_dtype=tri.F32)
+        E3 = tri.gdn_chunk_tri_solve(K, beta, g, X, C, row_scale=sc)
         torch.cuda.synchronize()
-        assert torch.equal(T1, E1) and torch.equal(T2, E2), f"replay {rep} differs from the eager launch"
+        assert torch.equal(T1, E1) and torch.equal(T2, E2) and torch.equal(W, E3), f"replay {rep} differs from the eager launch"
+        check_solve(W, oracle.gdn_chunk_tri_solve(src["K"], src["beta"], src["g"], rhs[rep % 3]["X"], rhs[rep % 3]["row_scale"], 0, C),
+                    2e-2, f"graph replay {rep} (solve)")
         check(T1, oracle.gdn_chunk_tri_inv_ragged(src["K"], src["beta"], src["g"], 0, C), 2e-2, f"graph replay {rep}")
 
 
