@@ -61,6 +61,8 @@ def main() -> int:
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--vendor-ref", action="store_true",
+                    help="also time torch.linalg.solve_triangular (the ROCm libraries' batched triangular solve) on the same matrices")
     ap.add_argument("--solve", type=int, default=0, metavar="D_X",
                     help="also time gdn_chunk_tri_solve (the inverse applied to D_X right-hand-side columns instead of stored)")
     ap.add_argument("--accuracy", action="store_true",
@@ -329,6 +331,30 @@ def main() -> int:
     }
     if copy_ref is not None:
         out["copy_ref"] = copy_ref
+
+    if args.vendor_ref:
+        # context only: the vendor libraries' batched triangular solve against the identity, fp32, on the same chunk
+        # matrices (written out once by gdn_chunk_build_A), through torch.linalg.solve_triangular
+        K, beta, g, _ = sets[0]
+        A32 = tri.gdn_chunk_build_A(K, beta, g, C, gate_kind=w.gate_kind, op_dtype=tri.F32)
+        M = A32 + torch.eye(C, device=dev)
+        eye = torch.eye(C, device=dev).expand(n_mat, C, C).contiguous()
+        for _ in range(2):
+            Tv = torch.linalg.solve_triangular(M, eye, upper=False, unitriangular=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            Tv = torch.linalg.solve_triangular(M, eye, upper=False, unitriangular=True)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        Tours = tri.tri_inv_ex(A32, method=tri.FWD_SUBST)
+        torch.cuda.synchronize()
+        out["vendor_ref"] = {"call": "torch.linalg.solve_triangular(I + A, I, upper=False, unitriangular=True), fp32",
+                             "ms": ms, "matrices_per_s": n_mat / (ms * 1e-3),
+                             "max_abs_diff_to_tri_inv_fwd_subst": float((Tv - Tours).abs().max())}
+        del A32, M, eye, Tv, Tours
 
     if args.solve:
         # W = (I + A)^{-1} diag(s) X with X, W [B, Tlen, H, d_x] in the operand type: same rotation over buffer sets

@@ -1015,3 +1015,15 @@ def test_solve_packed_sequences_with_no_tokens_are_a_no_op():
     X = torch.zeros((0, 2, 64), dtype=torch.bfloat16, device=DEV)
     W = tri.gdn_chunk_tri_solve_varlen(K, torch.zeros((0, 2), device=DEV), None, X, [0, 0], 64, gate_kind=tri.GATE_NONE)
     assert W.shape == X.shape
+
+
+def test_forward_substitution_against_the_vendor_triangular_solve(cases):
+    # an independent GPU-side check: the ROCm libraries' batched triangular solve of (I + A) T = I in fp32
+    A32 = torch.from_numpy(cases[1]["A"].astype(np.float32)).to(DEV)
+    C = A32.shape[-1]
+    eye = torch.eye(C, device=DEV).expand(A32.shape[0], C, C).contiguous()
+    Tv = torch.linalg.solve_triangular(torch.tril(A32, -1) + torch.eye(C, device=DEV), eye, upper=False, unitriangular=True)
+    T = tri.tri_inv_ex(A32, method=tri.FWD_SUBST)
+    torch.cuda.synchronize()
+    rel = ((T - Tv).flatten(1).norm(dim=1) / Tv.flatten(1).norm(dim=1)).max().item()
+    assert rel < 1e-6, rel
