@@ -198,8 +198,15 @@ template <class ASrc> struct PairView {
     template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const { return a.template get<TR>(P + i, P + j); }
 };
 
-template <int OP, int NB, bool ROOT_T, int LEAF, class ASrc>
-__device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln, int leaf_r = 0)
+struct NoHook {
+    __device__ __forceinline__ void operator()() const {}
+};
+
+// after_last_fetch: called in the last merge once its tiles of A have been fetched, i.e. when A is no longer needed
+// (a source that builds its tiles from keys held in registers has those registers free from here on).
+template <int OP, int NB, bool ROOT_T, int LEAF, class ASrc, class Hook = NoHook>
+__device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln, int leaf_r = 0,
+                                                Hook after_last_fetch = Hook())
 {
     v4f leafN[NB], leafT[NB];
     if constexpr (LEAF == LEAF_FORWARD) {
@@ -258,6 +265,7 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
                 for (int d = 0; d < h; ++d)
                     a21[b * h + d] = blockT ? pack<OP>(A.template get<false>(mid + b, lo + d))
                                             : pack<OP>(A.template get<true>(mid + b, lo + d));
+            if (2 * h == NB) after_last_fetch();
             if (!blockT) {
                 // W = -T22 (A21 T11), N orientation
 #pragma unroll

@@ -138,9 +138,12 @@ template <int OP, int NB> struct RhsX {
 };
 
 // Recursion (blocked, or mixed with aux refinement steps on the leaves), then W = T diag(s) X.
-// ISSUE_FROM: the loads of tile rows ISSUE_FROM .. NB - 1 of X's first column group start here, after the
-// recursion (the caller has issued the rows before).  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
-template <int OP, int NB, int METHOD, int ISSUE_FROM, class ASrc>
+// ISSUE_FROM: the loads of tile rows ISSUE_FROM .. NB - 1 of X's first column group start here (the caller has
+// issued the rows before).  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
+// IN_MERGE: ... inside the recursion's last merge (as soon as its tiles of A exist: a source that holds keys in
+// registers has them free from there on, and the merge's products run while the loads are in flight); otherwise
+// after the recursion.
+template <int OP, int NB, int METHOD, int ISSUE_FROM, bool IN_MERGE = false, class ASrc>
 __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& x, float* lds, Lane ln, int aux)
 {
     static_assert(METHOD == M_BLOCK || METHOD == M_MIXED, "built for the blocked and the mixed recursion");
@@ -149,8 +152,10 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
     {
         v4f Tt[NT];
         constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE;
-        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln, aux);
-        if constexpr (ISSUE_FROM < NB) x.issue(0, ISSUE_FROM, NB);
+        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln, aux, [&]() {
+            if constexpr (ISSUE_FROM < NB && IN_MERGE) x.issue(0, ISSUE_FROM, NB);
+        });
+        if constexpr (ISSUE_FROM < NB && !IN_MERGE) x.issue(0, ISSUE_FROM, NB);
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -239,8 +244,9 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
         // after it: the first strips are multiplied and stored while the later rows' loads are still in flight
         constexpr int KEY_REGS = NB * DKS * 4;
         constexpr int EARLY = KEY_REGS <= 64 ? NB / 2 : KEY_REGS <= 128 ? NB / 4 : 0;
+        constexpr bool IN_MERGE = KEY_REGS <= 128 && KD != OP_F32 && OP != OP_F32;  // elsewhere the registers do not allow it
         x.issue(0, 0, EARLY);
-        invert_and_apply<OP, NB, METHOD, EARLY>(src, x, lds, ln, aux);
+        invert_and_apply<OP, NB, METHOD, EARLY, IN_MERGE>(src, x, lds, ln, aux);
     }
 }
 
