@@ -1027,3 +1027,41 @@ def test_forward_substitution_against_the_vendor_triangular_solve(cases):
     torch.cuda.synchronize()
     rel = ((T - Tv).flatten(1).norm(dim=1) / Tv.flatten(1).norm(dim=1)).max().item()
     assert rel < 1e-6, rel
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_solve_full_size_workload(idx):
+    """gdn_chunk_tri_solve in the launch configuration the benchmark times (full-size workload, d_x = 128, bf16):
+    the oracle recomputes sampled chunks, and the residual of (I + A) W = diag(s) X is checked for EVERY chunk (A
+    written by gdn_chunk_build_A, products in fp64 on the device)."""
+    w = si.WORKLOADS[idx]
+    C, d_x = w.C, 128
+    inp = si.make_inputs(w)
+    rhs = si.make_rhs(w, d_x, torch.bfloat16)
+    K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    X, s = rhs["X"].to(DEV), rhs["row_scale"].to(DEV)
+    W = tri.gdn_chunk_tri_solve(K, beta, g, X, C, row_scale=s, gate_kind=w.gate_kind)
+    torch.cuda.synchronize()
+    # (a) sampled chunks against the oracle: chunks are independent, so a slice of whole chunks is a workload of its own
+    n_chunk = w.Tlen // C
+    rng = np.random.default_rng(idx)
+    for b, c in {(0, 0), (w.B - 1, n_chunk - 1)} | {(int(rng.integers(w.B)), int(rng.integers(n_chunk))) for _ in range(6)}:
+        sl = (slice(b, b + 1), slice(c * C, (c + 1) * C))
+        W_ref = oracle.gdn_chunk_tri_solve(inp["K"][sl], inp["beta"][sl], None if inp["g"] is None else inp["g"][sl],
+                                           rhs["X"][sl], rhs["row_scale"][sl], w.gate_kind, C)
+        check_solve(W[sl], W_ref, 2e-2, f"full cfg{idx} solve, batch {b} chunk {c}")
+    # (b) every chunk: || (I + A) W - s X ||_F / (|| I + A ||_F || W ||_F)
+    A = tri.gdn_chunk_build_A(K, beta, g, C, gate_kind=w.gate_kind, op_dtype=tri.F32)             # [B * n_chunk * H, C, C]
+    eye = torch.eye(C, device=DEV, dtype=torch.float64)
+    Wm = W.view(w.B, n_chunk, C, w.H, d_x).permute(0, 1, 3, 2, 4).reshape(-1, C, d_x)               # matrix order of A
+    Rm = (s[..., None] * X.float()).view(w.B, n_chunk, C, w.H, d_x).permute(0, 1, 3, 2, 4).reshape(-1, C, d_x)
+    worst = 0.0
+    for m0 in range(0, w.n_mat, 4096):
+        M = A[m0:m0 + 4096].double() + eye
+        Wd = Wm[m0:m0 + 4096].double()
+        R = torch.bmm(M, Wd) - Rm[m0:m0 + 4096].double()
+        nrm = torch.linalg.matrix_norm(R) / (torch.linalg.matrix_norm(M) * torch.linalg.matrix_norm(Wd))
+        assert bool(torch.isfinite(nrm).all())
+        worst = max(worst, float(nrm.max()))
+    assert worst <= 2e-3, (idx, worst)
