@@ -135,6 +135,44 @@ def test_varlen_argument_errors(L):
     assert call(T=R) == -7 and call(T=P) == -7
 
 
+def test_solve_argument_errors(L):
+    sv, vl = L.gdn_chunk_tri_solve, L.gdn_chunk_tri_solve_varlen
+    G = 1 << 30
+    base = dict(K=P, beta=Q, g=Q + G, X=Q + 2 * G, s=Q + 3 * G, W=Q + 4 * G, B=1, Tlen=128, H=2, d_k=128, d_x=128, C=64, kd=2,
+                gate=0, m=1, op=2, flags=0)
+
+    def call(**kw):
+        a = {**base, **kw}
+        return sv(a["K"], a["beta"], a["g"], a["X"], a["s"], a["W"], a["B"], a["Tlen"], a["H"], a["d_k"], a["d_x"], a["C"], a["kd"],
+                  a["gate"], a["m"], a["op"], None, a["flags"])
+
+    assert call(Tlen=0) == 0                                   # nothing to do
+    assert call(C=48) == -2 and call(kd=4) == -3 and call(op=3) == -3 and call(m=9) == -4 and call(gate=3) == -4
+    assert call(B=0) == -5 and call(H=0) == -5 and call(d_k=40) == -5 and call(Tlen=-1) == -5
+    assert call(d_x=0) == -5 and call(d_x=4) == -5 and call(d_x=60) == -5 and call(d_x=520) == -5
+    assert call(K=None) == -1 and call(X=None) == -1 and call(W=None) == -1 and call(g=None) == -1
+    assert call(X=Q + 2 * G + 8) == -6 and call(W=Q + 4 * G + 2) == -6 and call(s=Q + 3 * G + 2) == -6
+    assert call(W=P) == -7 and call(W=Q + 2 * G) == -7 and call(W=Q + 3 * G) == -7 and call(W=Q + G) == -7
+    # valid arguments, combination not built: other methods, refinement and output-type flags (checked before any launch)
+    assert call(m=0) == -9 and call(m=2) == -9 and call(m=4) == -9 and call(m=5) == -9 and call(m=6) == -9
+    assert call(flags=0x1) == -9 and call(flags=0x4) == -9
+
+    R = Q + 5 * G
+    vbase = dict(base, cs=R, cc=R + 4096, n_seq=3, tok=200, chunks=5)
+
+    def vcall(**kw):
+        a = {**vbase, **kw}
+        return vl(a["K"], a["beta"], a["g"], a["X"], a["s"], a["W"], a["cs"], a["cc"], a["n_seq"], a["tok"], a["chunks"], a["H"],
+                  a["d_k"], a["d_x"], a["C"], a["kd"], a["gate"], a["m"], a["op"], None, a["flags"])
+
+    assert vcall(tok=0, chunks=0) == 0
+    assert vcall(C=100) == -2 and vcall(n_seq=0) == -5 and vcall(chunks=3) == -5 and vcall(chunks=8) == -5 and vcall(d_x=12) == -5
+    assert vcall(cs=None) == -1 and vcall(cc=None) == -1 and vcall(W=None) == -1
+    assert vcall(cs=R + 4) == -6
+    assert vcall(W=R) == -7 and vcall(W=Q + 2 * G) == -7
+    assert vcall(m=2) == -9
+
+
 def test_binding_refuses_host_tensors_and_missing_library(monkeypatch, L):
     import torch
 
