@@ -61,6 +61,8 @@ def main() -> int:
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--solve-rhs", type=int, default=1, choices=[1, 2],
+                    help="with --solve: right-hand sides per launch (2 = two D_X-column tensors sharing one inversion)")
     ap.add_argument("--vendor-ref", action="store_true",
                     help="also time torch.linalg.solve_triangular (the ROCm libraries' batched triangular solve) on the same matrices")
     ap.add_argument("--solve", type=int, default=0, metavar="D_X",
@@ -361,14 +363,24 @@ def main() -> int:
         d_x = args.solve
         xdt = {0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[args.op]
         rhs = si.make_rhs(w, d_x, xdt)
+        n_rhs = args.solve_rhs
         Xs = [rhs["X"].to(dev) for _ in sets]
         Ws = [torch.empty_like(x) for x in Xs]
         scale = rhs["row_scale"].to(dev)
+        if n_rhs == 2:      # a second right-hand side of the same shape, with its own values, scale and result
+            rhs2 = si.make_rhs(w, d_x, xdt, seed_offset=1)
+            X2s = [rhs2["X"].to(dev) for _ in sets]
+            W2s = [torch.empty_like(x) for x in X2s]
+            scale2 = rhs2["row_scale"].to(dev)
 
         def solve_step(i):
             K, beta, g, _ = sets[i % len(sets)]
-            tri.gdn_chunk_tri_solve(K, beta, g, Xs[i % len(sets)], C, row_scale=scale, W=Ws[i % len(sets)], gate_kind=w.gate_kind,
-                                    method=args.method)
+            j = i % len(sets)
+            if n_rhs == 1:
+                tri.gdn_chunk_tri_solve(K, beta, g, Xs[j], C, row_scale=scale, W=Ws[j], gate_kind=w.gate_kind, method=args.method)
+            else:
+                tri.gdn_chunk_tri_solve_multi(K, beta, g, [Xs[j], X2s[j]], C, row_scales=[scale, scale2], Ws=[Ws[j], W2s[j]],
+                                              gate_kind=w.gate_kind, method=args.method)
 
         for i in range(args.warmup):
             solve_step(i)
@@ -382,14 +394,19 @@ def main() -> int:
         ms = e0.elapsed_time(e1) / args.steps
         esz = 4 if args.op == 0 else 2
         # inputs of the fused kernel (everything but T) + the row scale + X in + W out
-        bpm = algorithmic_bytes_per_matrix(w, True) - 4 * C * C + 4 * C + 2 * C * d_x * esz
+        bpm = algorithmic_bytes_per_matrix(w, True) - 4 * C * C + n_rhs * (4 * C + 2 * C * d_x * esz)
         # sampled check against the oracle: the first and the last batch entry's rows
         b_sel = sorted({0, w.B - 1})
         W_ref = oracle.gdn_chunk_tri_solve(inp["K"][b_sel], inp["beta"][b_sel], None if inp["g"] is None else inp["g"][b_sel],
                                            rhs["X"][b_sel], rhs["row_scale"][b_sel], w.gate_kind, C)
         W_gpu = Ws[(args.steps - 1) % len(sets)][b_sel].float().cpu().numpy().astype(np.float64)
         rel = float((np.sqrt(((W_gpu - W_ref) ** 2).sum(axis=(1, 3))) / np.sqrt((W_ref ** 2).sum(axis=(1, 3)))).max())
-        out["solve"] = {"entry": "gdn_chunk_tri_solve", "d_x": d_x, "x_dtype": tri.DTYPE_NAMES[args.op], "kernel_ms_avg": ms,
+        if n_rhs == 2:
+            W2_ref = oracle.gdn_chunk_tri_solve(inp["K"][b_sel], inp["beta"][b_sel], None if inp["g"] is None else inp["g"][b_sel],
+                                                rhs2["X"][b_sel], rhs2["row_scale"][b_sel], w.gate_kind, C)
+            W2_gpu = W2s[(args.steps - 1) % len(sets)][b_sel].float().cpu().numpy().astype(np.float64)
+            rel = max(rel, float((np.sqrt(((W2_gpu - W2_ref) ** 2).sum(axis=(1, 3))) / np.sqrt((W2_ref ** 2).sum(axis=(1, 3)))).max()))
+        out["solve"] = {"entry": "gdn_chunk_tri_solve" if n_rhs == 1 else "gdn_chunk_tri_solve_multi", "n_rhs": n_rhs, "d_x": d_x, "x_dtype": tri.DTYPE_NAMES[args.op], "kernel_ms_avg": ms,
                         "matrices_per_s": n_mat / (ms * 1e-3), "algorithmic_bytes_per_matrix": bpm,
                         "GBps": bpm * n_mat / (ms * 1e-3) / 1e9, "hbm_frac": bpm * n_mat / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                         "rel_fro_max_sampled": rel, "tolerance": 1e-5 if args.op == 0 else 2e-2,

@@ -226,7 +226,8 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
  *              not overlap X.  Caller-owned.
  *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
  *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R); d_k = 64 or 128 for the
- *              scalar / no-gate kinds; the per-channel gate at C <= 64 only, with any supported d_k.
+ *              scalar / no-gate kinds (not fp32 keys with d_k = 128 at C = 128); the per-channel gate at
+ *              C <= 64 only, with any supported d_k.
  *              Anything else returns TRIINV_ERR_UNSUPPORTED.
  *   flags      TRIINV_FLAG_MXR_R only.
  * Accuracy: that of the method's inverse (see tri_inv_ex) plus one rounding of the scaled inverse
@@ -237,6 +238,23 @@ int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g,
                         int B, int64_t Tlen, int H, int d_k, int d_x, int C,
                         int k_dtype, int gate_kind, int method, int op_dtype,
                         void* hip_stream, uint32_t flags);
+
+/*
+ * gdn_chunk_tri_solve_multi: gdn_chunk_tri_solve for one or two right-hand sides that share the inverse,
+ *     W_k = (I + A)^{-1} diag(s_k) X_k,   k = 0 .. n_rhs - 1,
+ * with A built and inverted once per chunk (e.g. the key-side and the value-side product of a layer in one pass).
+ *   n_rhs       1 or 2 (TRIINV_ERR_BAD_SHAPE otherwise); 2 at C <= 64 only (TRIINV_ERR_UNSUPPORTED at C = 128).
+ *   X, row_scale, W, d_x   HOST arrays of n_rhs entries: device pointers (row_scale[k] may be NULL) and column
+ *               counts, each as in gdn_chunk_tri_solve; read during the call only.  No W_k may overlap any
+ *               input, scale or other result.
+ * Everything else as in gdn_chunk_tri_solve.
+ */
+int gdn_chunk_tri_solve_multi(const void* K, const float* beta, const float* g,
+                              int n_rhs, const void* const* X, const float* const* row_scale,
+                              void* const* W, const int* d_x,
+                              int B, int64_t Tlen, int H, int d_k, int C,
+                              int k_dtype, int gate_kind, int method, int op_dtype,
+                              void* hip_stream, uint32_t flags);
 
 /*
  * gdn_chunk_tri_solve_varlen: gdn_chunk_tri_solve on sequences of different lengths packed back to back

@@ -42,7 +42,7 @@ METHOD_NAMES = {FWD_SUBST: "fwd_subst", BLOCK_RECURSIVE: "block_recursive", NEUM
 DTYPE_NAMES = {F32: "f32", F16: "f16", BF16: "bf16"}
 
 EXPORTS = ("tri_inv", "tri_inv_ex", "gdn_chunk_tri_inv", "gdn_chunk_tri_inv_ex", "gdn_chunk_tri_inv_varlen", "gdn_chunk_build_A",
-           "gdn_chunk_tri_solve", "gdn_chunk_tri_solve_varlen", "triinv_status_string", "triinv_version")
+           "gdn_chunk_tri_solve", "gdn_chunk_tri_solve_multi", "gdn_chunk_tri_solve_varlen", "triinv_status_string", "triinv_version")
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.gdn_chunk_build_A.restype = i32
         L.gdn_chunk_tri_solve.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, i32, i32, vp, u32]
         L.gdn_chunk_tri_solve.restype = i32
+        L.gdn_chunk_tri_solve_multi.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, i32, i32, vp, u32]
+        L.gdn_chunk_tri_solve_multi.restype = i32
         L.gdn_chunk_tri_solve_varlen.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i32, i32, i32, i32, vp, u32]
         L.gdn_chunk_tri_solve_varlen.restype = i32
         L.triinv_status_string.argtypes = [i32]
@@ -287,3 +289,33 @@ def gdn_chunk_tri_solve_varlen(K: torch.Tensor, beta: torch.Tensor, g: Optional[
         raise TriInvError(st, "gdn_chunk_tri_solve_varlen")
     W._triinv_keepalive = (cu_seqlens, cu_chunks)  # the launch is asynchronous: the offsets live as long as the result
     return W
+
+
+def gdn_chunk_tri_solve_multi(K: torch.Tensor, beta: torch.Tensor, g: Optional[torch.Tensor], Xs, C: int, row_scales=None, Ws=None,
+                              gate_kind: int = GATE_SCALAR, method: int = BLOCK_RECURSIVE, stream=None, flags: int = 0):
+    """W_k = (I + A)^{-1} diag(row_scales[k]) Xs[k] for one or two right-hand sides sharing one inversion per chunk.
+    Xs: sequence of [B, Tlen, H, d_x_k] tensors of one element type; row_scales: sequence of [B, Tlen, H] tensors or None."""
+    B, Tlen, H, d_k = K.shape
+    n = len(Xs)
+    if row_scales is None:
+        row_scales = [None] * n
+    if Ws is None:
+        Ws = [torch.empty_like(x) for x in Xs]
+    if len(row_scales) != n or len(Ws) != n:
+        raise ValueError("Xs, row_scales and Ws must have the same length")
+    for x, w in zip(Xs, Ws):
+        if tuple(x.shape[:3]) != (B, Tlen, H) or x.dtype != Xs[0].dtype or w.shape != x.shape or w.dtype != x.dtype:
+            raise ValueError("every X must be [B, Tlen, H, d_x] of one element type, every W like its X")
+    vp_arr = ctypes.c_void_p * n
+    xp = vp_arr(*[_dev(x, "X") if x.numel() else None for x in Xs])
+    sp = vp_arr(*[None if s is None else _dev(s, "row_scale") for s in row_scales])
+    wp = vp_arr(*[_dev(w, "W") if w.numel() else None for w in Ws])
+    dx = (ctypes.c_int32 * n)(*[int(x.shape[-1]) for x in Xs])
+    gp = None if g is None else _dev(g, "g")
+    st = lib().gdn_chunk_tri_solve_multi(_dev(K, "K"), _dev(beta, "beta"), gp, n, ctypes.cast(xp, ctypes.c_void_p),
+                                         ctypes.cast(sp, ctypes.c_void_p), ctypes.cast(wp, ctypes.c_void_p),
+                                         ctypes.cast(dx, ctypes.c_void_p), B, Tlen, H, d_k, C, dtype_code(K.dtype), gate_kind, method,
+                                         dtype_code(Xs[0].dtype), _stream_ptr(stream), flags)
+    if st != OK:
+        raise TriInvError(st, "gdn_chunk_tri_solve_multi")
+    return Ws

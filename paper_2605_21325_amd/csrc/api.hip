@@ -88,35 +88,54 @@ int check_fused(const void* K, const float* beta, const float* g, float* T, uint
     return TRIINV_OK;
 }
 
-// Shared tail of the two token layouts of the applied-inverse entry points.  n_token: tokens in K / X / W.
-int solve_common(const void* K, const float* beta, const float* g, const void* X, const float* row_scale, void* W, uint64_t n_token,
-                 int64_t n_chunk, const ChunkMap& map, int H, int d_k, int d_x, int C, int k_dtype, int gate_kind, int method,
-                 int op_dtype, void* hip_stream, uint32_t flags)
+// Shared tail of the applied-inverse entry points.  n_token: tokens in K / X / W; n_rhs right-hand sides (host arrays).
+int solve_common(const void* K, const float* beta, const float* g, int n_rhs, const void* const* X, const float* const* row_scale,
+                 void* const* W, const int* d_x, uint64_t n_token, int64_t n_chunk, const ChunkMap& map, int H, int d_k, int C,
+                 int k_dtype, int gate_kind, int method, int op_dtype, void* hip_stream, uint32_t flags)
 {
     if (!dtype_ok(k_dtype) || !dtype_ok(op_dtype)) return TRIINV_ERR_BAD_DTYPE;
     if (!method_ok(method)) return TRIINV_ERR_BAD_METHOD;
     if (gate_kind < TRIINV_GATE_SCALAR || gate_kind > TRIINV_GATE_NONE) return TRIINV_ERR_BAD_METHOD;
     if (H <= 0 || d_k <= 0 || d_k % 32 != 0 || d_k > 256) return TRIINV_ERR_BAD_SHAPE;
-    if (d_x < 8 || d_x > 512 || d_x % 8 != 0) return TRIINV_ERR_BAD_SHAPE;
+    if (n_rhs < 1 || n_rhs > 2) return TRIINV_ERR_BAD_SHAPE;
+    if (!X || !row_scale || !W || !d_x) return TRIINV_ERR_NULL;
+    for (int k = 0; k < n_rhs; ++k)
+        if (d_x[k] < 8 || d_x[k] > 512 || d_x[k] % 8 != 0) return TRIINV_ERR_BAD_SHAPE;
     if (n_chunk > 0x7fffffffLL / H) return TRIINV_ERR_BAD_SHAPE;
     const int64_t n_mat = n_chunk * H;
     if (n_mat == 0) return TRIINV_OK;
     const bool need_g = gate_kind != TRIINV_GATE_NONE;
-    if (!K || !beta || !X || !W || (need_g && !g)) return TRIINV_ERR_NULL;
-    if (!aligned16(K) || !aligned16(beta) || !aligned16(X) || !aligned16(W) || (need_g && !aligned16(g)) ||
-        (reinterpret_cast<uintptr_t>(row_scale) & 3u))
-        return TRIINV_ERR_ALIGN;
-    const uint64_t n_tok = n_token * H, w_bytes = n_tok * d_x * esize(op_dtype);
-    if (overlap(K, n_tok * d_k * esize(k_dtype), W, w_bytes) || overlap(beta, n_tok * 4, W, w_bytes) || overlap(X, w_bytes, W, w_bytes) ||
-        (row_scale && overlap(row_scale, n_tok * 4, W, w_bytes)) ||
-        (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), W, w_bytes)))
-        return TRIINV_ERR_ALIAS;
+    if (!K || !beta || (need_g && !g)) return TRIINV_ERR_NULL;
+    for (int k = 0; k < n_rhs; ++k)
+        if (!X[k] || !W[k]) return TRIINV_ERR_NULL;
+    if (!aligned16(K) || !aligned16(beta) || (need_g && !aligned16(g))) return TRIINV_ERR_ALIGN;
+    for (int k = 0; k < n_rhs; ++k)
+        if (!aligned16(X[k]) || !aligned16(W[k]) || (reinterpret_cast<uintptr_t>(row_scale[k]) & 3u)) return TRIINV_ERR_ALIGN;
+    const uint64_t n_tok = n_token * H;
+    for (int k = 0; k < n_rhs; ++k) {
+        const uint64_t w_bytes = n_tok * d_x[k] * esize(op_dtype);
+        if (overlap(K, n_tok * d_k * esize(k_dtype), W[k], w_bytes) || overlap(beta, n_tok * 4, W[k], w_bytes) ||
+            (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), W[k], w_bytes)))
+            return TRIINV_ERR_ALIAS;
+        for (int j = 0; j < n_rhs; ++j) {  // no result may overlap any right-hand side, scale or other result
+            const uint64_t x_bytes = n_tok * d_x[j] * esize(op_dtype);
+            if (overlap(X[j], x_bytes, W[k], w_bytes) || (row_scale[j] && overlap(row_scale[j], n_tok * 4, W[k], w_bytes)) ||
+                (j != k && overlap(W[j], x_bytes, W[k], w_bytes)))
+                return TRIINV_ERR_ALIAS;
+        }
+    }
     if (flags & ~0x70000u) return TRIINV_ERR_UNSUPPORTED;  // TRIINV_FLAG_MXR_R only
     if (method != TRIINV_BLOCK_RECURSIVE && method != TRIINV_MIXED) return TRIINV_ERR_UNSUPPORTED;
 
     SolveArgs a{GdnArgs{K, beta, need_g ? g : nullptr, nullptr, n_mat, n_chunk, map, H, d_k, k_dtype, gate_kind, method,
                         static_cast<hipStream_t>(hip_stream), false, method_count(method, flags, C), TRIINV_F32},
-                X, row_scale, W, d_x};
+                n_rhs, {}, {}, {}, {}};
+    for (int k = 0; k < n_rhs; ++k) {
+        a.X[k] = X[k];
+        a.scale[k] = row_scale[k];
+        a.W[k] = W[k];
+        a.d_x[k] = d_x[k];
+    }
     int nb = 1;
 #define TRIINV_PICK_OP(NBV) \
     (op_dtype == TRIINV_F32 ? launch_solve_nb##NBV##_op0(a) : op_dtype == TRIINV_F16 ? launch_solve_nb##NBV##_op1(a) : launch_solve_nb##NBV##_op2(a))
@@ -263,8 +282,21 @@ int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g, const 
     const int64_t cps = (Tlen + C - 1) / C;
     if (cps > 0x7fffffffLL / B) return TRIINV_ERR_BAD_SHAPE;
     const ChunkMap map{Tlen, (uint32_t)cps, 0u, nullptr, nullptr};
-    return solve_common(K, beta, g, X, row_scale, W, (uint64_t)B * Tlen, (int64_t)B * cps, map, H, d_k, d_x, C, k_dtype, gate_kind,
-                        method, op_dtype, hip_stream, flags);
+    return solve_common(K, beta, g, 1, &X, &row_scale, &W, &d_x, (uint64_t)B * Tlen, (int64_t)B * cps, map, H, d_k, C, k_dtype,
+                        gate_kind, method, op_dtype, hip_stream, flags);
+}
+
+int gdn_chunk_tri_solve_multi(const void* K, const float* beta, const float* g, int n_rhs, const void* const* X,
+                              const float* const* row_scale, void* const* W, const int* d_x, int B, int64_t Tlen, int H, int d_k,
+                              int C, int k_dtype, int gate_kind, int method, int op_dtype, void* hip_stream, uint32_t flags)
+{
+    if (!chunk_size_ok(C)) return TRIINV_ERR_BAD_C;
+    if (B <= 0 || Tlen < 0) return TRIINV_ERR_BAD_SHAPE;
+    const int64_t cps = (Tlen + C - 1) / C;
+    if (cps > 0x7fffffffLL / B) return TRIINV_ERR_BAD_SHAPE;
+    const ChunkMap map{Tlen, (uint32_t)cps, 0u, nullptr, nullptr};
+    return solve_common(K, beta, g, n_rhs, X, row_scale, W, d_x, (uint64_t)B * Tlen, (int64_t)B * cps, map, H, d_k, C, k_dtype,
+                        gate_kind, method, op_dtype, hip_stream, flags);
 }
 
 int gdn_chunk_tri_solve_varlen(const void* K, const float* beta, const float* g, const void* X, const float* row_scale, void* W,
@@ -283,8 +315,8 @@ int gdn_chunk_tri_solve_varlen(const void* K, const float* beta, const float* g,
         if (overlap(cu_seqlens, cu_bytes, W, w_bytes) || overlap(cu_chunks, cu_bytes, W, w_bytes)) return TRIINV_ERR_ALIAS;
     }
     const ChunkMap map{0, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
-    return solve_common(K, beta, g, X, row_scale, W, (uint64_t)total_tokens, total_chunks, map, H, d_k, d_x, C, k_dtype, gate_kind,
-                        method, op_dtype, hip_stream, flags);
+    return solve_common(K, beta, g, 1, &X, &row_scale, &W, &d_x, (uint64_t)total_tokens, total_chunks, map, H, d_k, C, k_dtype,
+                        gate_kind, method, op_dtype, hip_stream, flags);
 }
 
 int gdn_chunk_tri_inv(const void* K, const float* beta, const float* g, float* T, int B, int64_t Tlen, int H, int d_k, int C)

@@ -42,10 +42,11 @@ struct GdnArgs {
 // gdn_chunk_tri_solve: the fused arguments (T unused) plus the right-hand sides.
 struct SolveArgs {
     GdnArgs f;
-    const void* X;       // [tokens][H][d_x], element type = operand type
-    const float* scale;  // [tokens][H] or null
-    void* W;             // [tokens][H][d_x]
-    int d_x;
+    int n_rhs;             // 1 or 2 right-hand sides sharing the inverse
+    const void* X[2];      // [tokens][H][d_x], element type = operand type
+    const float* scale[2]; // [tokens][H] or null
+    void* W[2];            // [tokens][H][d_x]
+    int d_x[2];
 };
 
 // Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.

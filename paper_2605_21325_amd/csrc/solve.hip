@@ -24,14 +24,31 @@ constexpr unsigned PAD = (NB == 4 && OP != OP_F32) ? 24576u : 0u;
 // after the recursion at C = 128, whose tiles and keys fill the register file (measured equal at C = 64).
 constexpr int XPOS = NB <= 4 ? 1 : 3;
 
-static RhsArgs rhs_of(const SolveArgs& a) { return RhsArgs{a.X, a.scale, a.W, a.d_x}; }
+static RhsList rhs_of(const SolveArgs& a)
+{
+    RhsList l{};
+    for (int k = 0; k < a.n_rhs && k < MAX_RHS; ++k) l.r[k] = RhsArgs{a.X[k], a.scale[k], a.W[k], a.d_x[k]};
+    return l;
+}
+
+// Two right-hand sides per launch are built at C <= 64.
+constexpr bool HAS_PAIR = NB <= 4;
 
 template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
 {
     const GdnArgs& f = a.f;
-    hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS>), dim3((unsigned)((f.n_mat + WPB - 1) / WPB)), dim3(64 * WPB),
-                       PAD, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
-    return 0;
+    const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
+    if (a.n_rhs == 1) {
+        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 1>), grid, block, PAD, f.stream, f.K, f.beta, f.g,
+                           rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+        return 0;
+    }
+    if constexpr (HAS_PAIR) {
+        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 2>), grid, block, PAD, f.stream, f.K, f.beta, f.g,
+                           rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+        return 0;
+    }
+    return 1;
 }
 
 template <int KD, int DKS> static int gdn_method(const SolveArgs& a)
@@ -44,15 +61,25 @@ template <int KD, int DKS> static int gdn_method(const SolveArgs& a)
 template <int METHOD> static int go_kda(const SolveArgs& a)
 {
     const GdnArgs& f = a.f;
-    hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB>), dim3((unsigned)((f.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
-                       f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.k_dt, f.iters);
-    return 0;
+    const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
+    if (a.n_rhs == 1) {
+        hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+                           f.map, f.H, f.d_k, f.k_dt, f.iters);
+        return 0;
+    }
+    if constexpr (HAS_PAIR) {
+        hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+                           f.map, f.H, f.d_k, f.k_dt, f.iters);
+        return 0;
+    }
+    return 1;
 }
 
 int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a)
 {
     const GdnArgs& f = a.f;
     if (f.refine) return 1;
+    if (a.n_rhs < 1 || a.n_rhs > MAX_RHS) return 1;
     if (f.gate == G_CHANNEL) {
 #if TRIINV_INST_NB <= 4
         if (f.method == M_BLOCK) return go_kda<M_BLOCK>(a);
@@ -62,7 +89,11 @@ int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a
     }
     if (f.k_dt == OP_F32) {
         if (f.d_k == 64) return gdn_method<OP_F32, 4>(a);
+#if TRIINV_INST_NB <= 4
         if (f.d_k == 128) return gdn_method<OP_F32, 8>(a);
+#else
+        if (f.d_k == 128) return 1;  // 128 fp32 channels x 128 rows of keys beside the right-hand sides do not fit the register file
+#endif
     } else if (f.k_dt == OP_BF16) {
         if (f.d_k == 64) return gdn_method<OP_BF16, 2>(a);
         if (f.d_k == 128) return gdn_method<OP_BF16, 4>(a);

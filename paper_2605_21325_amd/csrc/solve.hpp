@@ -24,6 +24,13 @@ struct RhsArgs {
     int d_x;
 };
 
+// NRHS right-hand sides sharing one inverse: W_k = T diag(s_k) X_k.  NRHS is a compile-time count (1 or 2) so that
+// every access to the list is a plain kernel-argument read.
+constexpr int MAX_RHS = 2;
+struct RhsList {
+    RhsArgs r[MAX_RHS];
+};
+
 // Sixteen bytes of one row of X as stored: VEC consecutive columns.
 template <int OP> struct XRow;
 template <> struct XRow<OP_F32> { v4f f; };
@@ -137,22 +144,25 @@ template <int OP, int NB> struct RhsX {
     }
 };
 
-// Recursion (blocked, or mixed with aux refinement steps on the leaves), then W = T diag(s) X.
+// Recursion (blocked, or mixed with aux refinement steps on the leaves), then W_k = T diag(s_k) X_k for the NRHS
+// right-hand sides in turn; x holds the first one, next_rhs(k) re-initialises x for right-hand side k and starts the
+// loads of its first column group.  Two right-hand sides are built at C <= 64 only, where the 10 fp32 tiles of T stay
+// in registers beside everything else.
 // ISSUE_FROM: the loads of tile rows ISSUE_FROM .. NB - 1 of X's first column group start here (the caller has
 // issued the rows before).  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
 // IN_MERGE: ... inside the recursion's last merge (as soon as its tiles of A exist: a source that holds keys in
 // registers has them free from there on, and the merge's products run while the loads are in flight); otherwise
 // after the recursion.
-template <int OP, int NB, int METHOD, int ISSUE_FROM, bool IN_MERGE = false, class ASrc>
-__device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& x, float* lds, Lane ln, int aux)
+template <int OP, int NB, int METHOD, int ISSUE_FROM, bool IN_MERGE, int NRHS, class ASrc, class NextRhs>
+__device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& x, float* lds, Lane ln, int aux, NextRhs next_rhs)
 {
     static_assert(METHOD == M_BLOCK || METHOD == M_MIXED, "built for the blocked and the mixed recursion");
     constexpr int NT = NB * (NB + 1) / 2;
-    Opnd<OP> Top[NT];
+    static_assert(NRHS == 1 || NB <= 4, "two right-hand sides: C <= 64");
+    v4f Tm[NT];  // T orientation: Tm[tix(i, j)][r] = T[16 i + n][16 j + 4 q + r], exact unit diagonal, zeros above it
     {
-        v4f Tt[NT];
         constexpr int LEAF = METHOD == M_MIXED ? LEAF_NEUMANN : LEAF_BLOCK_RECURSIVE;
-        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tt, lds, ln, aux, [&]() {
+        block_recursive<OP, NB, ROOT_T, LEAF>(src, Tm, lds, ln, aux, [&]() {
             if constexpr (ISSUE_FROM < NB && IN_MERGE) x.issue(0, ISSUE_FROM, NB);
         });
         if constexpr (ISSUE_FROM < NB && !IN_MERGE) x.issue(0, ISSUE_FROM, NB);
@@ -160,48 +170,57 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
         for (int i = 0; i < NB; ++i)
 #pragma unroll
             for (int j = 0; j <= i; ++j) {
-                v4f t = Tt[tix(i, j)];
+                v4f t = Tm[tix(i, j)];
                 if (!result_is_T<NB, ROOT_T>(i, j)) t = transpose_tile(t, lds, ln);
-                // t[r] = T[16 i + n][16 j + 4 q + r]: exact unit diagonal, zeros above it, column scale
+                if (i == j) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int rr = ln.n, cc = 4 * ln.q + r;
-                    float v = t[r];
-                    if (i == j) v = (rr == cc) ? 1.f : ((rr > cc) ? v : 0.f);
-                    t[r] = v * x.s_q[j][r];
+                    for (int r = 0; r < 4; ++r) {
+                        const int rr = ln.n, cc = 4 * ln.q + r;
+                        t[r] = (rr == cc) ? 1.f : ((rr > cc) ? t[r] : 0.f);
+                    }
                 }
-                Top[tix(i, j)] = pack<OP>(t);
+                Tm[tix(i, j)] = t;
             }
     }
     constexpr int VEC = RhsX<OP, NB>::VEC;
-    const int n_group = x.n_group();
-    for (int gi = 0;;) {
-        Opnd<OP> xo[NB][VEC];
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
+    for (int k = 0; k < NRHS; ++k) {
+        if (k > 0) next_rhs(k);
+        Opnd<OP> Top[NT];  // columns scaled by s in fp32, then rounded to the operand type
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) xo[j][c] = x_operand<OP>(x.raw[j], c);
+        for (int i = 0; i < NB; ++i)
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            v4f acc[VEC];
+            for (int j = 0; j <= i; ++j) Top[tix(i, j)] = pack<OP>(Tm[tix(i, j)] * x.s_q[j]);
+        const int n_group = x.n_group();
+#pragma unroll 1
+        for (int gi = 0;;) {
+            Opnd<OP> xo[NB][VEC];
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) acc[c] = zero4();
+            for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int j = 0; j <= i; ++j)
+                for (int c = 0; c < VEC; ++c) xo[j][c] = x_operand<OP>(x.raw[j], c);
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(Top[tix(i, j)], xo[j][c], acc[c]);
-            x.store(gi, i, acc);
+            for (int i = 0; i < NB; ++i) {
+                v4f acc[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = zero4();
+#pragma unroll
+                for (int j = 0; j <= i; ++j)
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(Top[tix(i, j)], xo[j][c], acc[c]);
+                x.store(gi, i, acc);
+            }
+            if (++gi >= n_group) break;
+            x.issue(gi);
         }
-        if (++gi >= n_group) break;
-        x.issue(gi);
     }
 }
 
 // XPOS: where X's first loads are issued -- 1: between the Gram products and the recursion, 2: after the recursion,
 // 3: half before the recursion (with the keys still in registers), half after it.
-template <int KD, int OP, int NB, int METHOD, int DKS, int WPB, int XPOS>
+template <int KD, int OP, int NB, int METHOD, int DKS, int WPB, int XPOS, int NRHS>
 __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
-                                                            const float* __restrict__ g, RhsArgs rhs, int64_t n_chunk, ChunkMap map,
+                                                            const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
                                                             int H, int d_k, int aux)
 {
     constexpr int C = 16 * NB;
@@ -223,7 +242,11 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
     src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
     src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
     RhsX<OP, NB> x;
-    x.init(rhs, tok0, h, H, pos.valid, ln);
+    x.init(rhs.r[0], tok0, h, H, pos.valid, ln);
+    auto next_rhs = [&](int k) {
+        x.init(rhs.r[k < MAX_RHS ? k : 0], tok0, h, H, pos.valid, ln);
+        x.issue(0);
+    };
     src.stage_gate(lds);
     if constexpr (XPOS == 1) {
         // every tile of A first (the key registers are free afterwards), then X's loads, then the recursion
@@ -236,9 +259,9 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
                 if (need_tile<NB, METHOD>(i, j, true)) pre.t[tix(i, j)] = src.template get<true>(i, j);
             }
         x.issue(0);
-        invert_and_apply<OP, NB, METHOD, NB>(pre, x, lds, ln, aux);
+        invert_and_apply<OP, NB, METHOD, NB, false, NRHS>(pre, x, lds, ln, aux, next_rhs);
     } else if constexpr (XPOS == 2) {
-        invert_and_apply<OP, NB, METHOD, 0>(src, x, lds, ln, aux);
+        invert_and_apply<OP, NB, METHOD, 0, false, NRHS>(src, x, lds, ln, aux, next_rhs);
     } else {
         // the first tile rows of X before the recursion (as many as the registers beside the keys allow), the rest
         // after it: the first strips are multiplied and stored while the later rows' loads are still in flight
@@ -246,13 +269,13 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
         constexpr int EARLY = KEY_REGS <= 64 ? NB / 2 : KEY_REGS <= 128 ? NB / 4 : 0;
         constexpr bool IN_MERGE = KEY_REGS <= 128 && KD != OP_F32 && OP != OP_F32;  // elsewhere the registers do not allow it
         x.issue(0, 0, EARLY);
-        invert_and_apply<OP, NB, METHOD, EARLY, IN_MERGE>(src, x, lds, ln, aux);
+        invert_and_apply<OP, NB, METHOD, EARLY, IN_MERGE, NRHS>(src, x, lds, ln, aux, next_rhs);
     }
 }
 
-template <int OP, int NB, int METHOD, int WPB>
+template <int OP, int NB, int METHOD, int WPB, int NRHS>
 __global__ __launch_bounds__(64 * WPB) void k_kda_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
-                                                            const float* __restrict__ g, RhsArgs rhs, int64_t n_chunk, ChunkMap map,
+                                                            const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
                                                             int H, int d_k, int k_dt, int aux)
 {
     constexpr int C = 16 * NB;
@@ -273,9 +296,13 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_solve(const void* __restri
     build_A_per_channel<OP, NB, METHOD>(src, static_cast<const char*>(K) + e0 * esz, k_dt, g + e0, (int64_t)H * d_k,
                                         beta + tok0 * H + h, H, d_k, lds, ln, pos.valid);
     RhsX<OP, NB> x;  // after the Gram passes, which need the registers
-    x.init(rhs, tok0, h, H, pos.valid, ln);
+    x.init(rhs.r[0], tok0, h, H, pos.valid, ln);
+    auto next_rhs = [&](int k) {
+        x.init(rhs.r[k < MAX_RHS ? k : 0], tok0, h, H, pos.valid, ln);
+        x.issue(0);
+    };
     x.issue(0);
-    invert_and_apply<OP, NB, METHOD, NB>(src, x, lds, ln, aux);
+    invert_and_apply<OP, NB, METHOD, NB, false, NRHS>(src, x, lds, ln, aux, next_rhs);
 }
 
 }  // namespace triinv

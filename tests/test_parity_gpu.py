@@ -1065,3 +1065,43 @@ def test_solve_full_size_workload(idx):
         assert bool(torch.isfinite(nrm).all())
         worst = max(worst, float(nrm.max()))
     assert worst <= 2e-3, (idx, worst)
+
+
+@pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("idx,kw", [(1, dict(Tlen=300, H=4)), (3, dict(B=2, Tlen=128, H=3)), (4, dict(Tlen=200, H=4, C=32)),
+                                    (1, dict(Tlen=96, H=2, C=16))])
+def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
+    # two right-hand sides of different widths and scales in one launch: each result is what a launch of its own gives
+    # (bit for bit: the same kernels' arithmetic), and matches the oracle
+    w = si.workload(idx, **kw)
+    inp = si.make_inputs(w)
+    r1, r2 = si.make_rhs(w, 128, XDT[op]), si.make_rhs(w, 72, XDT[op], seed_offset=1)
+    K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    X1, X2, s2 = r1["X"].to(DEV), r2["X"].to(DEV), r2["row_scale"].to(DEV)
+    for method in (tri.BLOCK_RECURSIVE, tri.MIXED):
+        W1, W2 = tri.gdn_chunk_tri_solve_multi(K, beta, g, [X1, X2], w.C, row_scales=[None, s2], gate_kind=w.gate_kind, method=method)
+        E1 = tri.gdn_chunk_tri_solve(K, beta, g, X1, w.C, gate_kind=w.gate_kind, method=method)
+        E2 = tri.gdn_chunk_tri_solve(K, beta, g, X2, w.C, row_scale=s2, gate_kind=w.gate_kind, method=method)
+        torch.cuda.synchronize()
+        assert torch.equal(W1, E1) and torch.equal(W2, E2)
+        check_solve(W1, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], None, w.gate_kind, w.C), SOLVE_TOL[op], "rhs 0")
+        check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], r2["row_scale"], w.gate_kind, w.C),
+                    SOLVE_TOL[op], "rhs 1")
+
+
+def test_solve_multi_limits():
+    w, inp, rhs = solve_case(4, 64, tri.BF16, Tlen=256, H=2)
+    K, beta, X = inp["K"].to(DEV), inp["beta"].to(DEV), rhs["X"].to(DEV)
+    with pytest.raises(tri.TriInvError) as e:                                 # two right-hand sides at C = 128
+        tri.gdn_chunk_tri_solve_multi(K, beta, None, [X, X.clone()], 128, gate_kind=tri.GATE_NONE)
+    assert e.value.status == -9
+    with pytest.raises(tri.TriInvError) as e:                                 # three
+        tri.gdn_chunk_tri_solve_multi(K, beta, None, [X, X.clone(), X.clone()], 64, gate_kind=tri.GATE_NONE)
+    assert e.value.status == -5
+    W = torch.empty_like(X)
+    with pytest.raises(tri.TriInvError) as e:                                 # both results in one buffer
+        tri.gdn_chunk_tri_solve_multi(K, beta, None, [X, X.clone()], 64, Ws=[W, W], gate_kind=tri.GATE_NONE)
+    assert e.value.status == -7
+    (W1,) = tri.gdn_chunk_tri_solve_multi(K, beta, None, [X], 128, gate_kind=tri.GATE_NONE)   # one is fine at C = 128
+    assert torch.equal(W1, tri.gdn_chunk_tri_solve(K, beta, None, X, 128, gate_kind=tri.GATE_NONE))
