@@ -173,6 +173,29 @@ def test_solve_argument_errors(L):
     assert vcall(m=2) == -9
 
 
+def test_solve_multi_argument_errors(L):
+    import ctypes
+
+    G = 1 << 30
+    mv = L.gdn_chunk_tri_solve_multi
+
+    def call(n=2, X=(Q + 2 * G, Q + 3 * G), S=(None, Q + 4 * G), W=(Q + 5 * G, Q + 6 * G), dx=(128, 64), C=64, m=1, K=P):
+        arr = ctypes.c_void_p * len(X)
+        xs, ss, ws = arr(*X), arr(*S), arr(*W)
+        ds = (ctypes.c_int32 * len(dx))(*dx)
+        cast = lambda a: ctypes.cast(a, ctypes.c_void_p)
+        return mv(K, Q, Q + G, n, cast(xs), cast(ss), cast(ws), cast(ds), 1, 128, 2, 128, C, 2, 0, m, 2, None, 0)
+
+    assert call(n=0) == -5 and call(n=3, X=(P,) * 3, S=(None,) * 3, W=(Q,) * 3, dx=(8,) * 3) == -5
+    assert call(dx=(128, 12)) == -5
+    assert call(X=(Q + 2 * G, None)) == -1 and call(W=(None, Q + 6 * G)) == -1 and call(K=None) == -1
+    assert call(W=(Q + 5 * G, Q + 6 * G + 4)) == -6 and call(S=(None, Q + 4 * G + 1)) == -6
+    assert call(W=(Q + 5 * G, Q + 5 * G)) == -7              # the two results in one buffer
+    assert call(W=(Q + 3 * G, Q + 6 * G)) == -7              # result 0 on top of right-hand side 1
+    assert call(W=(Q + 5 * G, Q + 4 * G)) == -7              # result 1 on top of scale 1
+    assert call(m=2) == -9
+
+
 def test_binding_refuses_host_tensors_and_missing_library(monkeypatch, L):
     import torch
 
