@@ -61,6 +61,10 @@ def main() -> int:
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="the shape of the paper's kernel-scaling experiment (Sec. 5.1): B=32, 4 heads, C=64, sequence lengths "
+                         "1K..16K, every method, 5 warm-up + 20 timed launches with the cache cleared before each; prints its own "
+                         "JSON line and exits")
     ap.add_argument("--solve-rhs", type=int, default=1, choices=[1, 2],
                     help="with --solve: right-hand sides per launch (2 = two D_X-column tensors sharing one inversion)")
     ap.add_argument("--vendor-ref", action="store_true",
@@ -93,6 +97,42 @@ def main() -> int:
         return 3
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.paper_sweep:
+        # Sec. 5.1's experiment on this chip: the workload recipe of configs[2] (bf16 keys, scalar gate, d_k = 128) at the
+        # paper's batch 32 x 4 heads; the cache is cleared by reading an unrelated 512 MiB buffer before every launch
+        flush = torch.empty(1 << 27, dtype=torch.float32, device=dev).normal_()
+        rows = []
+        variants = [("fwd_subst", 0, 0), ("block_recursive", 1, 2), ("mixed", 3, 2), ("mixed_b32", 6, 2), ("block_direct", 4, 2),
+                    ("neumann", 2, 2), ("newton_schulz", 5, 2)]
+        for Tlen in (1024, 2048, 4096, 8192, 16384):
+            ws = si.workload(2, B=32, Tlen=Tlen, H=4)
+            si_inp = si.make_inputs(ws)
+            K, beta, g = si_inp["K"].to(dev), si_inp["beta"].to(dev), si_inp["g"].to(dev)
+            T = torch.empty((ws.n_mat, 64, 64), device=dev)
+            A32 = tri.gdn_chunk_build_A(K, beta, g, 64, op_dtype=tri.F32)
+            for name, method, op in variants:
+                for entry in ("fused", "standalone"):
+                    ms = []
+                    for i in range(25):
+                        sink = flush.sum()
+                        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        a.record()
+                        if entry == "fused":
+                            tri.gdn_chunk_tri_inv_ex(K, beta, g, 64, T=T, method=method, op_dtype=op)
+                        else:
+                            tri.tri_inv_ex(A32, T=T, method=method, op_dtype=op)
+                        b.record()
+                        torch.cuda.synchronize()
+                        if i >= 5:
+                            ms.append(a.elapsed_time(b))
+                    rows.append({"Tlen": Tlen, "n_mat": ws.n_mat, "method": name, "op": tri.DTYPE_NAMES[op], "entry": entry,
+                                 "us_median": float(np.median(ms)) * 1e3, "us_min": float(np.min(ms)) * 1e3,
+                                 "matrices_per_s": ws.n_mat / (float(np.median(ms)) * 1e-3)})
+            del K, beta, g, T, A32
+        print(json.dumps({"paper_sweep": rows, "protocol": "B=32, H=4, d_k=128, C=64, bf16 keys, scalar gate; per point 5 warm-up + 20 "
+                          "timed launches, a 512 MiB read before each to clear the caches, HIP events around the single launch, median"}))
+        return 0
 
     out_torch = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.out]
     out_bytes = 4 if args.out == "f32" else 2
