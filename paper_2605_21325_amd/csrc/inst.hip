@@ -99,16 +99,19 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 // Unused dynamic LDS that keeps a compute unit (160 KB of LDS) at two workgroups = two wavefronts per
 // SIMD for the 16-bit-operand recursions at C = 64.  Those kernels are bound by the memory system,
 // not by latency: with more wavefronts resident they measured 2-4 % slower (more requests queued at
-// the memory controllers, none served sooner).
-template <int METHOD> constexpr unsigned occupancy_pad_bytes()
+// the memory controllers, none served sooner).  That holds for H >= 8; with fewer heads (key rows less
+// than 2 KB apart) memory latency measured ~10 % higher and the third wavefront per SIMD gains 4-5 %.
+template <int METHOD> unsigned occupancy_pad_bytes(int H)
 {
-    return (NB == 4 && WPB == 4 && OP != OP_F32 && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT)) ? 24576u : 0u;
+    constexpr bool padded = NB == 4 && WPB == 4 && OP != OP_F32 &&
+                            (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT);
+    return (padded && H >= 8) ? 24576u : 0u;
 }
 
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
-                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
+                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(a.H), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
                        a.iters, a.out_dt);
     return 0;
 }

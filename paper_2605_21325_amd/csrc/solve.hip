@@ -16,10 +16,6 @@ constexpr int NB = TRIINV_INST_NB;
 constexpr int OP = TRIINV_INST_OP;
 constexpr int WPB = NB <= 4 ? 4 : 1;  // four adjacent heads per workgroup at C <= 64, as in the storing kernels
 
-// Two wavefronts per SIMD for the 16-bit-operand kernels at C = 64 (see the storing kernels: they are bound
-// by the memory system and measured slower with more wavefronts resident).
-constexpr unsigned PAD = (NB == 4 && OP != OP_F32) ? 24576u : 0u;
-
 // X's first loads: between the Gram products and the recursion at C <= 64 (the keys' registers are free by then);
 // after the recursion at C = 128, whose tiles and keys fill the register file (measured equal at C = 64).
 constexpr int XPOS = NB <= 4 ? 1 : 3;
@@ -39,12 +35,12 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     const GdnArgs& f = a.f;
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {
-        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 1>), grid, block, PAD, f.stream, f.K, f.beta, f.g,
+        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g,
                            rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
         return 0;
     }
     if constexpr (HAS_PAIR) {
-        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 2>), grid, block, PAD, f.stream, f.K, f.beta, f.g,
+        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g,
                            rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
         return 0;
     }
