@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--mover", action="store_true",
+                    help="also time the data mover of libtriinv_probe.so: the fused kernel's memory access pattern and nothing "
+                         "else, on the same buffers (the practical ceiling of that pattern; 16-bit keys, d_k = 128, scalar / no gate)")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="the shape of the paper's kernel-scaling experiment (Sec. 5.1): B=32, 4 heads, C=64, sequence lengths "
                          "1K..16K, every method, 5 warm-up + 20 timed launches with the cache cleared before each; prints its own "
@@ -373,6 +376,41 @@ def main() -> int:
     }
     if copy_ref is not None:
         out["copy_ref"] = copy_ref
+
+    if args.mover and w.k_dtype == "bf16" and w.d_k == 128 and w.gate_kind != si.GATE_PER_CHANNEL and C in (64, 128) \
+            and args.out == "f32" and (C == 128 or w.H % 4 == 0):
+        import ctypes
+        from paper_2605_21325_amd import build as tri_build
+        P = ctypes.CDLL(tri_build.PROBE_LIB)
+        P.triinv_probe_mover.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_uint,
+                                         ctypes.c_void_p]
+        P.triinv_probe_mover.restype = ctypes.c_int
+        n_chunk = n_mat // w.H
+        # the resident-wavefront count the real kernel runs with: two workgroups of four per compute unit at C = 64 (H >= 8),
+        # four one-wavefront workgroups at C = 128
+        pad = (24576 if w.H >= 8 else 0) if C == 64 else 40000
+        stream = torch.cuda.current_stream().cuda_stream or None
+
+        def move(i):
+            K, _, _, T = sets[i % len(sets)]
+            rc = P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, w.H, C, pad, stream)
+            assert rc == 0, rc
+
+        for i in range(args.warmup):
+            move(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            move(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        moved = C * 256 + 4 * C * C            # key rows in, fp32 matrix out (beta / g are not read)
+        out["mover"] = {"what": "same key-load and result-store pattern as the fused kernel, no arithmetic", "kernel_ms_avg": ms,
+                        "bytes_per_matrix": moved, "GBps": moved * n_mat / (ms * 1e-3) / 1e9,
+                        "hbm_frac": moved * n_mat / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "fused_kernel_over_mover_time": avg_kernel_ms / ms}
 
     if args.vendor_ref:
         # context only: the vendor libraries' batched triangular solve against the identity, fp32, on the same chunk
