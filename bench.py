@@ -383,7 +383,7 @@ def main() -> int:
         from paper_2605_21325_amd import build as tri_build
         P = ctypes.CDLL(tri_build.PROBE_LIB)
         P.triinv_probe_mover.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_uint,
-                                         ctypes.c_void_p]
+                                         ctypes.c_int, ctypes.c_void_p]
         P.triinv_probe_mover.restype = ctypes.c_int
         n_chunk = n_mat // w.H
         # the resident-wavefront count the real kernel runs with: two workgroups of four per compute unit at C = 64 (H >= 8),
@@ -391,26 +391,27 @@ def main() -> int:
         pad = (24576 if w.H >= 8 else 0) if C == 64 else 40000
         stream = torch.cuda.current_stream().cuda_stream or None
 
-        def move(i):
+        def move(i, kind):
             K, _, _, T = sets[i % len(sets)]
-            rc = P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, w.H, C, pad, stream)
+            rc = P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, w.H, C, pad, kind, stream)
             assert rc == 0, rc
 
-        for i in range(args.warmup):
-            move(i)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(args.steps):
-            move(i)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
         moved = C * 256 + 4 * C * C            # key rows in, fp32 matrix out (beta / g are not read)
-        out["mover"] = {"what": "same key-load and result-store pattern as the fused kernel, no arithmetic", "kernel_ms_avg": ms,
-                        "bytes_per_matrix": moved, "GBps": moved * n_mat / (ms * 1e-3) / 1e9,
-                        "hbm_frac": moved * n_mat / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                        "fused_kernel_over_mover_time": avg_kernel_ms / ms}
+        out["mover"] = {"what": "same key-load and result-store pattern as the fused kernel, no arithmetic", "bytes_per_matrix": moved}
+        for kind, name in ((0, "buffer_stores"), (1, "global_stores")):
+            for i in range(args.warmup):
+                move(i, kind)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.steps):
+                move(i, kind)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            out["mover"][name] = {"kernel_ms_avg": ms, "GBps": moved * n_mat / (ms * 1e-3) / 1e9,
+                                  "hbm_frac": moved * n_mat / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                  "fused_kernel_over_mover_time": avg_kernel_ms / ms}
 
     if args.vendor_ref:
         # context only: the vendor libraries' batched triangular solve against the identity, fp32, on the same chunk

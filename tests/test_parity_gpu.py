@@ -1114,19 +1114,21 @@ def test_probe_mover_moves_what_it_says(C, H):
     import ctypes
     from paper_2605_21325_amd import build as tri_build
     P = ctypes.CDLL(tri_build.PROBE_LIB)
-    P.triinv_probe_mover.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_uint, ctypes.c_void_p]
+    P.triinv_probe_mover.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_uint, ctypes.c_int,
+                                     ctypes.c_void_p]
     P.triinv_probe_mover.restype = ctypes.c_int
     n_chunk = 11
     K = torch.randint(-30000, 30000, (n_chunk * C, H, 128), dtype=torch.int16, device=DEV)       # any 16-bit pattern
-    T = torch.full((n_chunk * H, C, C), -1.0, device=DEV)
-    assert P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, H, C, 0, None) == 0
-    torch.cuda.synchronize()
-    out = T.view(torch.int16).view(n_chunk, H, -1, 64, 8).cpu()          # [chunk, head, register, lane, 8 x int16]
     Kc = K.view(n_chunk, C, H, 4, 4, 8).cpu()                             # [chunk, row, head, s, q, 8 x int16]
     nreg = C // 4
-    for k in range(nreg * (C // 64)):
-        i, s = (k % nreg) >> 2, (k % nreg) & 3
-        for q in range(4):
-            want = Kc[:, 16 * i:16 * i + 16, :, s, q].permute(0, 2, 1, 3)   # [chunk, head, n, 8]
-            assert torch.equal(out[:, :, k, 16 * q:16 * q + 16], want), (k, q)
-    assert P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, 6, 64, 0, None) == -1   # C = 64 needs H % 4 == 0
+    for kind in (0, 1):                                                   # buffer stores, global stores
+        T = torch.full((n_chunk * H, C, C), -1.0, device=DEV)
+        assert P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, H, C, 0, kind, None) == 0
+        torch.cuda.synchronize()
+        out = T.view(torch.int16).view(n_chunk, H, -1, 64, 8).cpu()      # [chunk, head, register, lane, 8 x int16]
+        for k in range(nreg * (C // 64)):
+            i, s = (k % nreg) >> 2, (k % nreg) & 3
+            for q in range(4):
+                want = Kc[:, 16 * i:16 * i + 16, :, s, q].permute(0, 2, 1, 3)   # [chunk, head, n, 8]
+                assert torch.equal(out[:, :, k, 16 * q:16 * q + 16], want), (kind, k, q)
+    assert P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, 6, 64, 0, 0, None) == -1   # C = 64 needs H % 4 == 0
