@@ -56,8 +56,8 @@ typedef enum {
     TRIINV_BLOCK_DIRECT = 4,
     /* Newton-Schulz iteration (paper Alg. 3, Eq. 8): X <- I / C, then n times Y <- (I + A) X,
      * X <- 2X - XY.  n = TRIINV_FLAG_ITERS(n) in flags, default 12 (the count the paper finds
-     * sufficient at C = 64; 2 log2 C elsewhere).  At C = 128 not built for the per-channel gate
-     * and for fp32 keys with d_k = 128. */
+     * sufficient at C = 64; 2 log2 C elsewhere).  At C = 128 with the per-channel gate or with fp32 keys of
+     * d_k = 128 it runs as the two-launch path described at gdn_chunk_tri_inv (fp32 T only). */
     TRIINV_NEWTON_SCHULZ = 5,
     /* Mixed recursion with b0 = 32 (the other block size the paper proposes, Sec. 3.4): Neumann product
      * (four squarings) and r refinement steps on the 32 x 32 diagonal blocks, blocked recursion from block
@@ -143,9 +143,12 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
  *   (paper Sec. 1: chunks of "at most" C tokens) and is treated as padded with tokens whose key and
  *   beta are zero, so its matrix still is C x C, with identity rows and columns for the padding;
  *   nothing is read beyond token Tlen - 1 of a sequence.  d_k: a multiple of 32, <= 256.
- *   d_k = 64 and 128 have specialised kernels for every method; other values run a channel loop and
- *   are built for TRIINV_FWD_SUBST, TRIINV_BLOCK_RECURSIVE and TRIINV_BLOCK_DIRECT (and for every
- *   method with the per-channel gate); anything else returns TRIINV_ERR_UNSUPPORTED.
+ *   d_k = 64 and 128 have specialised kernels for every method; other values run a channel loop
+ *   with fused kernels for TRIINV_FWD_SUBST, TRIINV_BLOCK_RECURSIVE and TRIINV_BLOCK_DIRECT (and for
+ *   every method with the per-channel gate).  A matrix-product method without a fused kernel for the
+ *   gate kind / d_k / C asked for runs as two launches on the same stream -- the chunk matrices written
+ *   into T as fp32, then inverted in place by the method's tri_inv kernel -- with the same result;
+ *   that path needs an fp32 T and does not take TRIINV_FLAG_REFINE1 (TRIINV_ERR_UNSUPPORTED).
  * Short form: k_dtype = BF16, scalar gate, method = TRIINV_BLOCK_RECURSIVE, op_dtype = BF16,
  * default stream, flags 0.
  */

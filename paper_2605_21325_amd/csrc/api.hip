@@ -52,20 +52,50 @@ int finish(int not_built)
     return hipGetLastError() == hipSuccess ? TRIINV_OK : TRIINV_ERR_LAUNCH;
 }
 
-// Shared tail of the fused entry points: everything but the token layout has been validated.
-int launch_fused(const GdnArgs& a, int C, int op_dtype)
+int pick_fused(const GdnArgs& a, int C, int op_dtype)
 {
-    int nb = 1;
 #define TRIINV_PICK_OP(NBV, SUFFIX) \
     (op_dtype == TRIINV_F32 ? launch_gdn_nb##NBV##_op0##SUFFIX(a) : op_dtype == TRIINV_F16 ? launch_gdn_nb##NBV##_op1##SUFFIX(a) : launch_gdn_nb##NBV##_op2##SUFFIX(a))
-    if (a.method == TRIINV_FWD_SUBST && a.refine) {
-        nb = 1;
-    } else if (a.method == TRIINV_FWD_SUBST) {
-        nb = C == 16 ? TRIINV_PICK_OP(1, _fwd) : C == 32 ? TRIINV_PICK_OP(2, _fwd) : C == 64 ? TRIINV_PICK_OP(4, _fwd) : TRIINV_PICK_OP(8, _fwd);
-    } else {
-        nb = C == 16 ? TRIINV_PICK_OP(1, ) : C == 32 ? TRIINV_PICK_OP(2, ) : C == 64 ? TRIINV_PICK_OP(4, ) : TRIINV_PICK_OP(8, );
-    }
+    if (a.method == TRIINV_FWD_SUBST && a.refine) return 1;
+    if (a.method == TRIINV_FWD_SUBST)
+        return C == 16 ? TRIINV_PICK_OP(1, _fwd) : C == 32 ? TRIINV_PICK_OP(2, _fwd) : C == 64 ? TRIINV_PICK_OP(4, _fwd) : TRIINV_PICK_OP(8, _fwd);
+    return C == 16 ? TRIINV_PICK_OP(1, ) : C == 32 ? TRIINV_PICK_OP(2, ) : C == 64 ? TRIINV_PICK_OP(4, ) : TRIINV_PICK_OP(8, );
 #undef TRIINV_PICK_OP
+}
+
+int pick_tri_inv(const TriInvArgs& a, int C, int op_dtype)
+{
+#define TRIINV_PICK_OP(NBV) \
+    (op_dtype == TRIINV_F32 ? launch_tri_inv_nb##NBV##_op0(a) : op_dtype == TRIINV_F16 ? launch_tri_inv_nb##NBV##_op1(a) : launch_tri_inv_nb##NBV##_op2(a))
+    if (a.method == TRIINV_FWD_SUBST)
+        return a.refine ? 1
+               : C == 16 ? launch_tri_inv_nb1_op0_fwd(a)
+               : C == 32 ? launch_tri_inv_nb2_op0_fwd(a)
+               : C == 64 ? launch_tri_inv_nb4_op0_fwd(a)
+                         : launch_tri_inv_nb8_op0_fwd(a);
+    return C == 16 ? TRIINV_PICK_OP(1) : C == 32 ? TRIINV_PICK_OP(2) : C == 64 ? TRIINV_PICK_OP(4) : TRIINV_PICK_OP(8);
+#undef TRIINV_PICK_OP
+}
+
+// Shared tail of the fused entry points: everything but the token layout has been validated.
+// A matrix-product method that has no fused kernel for this gate kind / head dimension / chunk size runs as two
+// launches instead: the chunk matrices are written into T as fp32 (the build kernel every combination has), then the
+// standalone kernel of the method inverts them in place.  In place is safe for those kernels: a wavefront stores rows of
+// T only after it has fetched every tile of A in those rows (each stored row depends on all of them), and in the
+// four-wavefront C = 128 kernels a wavefront fetches, before the first barrier, exactly the tile rows it later stores.
+// The values of A are the fp32 tiles a fused kernel would hold in registers, so the result is the same.  Forward
+// substitution (always fused), the refinement flag (needs A and T side by side) and a 16-bit result (T must hold an
+// fp32 A) are not composed.
+int launch_fused(const GdnArgs& a, int C, int op_dtype)
+{
+    int nb = pick_fused(a, C, op_dtype);
+    if (nb == 1 && !a.refine && a.out_dt == TRIINV_F32 && a.method != TRIINV_FWD_SUBST && a.method != 100 /* M_BUILD_A */) {
+        GdnArgs b = a;
+        b.method = 100;
+        if (pick_fused(b, C, a.gate == TRIINV_GATE_PER_CHANNEL ? op_dtype : TRIINV_F32) != 0) return TRIINV_ERR_UNSUPPORTED;
+        const TriInvArgs t{a.T, a.T, a.n_mat, TRIINV_F32, a.method, a.stream, false, a.iters, TRIINV_F32, false};
+        nb = pick_tri_inv(t, C, op_dtype);
+    }
     return finish(nb);
 }
 
@@ -169,25 +199,7 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0,
                  method_count(method, flags, C), out_dt, (flags & TRIINV_FLAG_FWD_SHUFFLE) != 0};
     if (a.shuffle && method != TRIINV_FWD_SUBST) return TRIINV_ERR_UNSUPPORTED;
-    int nb = 1;
-#define TRIINV_PICK_OP(PREFIX, NBV, ARG) \
-    (op_dtype == TRIINV_F32 ? PREFIX##NBV##_op0(ARG) : op_dtype == TRIINV_F16 ? PREFIX##NBV##_op1(ARG) : PREFIX##NBV##_op2(ARG))
-    if (method == TRIINV_FWD_SUBST) {
-        nb = a.refine ? 1
-             : C == 16 ? launch_tri_inv_nb1_op0_fwd(a)
-             : C == 32 ? launch_tri_inv_nb2_op0_fwd(a)
-             : C == 64 ? launch_tri_inv_nb4_op0_fwd(a)
-                       : launch_tri_inv_nb8_op0_fwd(a);
-    } else if (C == 16) {
-        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 1, a);
-    } else if (C == 32) {
-        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 2, a);
-    } else if (C == 64) {
-        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 4, a);
-    } else {
-        nb = TRIINV_PICK_OP(launch_tri_inv_nb, 8, a);
-    }
-#undef TRIINV_PICK_OP
+    const int nb = pick_tri_inv(a, C, op_dtype);
     return finish(nb);
 }
 

@@ -400,29 +400,31 @@ def test_newton_schulz_iteration_count(cases):
 def test_unbuilt_combinations_report_unsupported(cases):
     c = cases[1]
     w, inp = c["w"], c["inp"]
-    # head dimensions other than 64 / 128 are built for three methods only
+    # head dimensions other than 64 / 128: the composed path needs an fp32 result and cannot take the refinement flag
     K96 = torch.zeros(1, 64, 2, 96, dtype=torch.bfloat16, device=DEV)
     b = torch.zeros(1, 64, 2, device=DEV)
-    with pytest.raises(tri.TriInvError) as e:
-        tri.gdn_chunk_tri_inv_ex(K96, b, b, 64, method=tri.MIXED)
-    assert e.value.status == -9
+    for kw in (dict(out_dtype=torch.bfloat16), dict(flags=tri.FLAG_REFINE1)):
+        with pytest.raises(tri.TriInvError) as e:
+            tri.gdn_chunk_tri_inv_ex(K96, b, b, 64, method=tri.MIXED, **kw)
+        assert e.value.status == -9
     for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=0x80), dict(method=tri.BLOCK_RECURSIVE, flags=8), dict(method=tri.FWD_SUBST, flags=1), dict(method=tri.NEUMANN, flags=1)):
         with pytest.raises(tri.TriInvError) as e:
             tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), op_dtype=tri.F32, **kw)
         assert e.value.status == -9
-    with pytest.raises(tri.TriInvError) as e:   # Newton-Schulz with the per-channel gate is not built at C = 128
+    with pytest.raises(tri.TriInvError) as e:   # Newton-Schulz with the per-channel gate at C = 128 is composed: fp32 result only
         tri.gdn_chunk_tri_inv_ex(torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV), torch.zeros(1, 128, 2, device=DEV),
                                  torch.zeros(1, 128, 2, 128, device=DEV), 128, gate_kind=tri.GATE_PER_CHANNEL,
-                                 method=tri.NEWTON_SCHULZ)
+                                 method=tri.NEWTON_SCHULZ, out_dtype=torch.float16)
     assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:   # refinement at C = 128 is a second pass over an fp32 result
         tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.MIXED, op_dtype=tri.F32, flags=1, out_dtype=torch.bfloat16)
     assert e.value.status == -9
-    # per-channel gate + Neumann product at C = 128 is not built
+    # per-channel gate + refinement step at C = 128 is not built (the second pass needs A and T side by side)
     K = torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV)
     g4 = torch.zeros(1, 128, 2, 128, device=DEV)
     with pytest.raises(tri.TriInvError) as e:
-        tri.gdn_chunk_tri_inv_ex(K, torch.zeros(1, 128, 2, device=DEV), g4, 128, gate_kind=tri.GATE_PER_CHANNEL, method=tri.NEUMANN)
+        tri.gdn_chunk_tri_inv_ex(K, torch.zeros(1, 128, 2, device=DEV), g4, 128, gate_kind=tri.GATE_PER_CHANNEL, method=tri.MIXED,
+                                 flags=tri.FLAG_REFINE1)
     assert e.value.status == -9
 
 
@@ -558,8 +560,6 @@ RAGGED_METHODS = [(tri.FWD_SUBST, tri.F32), (tri.BLOCK_RECURSIVE, tri.BF16), (tr
 @pytest.mark.parametrize("C,Tlen", [(64, 1), (64, 63), (64, 65), (64, 200), (128, 127), (128, 300)])
 def test_sequence_lengths_that_are_not_multiples_of_the_chunk(C, Tlen, gate_kind, mo):
     method, op = mo
-    if C == 128 and method == tri.NEUMANN and gate_kind == 1:
-        pytest.skip("not built: Neumann with the per-channel gate at C = 128")
     idx = {0: 1, 1: 3, 2: 4}[gate_kind]
     inp = si.make_inputs(si.workload(idx, B=2, Tlen=Tlen, H=3, C=C, d_k=128, k_dtype="bf16"))
     T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)
@@ -1132,3 +1132,36 @@ def test_probe_mover_moves_what_it_says(C, H):
                 want = Kc[:, 16 * i:16 * i + 16, :, s, q].permute(0, 2, 1, 3)   # [chunk, head, n, 8]
                 assert torch.equal(out[:, :, k, 16 * q:16 * q + 16], want), (kind, k, q)
     assert P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, 6, 64, 0, 0, None) == -1   # C = 64 needs H % 4 == 0
+
+
+# ------------------------------------------------------------------ combinations without a fused kernel: build A, invert in place
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("case", ["kda_c128_neumann", "kda_c128_ns", "f32keys_c128_neumann", "f32keys_c128_ns", "dk96_mixed", "dk96_ns",
+                                  "dk256_c128_neumann", "dk32_c32_mixed_b32"])
+def test_composed_combinations_match_oracle(case, op):
+    """Method / gate / head-dimension combinations that have no fused kernel run as gdn_chunk_build_A into T followed by the
+    standalone kernel in place; the result must be what tri_inv_ex gives on that A, bit for bit, and match the oracle."""
+    idx, kw, method = {
+        "kda_c128_neumann": (3, dict(B=1, Tlen=300, H=3, C=128), tri.NEUMANN),
+        "kda_c128_ns": (3, dict(B=1, Tlen=256, H=3, C=128), tri.NEWTON_SCHULZ),
+        "f32keys_c128_neumann": (1, dict(B=1, Tlen=256, H=3, C=128, k_dtype="f32"), tri.NEUMANN),
+        "f32keys_c128_ns": (1, dict(B=1, Tlen=200, H=3, C=128, k_dtype="f32"), tri.NEWTON_SCHULZ),
+        "dk96_mixed": (1, dict(B=2, Tlen=200, H=3, d_k=96), tri.MIXED),
+        "dk96_ns": (1, dict(B=2, Tlen=128, H=3, d_k=96), tri.NEWTON_SCHULZ),
+        "dk256_c128_neumann": (1, dict(B=1, Tlen=256, H=2, d_k=256, C=128), tri.NEUMANN),
+        "dk32_c32_mixed_b32": (1, dict(B=2, Tlen=100, H=3, d_k=32, C=32), tri.MIXED_B32),
+    }[case]
+    w = si.workload(idx, **kw)
+    inp = si.make_inputs(w)
+    K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    n_mat = w.B * ((w.Tlen + w.C - 1) // w.C) * w.H
+    guard = torch.full((n_mat + 1, w.C, w.C), 7.0, device=DEV)
+    T = tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, T=guard[:n_mat], gate_kind=w.gate_kind, method=method, op_dtype=op)
+    A = tri.gdn_chunk_build_A(K, beta, g, w.C, gate_kind=w.gate_kind, op_dtype=op)
+    E = tri.tri_inv_ex(A, method=method, op_dtype=op)
+    torch.cuda.synchronize()
+    assert torch.equal(T, E)
+    assert bool((guard[n_mat] == 7.0).all())
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
+    check(T, T_ref, TOL[op], f"composed {case} {tri.DTYPE_NAMES[op]}")
