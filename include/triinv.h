@@ -228,9 +228,9 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
  *              call (rows of a short last chunk's padding do not exist and are not written).  Must
  *              not overlap X.  Caller-owned.
  *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
- *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R); d_k = 64 or 128 for the
- *              scalar / no-gate kinds (not fp32 keys with d_k = 128 at C = 128); the per-channel gate at
- *              C <= 64 only, with any supported d_k.
+ *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R).  C = 128 takes the scalar /
+ *              no-gate kinds with d_k = 64 or 128 only (not fp32 keys with d_k = 128); C <= 64 takes every
+ *              gate kind and every supported d_k.
  *              Anything else returns TRIINV_ERR_UNSUPPORTED.
  *   flags      TRIINV_FLAG_MXR_R only.
  * Accuracy: that of the method's inverse (see tri_inv_ex) plus one rounding of the scaled inverse

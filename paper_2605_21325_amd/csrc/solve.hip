@@ -71,6 +71,29 @@ template <int METHOD> static int go_kda(const SolveArgs& a)
     return 1;
 }
 
+#if TRIINV_INST_NB <= 4
+// Head dimensions other than 64 / 128 (scalar / no-gate kinds), C <= 64.
+template <int KD, int METHOD> static int go_any_dk(const SolveArgs& a)
+{
+    const GdnArgs& f = a.f;
+    const dim3 grid((unsigned)f.n_mat), block(64);
+    if (a.n_rhs == 1)
+        hipLaunchKernelGGL((k_gdn_any_dk_tri_solve<KD, OP, NB, METHOD, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+                           f.map, f.H, f.d_k, f.iters);
+    else
+        hipLaunchKernelGGL((k_gdn_any_dk_tri_solve<KD, OP, NB, METHOD, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+                           f.map, f.H, f.d_k, f.iters);
+    return 0;
+}
+
+template <int KD> static int any_dk_method(const SolveArgs& a)
+{
+    if (a.f.method == M_BLOCK) return go_any_dk<KD, M_BLOCK>(a);
+    if (a.f.method == M_MIXED) return go_any_dk<KD, M_MIXED>(a);
+    return 1;
+}
+#endif
+
 int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a)
 {
     const GdnArgs& f = a.f;
@@ -97,7 +120,11 @@ int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a
         if (f.d_k == 64) return gdn_method<OP_F16, 2>(a);
         if (f.d_k == 128) return gdn_method<OP_F16, 4>(a);
     }
+#if TRIINV_INST_NB <= 4
+    return f.k_dt == OP_F32 ? any_dk_method<OP_F32>(a) : f.k_dt == OP_BF16 ? any_dk_method<OP_BF16>(a) : any_dk_method<OP_F16>(a);
+#else
     return 1;
+#endif
 }
 
 }  // namespace triinv

@@ -305,4 +305,35 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_solve(const void* __restri
     invert_and_apply<OP, NB, METHOD, NB, false, NRHS>(src, x, lds, ln, aux, next_rhs);
 }
 
+// Scalar / no-gate kinds for head dimensions without a specialised build (any multiple of 32): the channel-loop Gram of
+// the storing kernel, then the same recursion and products.  One wavefront per workgroup.
+template <int KD, int OP, int NB, int METHOD, int NRHS>
+__global__ __launch_bounds__(64) void k_gdn_any_dk_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
+                                                             const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
+                                                             int H, int d_k, int aux)
+{
+    constexpr int C = 16 * NB;
+    constexpr int CORE = core_lds_floats<NB, METHOD, true>();
+    constexpr int GATE = gate_lds_floats<NB>();
+    __shared__ __attribute__((aligned(16))) float lds[CORE > GATE ? CORE : GATE];
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
+    const Lane ln = lane_id();
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    PreA<NB> src;
+    build_A_scalar_any_dk<KD, NB, METHOD>(src, static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k,
+                                          beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, d_k, lds, ln, pos.valid);
+    RhsX<OP, NB> x;
+    x.init(rhs.r[0], tok0, h, H, pos.valid, ln);
+    auto next_rhs = [&](int k) {
+        x.init(rhs.r[k < MAX_RHS ? k : 0], tok0, h, H, pos.valid, ln);
+        x.issue(0);
+    };
+    x.issue(0);
+    invert_and_apply<OP, NB, METHOD, NB, false, NRHS>(src, x, lds, ln, aux, next_rhs);
+}
+
 }  // namespace triinv

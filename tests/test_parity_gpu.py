@@ -1165,3 +1165,31 @@ def test_composed_combinations_match_oracle(case, op):
     assert bool((guard[n_mat] == 7.0).all())
     T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
     check(T, T_ref, TOL[op], f"composed {case} {tri.DTYPE_NAMES[op]}")
+
+
+@pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("d_k,C,Tlen", [(32, 16, 50), (96, 64, 200), (256, 64, 128), (192, 32, 96)])
+def test_solve_other_head_dimensions(d_k, C, Tlen, op):
+    # scalar and no-gate kinds with a d_k that has no specialised build: the channel-loop Gram, one and two right-hand sides
+    for idx in (1, 4):
+        w = si.workload(idx, B=2, Tlen=Tlen, H=3, d_k=d_k, C=C, k_dtype="bf16" if op != tri.F32 else "f32")
+        inp = si.make_inputs(w)
+        r1, r2 = si.make_rhs(w, 64, XDT[op]), si.make_rhs(w, 136, XDT[op], seed_offset=1)
+        K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
+        g = None if inp["g"] is None else inp["g"].to(DEV)
+        for method in (tri.BLOCK_RECURSIVE, tri.MIXED):
+            W = tri.gdn_chunk_tri_solve(K, beta, g, r1["X"].to(DEV), C, row_scale=r1["row_scale"].to(DEV), gate_kind=w.gate_kind,
+                                        method=method)
+            W1, W2 = tri.gdn_chunk_tri_solve_multi(K, beta, g, [r1["X"].to(DEV), r2["X"].to(DEV)], C,
+                                                   row_scales=[r1["row_scale"].to(DEV), None], gate_kind=w.gate_kind, method=method)
+            torch.cuda.synchronize()
+            assert torch.equal(W, W1)
+            check_solve(W, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], r1["row_scale"], w.gate_kind, C),
+                        SOLVE_TOL[op], f"d_k={d_k} C={C} cfg{idx} rhs 0")
+            check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], None, w.gate_kind, C),
+                        SOLVE_TOL[op], f"d_k={d_k} C={C} cfg{idx} rhs 1")
+    with pytest.raises(tri.TriInvError) as e:                               # C = 128 keeps to d_k = 64 / 128
+        w = si.workload(1, B=1, Tlen=128, H=2, d_k=96, C=128)
+        inp = si.make_inputs(w)
+        tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), si.make_rhs(w, 64)["X"].to(DEV), 128)
+    assert e.value.status == -9
