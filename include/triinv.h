@@ -61,7 +61,7 @@ typedef enum {
     TRIINV_NEWTON_SCHULZ = 5,
     /* Mixed recursion with b0 = 32 (the other block size the paper proposes, Sec. 3.4): Neumann product
      * (four squarings) and r refinement steps on the 32 x 32 diagonal blocks, blocked recursion from block
-     * size 32.  C >= 32.  TRIINV_FLAG_REFINE1 is not built for it. */
+     * size 32.  C >= 32. */
     TRIINV_MIXED_B32 = 6
 } triinv_method;
 
@@ -88,10 +88,10 @@ typedef enum {
 
 /* Bits of `flags` (0 = none). */
 #define TRIINV_FLAG_REFINE1 0x1u /* one iterative-refinement step X <- X + (I - X(I+A))X on the whole matrix after the
-                                    method (paper Alg. 6, Eq. 9).  Built for TRIINV_BLOCK_RECURSIVE and TRIINV_MIXED
-                                    (tri_inv and every fused gate kind at C <= 64); at C = 128 it runs as a second
-                                    kernel over T, in place, for an fp32 result and the scalar / no-gate kinds only.
-                                    Anything else returns TRIINV_ERR_UNSUPPORTED */
+                                    method (paper Alg. 6, Eq. 9).  Built for every matrix-product method (all but
+                                    TRIINV_FWD_SUBST): inside the method's kernel at C <= 64 (tri_inv and every fused
+                                    gate kind); at C = 128 as a second kernel over T, in place, for an fp32 result and
+                                    the scalar / no-gate kinds only.  Anything else returns TRIINV_ERR_UNSUPPORTED */
 #define TRIINV_FLAG_OUT_F16 0x2u  /* T holds fp16 elements: [n_mat][C][C], 2 bytes each (pass the buffer as float*) */
 #define TRIINV_FLAG_OUT_BF16 0x4u /* T holds bf16 elements.  The fp32 result is rounded to nearest even on the way
                                      out; the diagonal is still exactly 1, the upper triangle exactly 0.  Not

@@ -43,13 +43,24 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 {
     if (a.refine) {
         if constexpr (HAS_REFINE) {
-            if (a.method == M_BLOCK) return go_tri<M_BLOCK, true>(a);
-            if (a.method == M_MIXED) return go_tri<M_MIXED, true>(a);
+            switch (a.method) {
+            case M_BLOCK: return go_tri<M_BLOCK, true>(a);
+            case M_MIXED: return go_tri<M_MIXED, true>(a);
+            case M_BLOCK_DIRECT: return go_tri<M_BLOCK_DIRECT, true>(a);
+            case M_NEUMANN: return go_tri<M_NEUMANN, true>(a);
+            case M_NEWTON_SCHULZ: return go_tri<M_NEWTON_SCHULZ, true>(a);
+#if TRIINV_INST_NB >= 2 && TRIINV_INST_NB <= 4
+            case M_MIXED32: return go_tri<M_MIXED32, true>(a);
+#endif
+            default: return 1;
+            }
         }
 #if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
         // C = 128: the method as usual, then the refinement step as a second pass over T, in place (fp32 result only)
-        if ((a.method == M_BLOCK || a.method == M_MIXED) && a.out_dt == OP_F32) {
-            if (a.method == M_BLOCK) go_tri<M_BLOCK>(a); else go_tri<M_MIXED>(a);
+        if (a.out_dt == OP_F32) {
+            TriInvArgs first = a;
+            first.refine = false;
+            if (CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(first) != 0) return 1;
             hipLaunchKernelGGL((k_tri_inv_refine128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
             return 0;
         }
@@ -120,13 +131,24 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 {
     if (a.refine) {
         if constexpr (HAS_REFINE) {
-            if (a.method == M_BLOCK) return go_gdn<KD, M_BLOCK, DKS, true>(a);
-            if (a.method == M_MIXED) return go_gdn<KD, M_MIXED, DKS, true>(a);
+            switch (a.method) {
+            case M_BLOCK: return go_gdn<KD, M_BLOCK, DKS, true>(a);
+            case M_MIXED: return go_gdn<KD, M_MIXED, DKS, true>(a);
+            case M_BLOCK_DIRECT: return go_gdn<KD, M_BLOCK_DIRECT, DKS, true>(a);
+            case M_NEUMANN: return go_gdn<KD, M_NEUMANN, DKS, true>(a);
+            case M_NEWTON_SCHULZ: return go_gdn<KD, M_NEWTON_SCHULZ, DKS, true>(a);
+#if TRIINV_INST_NB >= 2 && TRIINV_INST_NB <= 4
+            case M_MIXED32: return go_gdn<KD, M_MIXED32, DKS, true>(a);
+#endif
+            default: return 1;
+            }
         }
 #if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
         if constexpr (!(KD == OP_F32 && DKS == 8)) {  // (128 fp32 channels x 128 rows of keys per wave do not fit the register file)
-            if ((a.method == M_BLOCK || a.method == M_MIXED) && a.out_dt == OP_F32) {
-                if (a.method == M_BLOCK) go_gdn<KD, M_BLOCK, DKS>(a); else go_gdn<KD, M_MIXED, DKS>(a);
+            if (a.out_dt == OP_F32) {
+                GdnArgs first = a;
+                first.refine = false;
+                if (gdn_method<KD, DKS>(first) != 0) return 1;
                 hipLaunchKernelGGL((k_gdn_tri_inv_refine128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
                                    a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
                 return 0;
@@ -186,8 +208,17 @@ static int kda_method(const GdnArgs& a)
 {
     if (a.refine) {
         if constexpr (HAS_REFINE) {
-            if (a.method == M_BLOCK) return go_kda<M_BLOCK, true>(a);
-            if (a.method == M_MIXED) return go_kda<M_MIXED, true>(a);
+            switch (a.method) {
+            case M_BLOCK: return go_kda<M_BLOCK, true>(a);
+            case M_MIXED: return go_kda<M_MIXED, true>(a);
+            case M_BLOCK_DIRECT: return go_kda<M_BLOCK_DIRECT, true>(a);
+            case M_NEUMANN: return go_kda<M_NEUMANN, true>(a);
+            case M_NEWTON_SCHULZ: return go_kda<M_NEWTON_SCHULZ, true>(a);
+#if TRIINV_INST_NB >= 2 && TRIINV_INST_NB <= 4
+            case M_MIXED32: return go_kda<M_MIXED32, true>(a);
+#endif
+            default: return 1;
+            }
         }
         return 1;
     }

@@ -848,10 +848,12 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, Out Tm, float*
     } else if (METHOD == M_NEWTON_SCHULZ) {
         v4f Xt[NT];
         newton_schulz<OP, NB>(src, Xt, aux, ln);  // aux = number of iterations
+        if constexpr (REFINE) refine_once<OP, NB>(src, Xt, [](int, int) { return true; }, lds, ln);
         store_result<NB>(Tm, Xt, [](int, int) { return true; }, lds, ln);
     } else if (METHOD == M_NEUMANN) {
         v4f Xt[NT];
         neumann<OP, NB>(src, Xt, ln);
+        if constexpr (REFINE) refine_once<OP, NB>(src, Xt, [](int, int) { return true; }, lds, ln);
         store_result<NB>(Tm, Xt, [](int, int) { return true; }, lds, ln);
     } else {
         v4f Tt[NT];
