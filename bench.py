@@ -185,7 +185,7 @@ def main() -> int:
                 if method == 0 and op != 0:
                     continue
                 for flags, tag in ((0, ""), (tri.FLAG_REFINE1, "+refine")):
-                    if flags and method not in (1, 3):
+                    if flags and method == 0:
                         continue
                     row = {"method": tri.METHOD_NAMES[method] + tag, "op": tri.DTYPE_NAMES[op]}
                     try:
