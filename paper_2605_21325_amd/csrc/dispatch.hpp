@@ -49,6 +49,9 @@ struct SolveArgs {
     int d_x[2];
 };
 
+// The chunk stride of the few-heads workgroup map of the fused kernels (0 = the many-heads map): see fused_matrix_index.
+inline int head_spread(int H) { return H >= 8 ? 0 : (H >= 4 ? 1 : 4 / H); }
+
 // Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.
 #define TRIINV_DECL(NB, OP)                                  \
     int launch_tri_inv_nb##NB##_op##OP(const TriInvArgs& a); \

@@ -110,20 +110,17 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 // Unused dynamic LDS that keeps a compute unit (160 KB of LDS) at two workgroups = two wavefronts per
 // SIMD for the 16-bit-operand recursions at C = 64.  Those kernels are bound by the memory system,
 // not by latency: with more wavefronts resident they measured 2-4 % slower (more requests queued at
-// the memory controllers, none served sooner).  That holds for H >= 8; with fewer heads (key rows less
-// than 2 KB apart) memory latency measured ~10 % higher and the third wavefront per SIMD gains 4-5 %.
-template <int METHOD> unsigned occupancy_pad_bytes(int H)
+// the memory controllers, none served sooner).
+template <int METHOD> constexpr unsigned occupancy_pad_bytes()
 {
-    constexpr bool padded = NB == 4 && WPB == 4 && OP != OP_F32 &&
-                            (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT);
-    return (padded && H >= 8) ? 24576u : 0u;
+    return (NB == 4 && WPB == 4 && OP != OP_F32 && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT)) ? 24576u : 0u;
 }
 
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
-                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(a.H), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
-                       a.iters, a.out_dt);
+                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
+                       a.iters, a.out_dt, WPB > 1 ? head_spread(a.H) : 0);
     return 0;
 }
 
@@ -200,7 +197,8 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 template <int METHOD, bool REFINE = false> static int go_kda(const GdnArgs& a)
 {
     hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB, REFINE>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
-                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt);
+                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt,
+                       WPB > 1 ? head_spread(a.H) : 0);
     return 0;
 }
 

@@ -36,12 +36,12 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {
         hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g,
-                           rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+                           rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters, WPB > 1 ? head_spread(f.H) : 0);
         return 0;
     }
     if constexpr (HAS_PAIR) {
         hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g,
-                           rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+                           rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters, WPB > 1 ? head_spread(f.H) : 0);
         return 0;
     }
     return 1;
@@ -60,12 +60,12 @@ template <int METHOD> static int go_kda(const SolveArgs& a)
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {
         hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
-                           f.map, f.H, f.d_k, f.k_dt, f.iters);
+                           f.map, f.H, f.d_k, f.k_dt, f.iters, WPB > 1 ? head_spread(f.H) : 0);
         return 0;
     }
     if constexpr (HAS_PAIR) {
         hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
-                           f.map, f.H, f.d_k, f.k_dt, f.iters);
+                           f.map, f.H, f.d_k, f.k_dt, f.iters, WPB > 1 ? head_spread(f.H) : 0);
         return 0;
     }
     return 1;

@@ -221,7 +221,7 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
 template <int KD, int OP, int NB, int METHOD, int DKS, int WPB, int XPOS, int NRHS>
 __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
                                                             const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
-                                                            int H, int d_k, int aux)
+                                                            int H, int d_k, int aux, int spread)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
     constexpr int PER_WAVE = CORE > GATE ? CORE : GATE;
     __shared__ __attribute__((aligned(16))) float lds_all[WPB * PER_WAVE];
     float* lds = lds_all + ((WPB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * PER_WAVE;
-    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H);  // chunk id * H + h
+    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H, spread);  // chunk id * H + h
     if (m < 0) return;
     const uint32_t bc = (uint32_t)m / (uint32_t)H;
     const int h = (int)((uint32_t)m - bc * (uint32_t)H);
@@ -276,14 +276,14 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
 template <int OP, int NB, int METHOD, int WPB, int NRHS>
 __global__ __launch_bounds__(64 * WPB) void k_kda_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
                                                             const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
-                                                            int H, int d_k, int k_dt, int aux)
+                                                            int H, int d_k, int k_dt, int aux, int spread)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
     constexpr int PER_WAVE = CORE > C ? CORE : C;
     __shared__ __attribute__((aligned(16))) float lds_all[WPB * PER_WAVE];
     float* lds = lds_all + ((WPB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * PER_WAVE;
-    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H);
+    const int64_t m = fused_matrix_index<WPB>(n_chunk, H, n_chunk * H, spread);
     if (m < 0) return;
     const uint32_t bc = (uint32_t)m / (uint32_t)H;
     const int h = (int)((uint32_t)m - bc * (uint32_t)H);

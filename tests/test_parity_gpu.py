@@ -1240,3 +1240,43 @@ def test_refinement_repairs_an_unconverged_newton_schulz():
     assert e8r < 0.5 * e8
     # a refinement step and a Newton-Schulz iteration both square the residual: they land in the same place
     assert e8r < 3 * e9 + 1e-6 and e9 < 3 * e8r + 1e-6, (e8, e8r, e9)
+
+
+# ------------------------------------------------------------------ few heads: the chunk-strided workgroup map and its tail
+@pytest.mark.parametrize("H", [1, 2, 3, 4, 5, 7])
+@pytest.mark.parametrize("n_chunk", [1, 3, 4, 7, 16, 19, 33])
+def test_few_heads_workgroup_map_covers_every_matrix_once(H, n_chunk):
+    """H < 8 runs the map in which a workgroup takes one head of four chunks a stride apart; chunk counts that are not a
+    multiple of the group size end in a plain-order tail.  Every matrix must be written, with the right chunk's result,
+    for the storing kernels (scalar and per-channel gate), the applied inverse and the packed-sequence layout."""
+    C, d_k = 64, 64
+    for idx in (1, 3):
+        w = si.workload(idx, B=1, Tlen=n_chunk * C - 5, H=H, C=C, d_k=d_k)
+        inp = si.make_inputs(w)
+        K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+        T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], w.gate_kind, C)
+        T = torch.full((n_chunk * H + 1, C, C), 7.0, device=DEV)
+        tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=T[:-1], gate_kind=w.gate_kind)
+        check(T[:-1], T_ref, 2e-2, f"H={H} n_chunk={n_chunk} cfg{idx}")
+        assert bool((T[-1] == 7.0).all())
+        rhs = si.make_rhs(w, 64, torch.bfloat16)
+        W = torch.full(rhs["X"].shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+        tri.gdn_chunk_tri_solve(K, beta, g, rhs["X"].to(DEV), C, W=W, gate_kind=w.gate_kind)
+        check_solve(W, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], None, w.gate_kind, C), 2e-2,
+                    f"solve H={H} n_chunk={n_chunk} cfg{idx}")
+    # packed sequences: the same tensors read as two sequences
+    w = si.workload(1, B=1, Tlen=n_chunk * C - 5, H=H, C=C, d_k=d_k)
+    inp = si.make_inputs(w)
+    total = w.Tlen
+    seqlens = [total // 3, total - total // 3]
+    g = torch.zeros(total, H)
+    gen = torch.Generator().manual_seed(3)
+    t0 = 0
+    for n in seqlens:
+        for c0 in range(0, n, C):
+            m = min(C, n - c0)
+            g[t0 + c0:t0 + c0 + m] = torch.cumsum(-0.05 * torch.rand(m, H, generator=gen), 0)
+        t0 += n
+    Kp, bp = inp["K"][0].contiguous(), inp["beta"][0].contiguous()
+    T = tri.gdn_chunk_tri_inv_varlen(Kp.to(DEV), bp.to(DEV), g.to(DEV), seqlens, C)
+    check(T, oracle.gdn_chunk_tri_inv_varlen(Kp, bp, g, seqlens, 0, C), 2e-2, f"varlen H={H} n_chunk={n_chunk}")
