@@ -148,11 +148,10 @@ template <int OP, int NB> struct RhsX {
 // right-hand sides in turn; x holds the first one, next_rhs(k) re-initialises x for right-hand side k and starts the
 // loads of its first column group.  Two right-hand sides are built at C <= 64 only, where the 10 fp32 tiles of T stay
 // in registers beside everything else.
-// ISSUE_FROM: the loads of tile rows ISSUE_FROM .. NB - 1 of X's first column group start here (the caller has
-// issued the rows before).  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
-// IN_MERGE: ... inside the recursion's last merge (as soon as its tiles of A exist: a source that holds keys in
-// registers has them free from there on, and the merge's products run while the loads are in flight); otherwise
-// after the recursion.
+// ISSUE_FROM: the caller has started the loads of tile rows 0 .. ISSUE_FROM - 1 of X's first column group; the rest
+// (none when ISSUE_FROM = NB) start here.  IN_MERGE says where: inside the recursion's last merge, as soon as its tiles
+// of A exist (a source that holds keys in registers has them free from there on, and the merge's products run while
+// the loads are in flight), or after the recursion.  lds: the transpose patch (XPOSE_FLOATS floats, wave-private).
 template <int OP, int NB, int METHOD, int ISSUE_FROM, bool IN_MERGE, int NRHS, class ASrc, class NextRhs>
 __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& x, float* lds, Lane ln, int aux, NextRhs next_rhs)
 {
@@ -216,8 +215,10 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
     }
 }
 
-// XPOS: where X's first loads are issued -- 1: between the Gram products and the recursion, 2: after the recursion,
-// 3: half before the recursion (with the keys still in registers), half after it.
+// XPOS: where the loads of X's first column group are issued -- 1: between the Gram products and the recursion (every
+// tile of A is formed first, so the keys' registers are free); 2: after the recursion; 3: as many tile rows as fit beside
+// the keys before the recursion, the rest inside its last merge or after it (see invert_and_apply).
+// spread: see fused_matrix_index.
 template <int KD, int OP, int NB, int METHOD, int DKS, int WPB, int XPOS, int NRHS>
 __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
                                                             const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
