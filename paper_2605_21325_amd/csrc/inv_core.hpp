@@ -198,6 +198,19 @@ template <class ASrc> struct PairView {
     template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const { return a.template get<TR>(P + i, P + j); }
 };
 
+// A tile of A as a packed matrix-core operand.  Sources that already hold packed tiles say so by specialising
+// PackedSource and providing operand<TR>(i, j); every other source has its fp32 tile packed here.
+template <class ASrc> struct PackedSource {
+    static constexpr bool value = false;
+};
+template <int OP, bool TR, class ASrc> __device__ __forceinline__ Opnd<OP> tile_operand(const ASrc& A, int i, int j)
+{
+    if constexpr (PackedSource<ASrc>::value)
+        return A.template operand<TR>(i, j);
+    else
+        return pack<OP>(A.template get<TR>(i, j));
+}
+
 struct NoHook {
     __device__ __forceinline__ void operator()() const {}
 };
@@ -263,8 +276,7 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
             for (int b = 0; b < h; ++b)
 #pragma unroll
                 for (int d = 0; d < h; ++d)
-                    a21[b * h + d] = blockT ? pack<OP>(A.template get<false>(mid + b, lo + d))
-                                            : pack<OP>(A.template get<true>(mid + b, lo + d));
+                    a21[b * h + d] = blockT ? tile_operand<OP, false>(A, mid + b, lo + d) : tile_operand<OP, true>(A, mid + b, lo + d);
             if (2 * h == NB) after_last_fetch();
             if (!blockT) {
                 // W = -T22 (A21 T11), N orientation

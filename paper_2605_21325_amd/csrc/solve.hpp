@@ -24,6 +24,32 @@ struct RhsArgs {
     int d_x;
 };
 
+// Tile source for the recursion with every tile of A formed up front in the form the recursion consumes it: the
+// off-diagonal tiles as packed operands in the orientation their merge asks for (half or a quarter of the registers of
+// fp32 tiles in both orientations), the diagonal tiles in fp32 in both orientations (the leaves use them first).  Filling
+// it from a source that builds tiles out of keys held in registers frees the keys before the recursion starts.
+template <int OP, int NB> struct PackedA {
+    static constexpr bool kFromMemory = false;
+    Opnd<OP> off[NB * (NB + 1) / 2];
+    v4f dn[NB], dt[NB];
+    template <bool TR> __device__ __forceinline__ v4f get(int i, int) const { return TR ? dt[i] : dn[i]; }  // diagonal tiles only
+    template <bool TR> __device__ __forceinline__ Opnd<OP> operand(int i, int j) const { return off[tix(i, j)]; }
+    template <class Src> __device__ __forceinline__ void fill(const Src& s)
+    {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+#pragma unroll
+            for (int j = 0; j < i; ++j)
+                off[tix(i, j)] = merge_block_is_T<NB>(i, j) ? pack<OP>(s.template get<false>(i, j)) : pack<OP>(s.template get<true>(i, j));
+            dn[i] = s.template get<false>(i, i);
+            dt[i] = s.template get<true>(i, i);
+        }
+    }
+};
+template <int OP, int NB> struct PackedSource<PackedA<OP, NB>> {
+    static constexpr bool value = true;
+};
+
 // NRHS right-hand sides sharing one inverse: W_k = T diag(s_k) X_k.  NRHS is a compile-time count (1 or 2) so that
 // every access to the list is a plain kernel-argument read.
 constexpr int MAX_RHS = 2;
@@ -250,15 +276,9 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restri
     };
     src.stage_gate(lds);
     if constexpr (XPOS == 1) {
-        // every tile of A first (the key registers are free afterwards), then X's loads, then the recursion
-        PreA<NB> pre;
-#pragma unroll
-        for (int i = 0; i < NB; ++i)
-#pragma unroll
-            for (int j = 0; j <= i; ++j) {
-                if (need_tile<NB, METHOD>(i, j, false)) pre.n[tix(i, j)] = src.template get<false>(i, j);
-                if (need_tile<NB, METHOD>(i, j, true)) pre.t[tix(i, j)] = src.template get<true>(i, j);
-            }
+        // every tile of A first, packed (the key registers are free afterwards), then X's loads, then the recursion
+        PackedA<OP, NB> pre;
+        pre.fill(src);
         x.issue(0);
         invert_and_apply<OP, NB, METHOD, NB, false, NRHS>(pre, x, lds, ln, aux, next_rhs);
     } else if constexpr (XPOS == 2) {
