@@ -874,9 +874,20 @@ template <int NB, int METHOD, bool FUSED = false> constexpr int core_lds_floats(
     return METHOD != M_FWD ? STORE_LDS_FLOATS : (FUSED && NB == 8) ? fwd_resident_lds_floats<NB>() : fwd_lds_floats<NB>();
 }
 
+// The matrix-product kernels may be run in place (A and T the same memory: the composed path of the fused entry points),
+// so only forward substitution, which never is, declares its two pointers non-aliasing.
+template <int METHOD> struct TriInvPointers {
+    typedef const void* in;
+    typedef float* out;
+};
+template <> struct TriInvPointers<M_FWD> {
+    typedef const void* __restrict__ in;
+    typedef float* __restrict__ out;
+};
+
 template <int OP, int NB, int METHOD, bool REFINE = false>
-__global__ __launch_bounds__(64) void k_tri_inv(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt,
-                                                int aux, int out_dt)
+__global__ __launch_bounds__(64) void k_tri_inv(typename TriInvPointers<METHOD>::in A, typename TriInvPointers<METHOD>::out T, int64_t n_mat,
+                                                int in_dt, int aux, int out_dt)
 {
     constexpr int C = 16 * NB;
     __shared__ __attribute__((aligned(16))) float lds[core_lds_floats<NB, METHOD>()];
@@ -1338,8 +1349,7 @@ __global__ __launch_bounds__(256) void k_gdn_tri_inv_refine128(const void* __res
 }
 
 template <int OP>
-__global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt,
-                                                       int n_iter, int out_dt)
+__global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* A, float* T, int64_t n_mat, int in_dt, int n_iter, int out_dt)  // may run in place
 {
     __shared__ __attribute__((aligned(16))) float XY[NS128_LDS_FLOATS];
     const int64_t m = blockIdx.x;
@@ -1378,7 +1388,7 @@ __global__ __launch_bounds__(256) void k_gdn_tri_inv_ns128(const void* __restric
 }
 
 template <int OP>
-__global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* __restrict__ A, float* __restrict__ T, int64_t n_mat, int in_dt, int out_dt)
+__global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* A, float* T, int64_t n_mat, int in_dt, int out_dt)  // may run in place
 {
     __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
     const int64_t m = blockIdx.x;
