@@ -28,9 +28,12 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 METRIC = "64x64 tri-inversions/sec + effective TFLOP/s & GB/s vs roofline; rel error"
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
-# keyed by (workload index, method, op_dtype).  None = not measured for that configuration.
-MEASURED_TRAFFIC = {(2, 1, 2): 545.4e6, (3, 1, 2): 2149.9e6, (4, 1, 2): 809.9e6}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command (the counters
+# cannot be read from inside the process): a profiled constant with the summary it was read from, keyed by
+# (workload index, method, op_dtype).  Absent = not profiled for that configuration (reported as null).
+PROFILED_TRAFFIC = {(2, 1, 2): (545.4e6, "profiles/k_gdn_tri_inv_block_bf16_workload2.txt"),
+                    (3, 1, 2): (2149.9e6, "profiles/k_kda_tri_inv_block_bf16_workload3.txt"),
+                    (4, 1, 2): (809.9e6, "profiles/k_gdn_tri_inv_block_bf16_workload4.txt")}
 
 
 def algorithmic_bytes_per_matrix(w, fused: bool, in_bytes: int = 4, out_bytes: int = 4) -> int:
@@ -61,24 +64,16 @@ def main() -> int:
     ap.add_argument("--nbuf", type=int, default=4, help="distinct buffer sets the steps rotate over")
     ap.add_argument("--table", action="store_true", help="also time every method / operand type")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--mover", action="store_true",
-                    help="also time the data mover of libtriinv_probe.so: the fused kernel's memory access pattern and nothing "
-                         "else, on the same buffers (the practical ceiling of that pattern; 16-bit keys, d_k = 128, scalar / no gate)")
-    ap.add_argument("--paper-sweep", action="store_true",
-                    help="the shape of the paper's kernel-scaling experiment (Sec. 5.1): B=32, 4 heads, C=64, sequence lengths "
-                         "1K..16K, every method, 5 warm-up + 20 timed launches with the cache cleared before each; prints its own "
-                         "JSON line and exits")
     ap.add_argument("--solve-rhs", type=int, default=1, choices=[1, 2],
                     help="with --solve: right-hand sides per launch (2 = two D_X-column tensors sharing one inversion)")
-    ap.add_argument("--vendor-ref", action="store_true",
-                    help="also time torch.linalg.solve_triangular (the ROCm libraries' batched triangular solve) on the same matrices")
     ap.add_argument("--solve", type=int, default=0, metavar="D_X",
                     help="also time gdn_chunk_tri_solve (the inverse applied to D_X right-hand-side columns instead of stored)")
     ap.add_argument("--accuracy", action="store_true",
                     help="instead of timing: error and residual of every method / operand type against the oracle on "
                          "sampled matrices of the full-size workload, fused entry point and (scalar / no gate) standalone")
     ap.add_argument("--copy-ref", action="store_true",
-                    help="also run plain device copies of 1 GiB (reference for scaling profiler byte counters)")
+                    help="also run plain device copies of 1 GiB in the same process (under rocprofv3 --pmc their FETCH_SIZE / "
+                         "WRITE_SIZE readings give the factors that scale the kernels' readings to bytes)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -100,42 +95,6 @@ def main() -> int:
         return 3
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-
-    if args.paper_sweep:
-        # Sec. 5.1's experiment on this chip: the workload recipe of configs[2] (bf16 keys, scalar gate, d_k = 128) at the
-        # paper's batch 32 x 4 heads; the cache is cleared by reading an unrelated 512 MiB buffer before every launch
-        flush = torch.empty(1 << 27, dtype=torch.float32, device=dev).normal_()
-        rows = []
-        variants = [("fwd_subst", 0, 0), ("block_recursive", 1, 2), ("mixed", 3, 2), ("mixed_b32", 6, 2), ("block_direct", 4, 2),
-                    ("neumann", 2, 2), ("newton_schulz", 5, 2)]
-        for Tlen in (1024, 2048, 4096, 8192, 16384):
-            ws = si.workload(2, B=32, Tlen=Tlen, H=4)
-            si_inp = si.make_inputs(ws)
-            K, beta, g = si_inp["K"].to(dev), si_inp["beta"].to(dev), si_inp["g"].to(dev)
-            T = torch.empty((ws.n_mat, 64, 64), device=dev)
-            A32 = tri.gdn_chunk_build_A(K, beta, g, 64, op_dtype=tri.F32)
-            for name, method, op in variants:
-                for entry in ("fused", "standalone"):
-                    ms = []
-                    for i in range(25):
-                        sink = flush.sum()
-                        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                        a.record()
-                        if entry == "fused":
-                            tri.gdn_chunk_tri_inv_ex(K, beta, g, 64, T=T, method=method, op_dtype=op)
-                        else:
-                            tri.tri_inv_ex(A32, T=T, method=method, op_dtype=op)
-                        b.record()
-                        torch.cuda.synchronize()
-                        if i >= 5:
-                            ms.append(a.elapsed_time(b))
-                    rows.append({"Tlen": Tlen, "n_mat": ws.n_mat, "method": name, "op": tri.DTYPE_NAMES[op], "entry": entry,
-                                 "us_median": float(np.median(ms)) * 1e3, "us_min": float(np.min(ms)) * 1e3,
-                                 "matrices_per_s": ws.n_mat / (float(np.median(ms)) * 1e-3)})
-            del K, beta, g, T, A32
-        print(json.dumps({"paper_sweep": rows, "protocol": "B=32, H=4, d_k=128, C=64, bf16 keys, scalar gate; per point 5 warm-up + 20 "
-                          "timed launches, a 512 MiB read before each to clear the caches, HIP events around the single launch, median"}))
-        return 0
 
     out_torch = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.out]
     out_bytes = 4 if args.out == "f32" else 2
@@ -352,6 +311,9 @@ def main() -> int:
                                   f"substitution), {dt:.3f} s wall per pass on {cores} threads",
                         "one_thread_value": n1 / dt1, "one_thread_sample": f"first {n1} matrices, {dt1:.2f} s"}
 
+    traffic = PROFILED_TRAFFIC.get((w.index, args.method, args.op)) if args.out == "f32" and not args.chunk else None
+    traffic = (traffic[0], f"profiled constant, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, {traffic[1]}") \
+        if traffic else (None, None)
     out = {
         "metric": METRIC, "value": value, "unit": "matrices/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -370,72 +332,12 @@ def main() -> int:
                       "device_copy_same_bytes_GBps": copy_gbps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((w.index, args.method, args.op)) if args.out == "f32" else None},
+                     "traffic": traffic[0], "traffic_source": traffic[1]},
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }
     if copy_ref is not None:
         out["copy_ref"] = copy_ref
-
-    if args.mover and w.k_dtype == "bf16" and w.d_k == 128 and w.gate_kind != si.GATE_PER_CHANNEL and C in (64, 128) \
-            and args.out == "f32" and (C == 128 or w.H % 4 == 0):
-        import ctypes
-        from paper_2605_21325_amd import build as tri_build
-        P = ctypes.CDLL(tri_build.PROBE_LIB)
-        P.triinv_probe_mover.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_uint,
-                                         ctypes.c_int, ctypes.c_void_p]
-        P.triinv_probe_mover.restype = ctypes.c_int
-        n_chunk = n_mat // w.H
-        # the resident-wavefront count the real kernel runs with: two workgroups of four per compute unit at C = 64 (H >= 8),
-        # four one-wavefront workgroups at C = 128
-        pad = (24576 if w.H >= 8 else 0) if C == 64 else 40000
-        stream = torch.cuda.current_stream().cuda_stream or None
-
-        def move(i, kind):
-            K, _, _, T = sets[i % len(sets)]
-            rc = P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, w.H, C, pad, kind, stream)
-            assert rc == 0, rc
-
-        moved = C * 256 + 4 * C * C            # key rows in, fp32 matrix out (beta / g are not read)
-        out["mover"] = {"what": "same key-load and result-store pattern as the fused kernel, no arithmetic", "bytes_per_matrix": moved}
-        for kind, name in ((0, "buffer_stores"), (1, "global_stores")):
-            for i in range(args.warmup):
-                move(i, kind)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for i in range(args.steps):
-                move(i, kind)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / args.steps
-            out["mover"][name] = {"kernel_ms_avg": ms, "GBps": moved * n_mat / (ms * 1e-3) / 1e9,
-                                  "hbm_frac": moved * n_mat / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                  "fused_kernel_over_mover_time": avg_kernel_ms / ms}
-
-    if args.vendor_ref:
-        # context only: the vendor libraries' batched triangular solve against the identity, fp32, on the same chunk
-        # matrices (written out once by gdn_chunk_build_A), through torch.linalg.solve_triangular
-        K, beta, g, _ = sets[0]
-        A32 = tri.gdn_chunk_build_A(K, beta, g, C, gate_kind=w.gate_kind, op_dtype=tri.F32)
-        M = A32 + torch.eye(C, device=dev)
-        eye = torch.eye(C, device=dev).expand(n_mat, C, C).contiguous()
-        for _ in range(2):
-            Tv = torch.linalg.solve_triangular(M, eye, upper=False, unitriangular=True)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(5):
-            Tv = torch.linalg.solve_triangular(M, eye, upper=False, unitriangular=True)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 5
-        Tours = tri.tri_inv_ex(A32, method=tri.FWD_SUBST)
-        torch.cuda.synchronize()
-        out["vendor_ref"] = {"call": "torch.linalg.solve_triangular(I + A, I, upper=False, unitriangular=True), fp32",
-                             "ms": ms, "matrices_per_s": n_mat / (ms * 1e-3),
-                             "max_abs_diff_to_tri_inv_fwd_subst": float((Tv - Tours).abs().max())}
-        del A32, M, eye, Tv, Tours
 
     if args.solve:
         # W = (I + A)^{-1} diag(s) X with X, W [B, Tlen, H, d_x] in the operand type: same rotation over buffer sets

@@ -17,7 +17,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtriinv.so")
-PROBE_LIB = os.path.join(HERE, "libtriinv_probe.so")  # benchmark utility (data movers), loaded by bench.py only
 RESOURCES = os.path.join(HERE, "kernel_resources.json")  # registers / scratch / LDS of every kernel, from the compiler
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -86,9 +85,6 @@ def build(force: bool = False, jobs: int = 0) -> str:
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr[-4000:]}")
-    r = subprocess.run([HIPCC, *FLAGS[:-1], "-shared", os.path.join(CSRC, "probe.hip"), "-o", PROBE_LIB], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed for the probe library:\n{r.stderr[-4000:]}")
     return LIB
 
 

@@ -46,10 +46,10 @@ int out_dtype(uint32_t flags)
     return (h && b) ? -1 : h ? TRIINV_F16 : b ? TRIINV_BF16 : TRIINV_F32;
 }
 
-int finish(int not_built)
+// Launcher code -> status.  The launch's own return value is used; the runtime's sticky error state is left alone.
+int finish(int launcher_code)
 {
-    if (not_built) return TRIINV_ERR_UNSUPPORTED;
-    return hipGetLastError() == hipSuccess ? TRIINV_OK : TRIINV_ERR_LAUNCH;
+    return launcher_code == LAUNCHED ? TRIINV_OK : launcher_code == NOT_BUILT ? TRIINV_ERR_UNSUPPORTED : TRIINV_ERR_LAUNCH;
 }
 
 int pick_fused(const GdnArgs& a, int C, int op_dtype)
@@ -89,12 +89,17 @@ int pick_tri_inv(const TriInvArgs& a, int C, int op_dtype)
 int launch_fused(const GdnArgs& a, int C, int op_dtype)
 {
     int nb = pick_fused(a, C, op_dtype);
-    if (nb == 1 && !a.refine && a.out_dt == TRIINV_F32 && a.method != TRIINV_FWD_SUBST && a.method != 100 /* M_BUILD_A */) {
+    if (nb == NOT_BUILT && !a.refine && a.out_dt == TRIINV_F32 && a.method != TRIINV_FWD_SUBST && a.method != 100 /* M_BUILD_A */) {
         GdnArgs b = a;
         b.method = 100;
-        if (pick_fused(b, C, a.gate == TRIINV_GATE_PER_CHANNEL ? op_dtype : TRIINV_F32) != 0) return TRIINV_ERR_UNSUPPORTED;
-        const TriInvArgs t{a.T, a.T, a.n_mat, TRIINV_F32, a.method, a.stream, false, a.iters, TRIINV_F32, false};
-        nb = pick_tri_inv(t, C, op_dtype);
+        const int b_op = a.gate == TRIINV_GATE_PER_CHANNEL ? op_dtype : TRIINV_F32;
+        TriInvArgs t{a.T, a.T, a.n_mat, TRIINV_F32, a.method, a.stream, false, a.iters, TRIINV_F32, false};
+        // both halves must be built before the first one is launched: a failing call does no GPU work
+        b.dry = t.dry = true;
+        if (pick_fused(b, C, b_op) != LAUNCHED || pick_tri_inv(t, C, op_dtype) != LAUNCHED) return TRIINV_ERR_UNSUPPORTED;
+        b.dry = t.dry = false;
+        nb = pick_fused(b, C, b_op);
+        if (nb == LAUNCHED) nb = pick_tri_inv(t, C, op_dtype);
     }
     return finish(nb);
 }
@@ -279,7 +284,7 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
     if (overlap(cu_seqlens, cu_bytes, T, t_bytes) || overlap(cu_chunks, cu_bytes, T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (method == TRIINV_FWD_SUBST && gate_kind != TRIINV_GATE_PER_CHANNEL) op_dtype = TRIINV_F32;
 
-    const ChunkMap map{0, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
+    const ChunkMap map{total_tokens, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
     GdnArgs a{K, beta, gate_kind != TRIINV_GATE_NONE ? g : nullptr, T, n_mat, total_chunks, map, H, d_k, k_dtype, gate_kind, method,
               static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0, method_count(method, flags, C), out_dtype(flags)};
     return launch_fused(a, C, op_dtype);
@@ -326,7 +331,7 @@ int gdn_chunk_tri_solve_varlen(const void* K, const float* beta, const float* g,
         const uint64_t w_bytes = (uint64_t)total_tokens * H * d_x * esize(op_dtype), cu_bytes = (uint64_t)(n_seq + 1) * 8;
         if (overlap(cu_seqlens, cu_bytes, W, w_bytes) || overlap(cu_chunks, cu_bytes, W, w_bytes)) return TRIINV_ERR_ALIAS;
     }
-    const ChunkMap map{0, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
+    const ChunkMap map{total_tokens, 0u, (uint32_t)n_seq, cu_seqlens, cu_chunks};
     return solve_common(K, beta, g, 1, &X, &row_scale, &W, &d_x, (uint64_t)total_tokens, total_chunks, map, H, d_k, C, k_dtype,
                         gate_kind, method, op_dtype, hip_stream, flags);
 }

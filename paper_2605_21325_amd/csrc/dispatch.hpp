@@ -3,6 +3,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <tuple>
+#include <utility>
 #include "chunk_map.hpp"
 
 namespace triinv {
@@ -18,6 +20,7 @@ struct TriInvArgs {
     int iters;    // Newton-Schulz iteration count; for the mixed recursion: refinement steps on the 16 x 16 blocks
     int out_dt;   // element type of T: 0 fp32, 1 fp16, 2 bf16
     bool shuffle; // forward substitution: broadcast A by wavefront shuffles (C = 64)
+    bool dry = false;  // only report whether the combination is built; launch nothing
 };
 
 struct GdnArgs {
@@ -37,6 +40,7 @@ struct GdnArgs {
     bool refine;
     int iters;
     int out_dt;
+    bool dry = false;  // only report whether the combination is built; launch nothing
 };
 
 // gdn_chunk_tri_solve: the fused arguments (T unused) plus the right-hand sides.
@@ -52,7 +56,29 @@ struct SolveArgs {
 // The chunk stride of the few-heads workgroup map of the fused kernels (0 = the many-heads map): see fused_matrix_index.
 inline int head_spread(int H) { return H >= 8 ? 0 : (H >= 4 ? 1 : 4 / H); }
 
-// Return 0, or 1 when the combination is not instantiated; launch errors are left in hipGetLastError.
+// Launcher return codes.
+enum : int { LAUNCHED = 0, NOT_BUILT = 1, LAUNCH_FAILED = 2 };
+
+// One kernel launch whose own status is returned (the runtime's sticky per-thread error state, which may hold an
+// unrelated earlier error of the caller, is neither read nor cleared).  The arguments are converted to the kernel's
+// exact parameter types first.  dry: report LAUNCHED without launching.
+template <class... KArgs, class... Args, size_t... I>
+inline int launch_kernel_impl(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t stream,
+                              std::index_sequence<I...>, Args&&... args)
+{
+    std::tuple<KArgs...> vals{static_cast<KArgs>(std::forward<Args>(args))...};
+    void* ptrs[sizeof...(KArgs)] = {(void*)&std::get<I>(vals)...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, stream) == hipSuccess ? LAUNCHED : LAUNCH_FAILED;
+}
+template <class... KArgs, class... Args>
+inline int launch_kernel(bool dry, void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t stream, Args&&... args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    if (dry) return LAUNCHED;
+    return launch_kernel_impl(kernel, grid, block, lds_bytes, stream, std::index_sequence_for<KArgs...>{}, std::forward<Args>(args)...);
+}
+
+// Every launcher returns one of the codes above.
 #define TRIINV_DECL(NB, OP)                                  \
     int launch_tri_inv_nb##NB##_op##OP(const TriInvArgs& a); \
     int launch_gdn_nb##NB##_op##OP(const GdnArgs& a);        \

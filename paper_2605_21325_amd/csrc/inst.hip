@@ -27,9 +27,8 @@ constexpr int OP = TRIINV_INST_OP;
 
 template <int METHOD, bool REFINE = false> static int go_tri(const TriInvArgs& a)
 {
-    hipLaunchKernelGGL((k_tri_inv<OP, NB, METHOD, REFINE>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat,
+    return launch_kernel(a.dry, k_tri_inv<OP, NB, METHOD, REFINE>, dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat,
                        a.in_dt, a.iters, a.out_dt);
-    return 0;
 }
 
 // Fused matrix-core kernels at C <= 64 run four matrices (adjacent heads) per workgroup.
@@ -60,9 +59,8 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
         if (a.out_dt == OP_F32) {
             TriInvArgs first = a;
             first.refine = false;
-            if (CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(first) != 0) return 1;
-            hipLaunchKernelGGL((k_tri_inv_refine128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
-            return 0;
+            if (const int rc = CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(first)) return rc;
+            return launch_kernel(a.dry, k_tri_inv_refine128<OP>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
         }
 #endif
         return 1;
@@ -72,8 +70,7 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
     case M_FWD:
         if (a.shuffle) {
 #if TRIINV_INST_NB == 4
-            hipLaunchKernelGGL((k_tri_inv_fwd_shuffle64<0>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
-            return 0;
+            return launch_kernel(a.dry, k_tri_inv_fwd_shuffle64<0>, dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt);
 #else
             return 1;  // the shuffle variant is built at C = 64
 #endif
@@ -90,15 +87,13 @@ int CAT(launch_tri_inv_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const Tr
 #if TRIINV_INST_NB <= 4
         return go_tri<M_NEWTON_SCHULZ>(a);
 #else   // X in both orientations does not fit one wave's registers at C = 128: four waves, X and Y in LDS
-        hipLaunchKernelGGL((k_tri_inv_ns128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.iters, a.out_dt);
-        return 0;
+        return launch_kernel(a.dry, k_tri_inv_ns128<OP>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.iters, a.out_dt);
 #endif
     case M_NEUMANN:
 #if TRIINV_INST_NB <= 4
         return go_tri<M_NEUMANN>(a);
 #else   // C = 128: the one-wave register version would spill; a workgroup of four waves shares Y in LDS
-        hipLaunchKernelGGL((k_tri_inv_neumann128<OP>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.out_dt);
-        return 0;
+        return launch_kernel(a.dry, k_tri_inv_neumann128<OP>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.A, a.T, a.n_mat, a.in_dt, a.out_dt);
 #endif
 #endif
     default: return 1;
@@ -118,10 +113,9 @@ template <int METHOD> constexpr unsigned occupancy_pad_bytes()
 
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
-    hipLaunchKernelGGL((k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
+    return launch_kernel(a.dry, k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
                        dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
                        a.iters, a.out_dt, WPB > 1 ? head_spread(a.H) : 0);
-    return 0;
 }
 
 template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
@@ -141,15 +135,12 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
             }
         }
 #if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
-        if constexpr (!(KD == OP_F32 && DKS == 8)) {  // (128 fp32 channels x 128 rows of keys per wave do not fit the register file)
-            if (a.out_dt == OP_F32) {
-                GdnArgs first = a;
-                first.refine = false;
-                if (gdn_method<KD, DKS>(first) != 0) return 1;
-                hipLaunchKernelGGL((k_gdn_tri_inv_refine128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
-                                   a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
-                return 0;
-            }
+        if (a.out_dt == OP_F32) {
+            GdnArgs first = a;
+            first.refine = false;
+            if (const int rc = gdn_method<KD, DKS>(first)) return rc;
+            return launch_kernel(a.dry, k_gdn_tri_inv_refine128<KD, OP, DKS>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
+                               a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k);
         }
 #endif
         return 1;
@@ -169,25 +160,15 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 #if TRIINV_INST_NB <= 4
         return go_gdn<KD, M_NEWTON_SCHULZ, DKS>(a);
 #else
-        if constexpr (KD == OP_F32 && DKS == 8) {
-            return 1;  // 128 fp32 channels x 128 rows of keys per wave do not fit the register file
-        } else {
-            hipLaunchKernelGGL((k_gdn_tri_inv_ns128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K, a.beta,
-                               a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
-            return 0;
-        }
+        return launch_kernel(a.dry, k_gdn_tri_inv_ns128<KD, OP, DKS>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K, a.beta,
+                           a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
 #endif
     case M_NEUMANN:
 #if TRIINV_INST_NB <= 4
         return go_gdn<KD, M_NEUMANN, DKS>(a);
 #else
-        if constexpr (KD == OP_F32 && DKS == 8) {
-            return 1;  // 128 fp32 channels x 128 rows of keys per wave do not fit the register file
-        } else {
-            hipLaunchKernelGGL((k_gdn_tri_inv_neumann128<KD, OP, DKS>), dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
-                               a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.out_dt);
-            return 0;
-        }
+        return launch_kernel(a.dry, k_gdn_tri_inv_neumann128<KD, OP, DKS>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K,
+                           a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.out_dt);
 #endif
 #endif
     default: return 1;
@@ -196,10 +177,9 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 
 template <int METHOD, bool REFINE = false> static int go_kda(const GdnArgs& a)
 {
-    hipLaunchKernelGGL((k_kda_tri_inv<OP, NB, METHOD, WPB, REFINE>), dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
+    return launch_kernel(a.dry, k_kda_tri_inv<OP, NB, METHOD, WPB, REFINE>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
                        a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt,
                        WPB > 1 ? head_spread(a.H) : 0);
-    return 0;
 }
 
 static int kda_method(const GdnArgs& a)
@@ -246,9 +226,8 @@ static int kda_method(const GdnArgs& a)
 // directly solved blocks.
 template <int KD, int METHOD> static int go_any_dk(const GdnArgs& a)
 {
-    hipLaunchKernelGGL((k_gdn_any_dk_tri_inv<KD, OP, NB, METHOD>), dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
+    return launch_kernel(a.dry, k_gdn_any_dk_tri_inv<KD, OP, NB, METHOD>, dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
                        a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.out_dt);
-    return 0;
 }
 
 template <int KD> static int any_dk_method(const GdnArgs& a)
@@ -274,7 +253,11 @@ int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const GdnArg
 #else
     if (a.k_dt == OP_F32) {
         if (a.d_k == 64) return gdn_method<OP_F32, 4>(a);
+#if TRIINV_INST_NB <= 4
         if (a.d_k == 128) return gdn_method<OP_F32, 8>(a);
+#endif
+        // C = 128 with 128 fp32 channels: the chunk's keys alone would take 256 registers per lane, so that
+        // combination runs the channel loop below (keys consumed 32 channels at a time) like the other head dimensions
     } else if (a.k_dt == OP_BF16) {
         if (a.d_k == 64) return gdn_method<OP_BF16, 2>(a);
         if (a.d_k == 128) return gdn_method<OP_BF16, 4>(a);

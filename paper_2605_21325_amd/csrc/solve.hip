@@ -36,14 +36,12 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     const GdnArgs& f = a.f;
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {
-        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g,
+        return launch_kernel(f.dry, k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 1>, grid, block, 0, f.stream, f.K, f.beta, f.g,
                            rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters, WPB > 1 ? head_spread(f.H) : 0);
-        return 0;
     }
     if constexpr (HAS_PAIR) {
-        hipLaunchKernelGGL((k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g,
+        return launch_kernel(f.dry, k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 2>, grid, block, 0, f.stream, f.K, f.beta, f.g,
                            rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters, WPB > 1 ? head_spread(f.H) : 0);
-        return 0;
     }
     return 1;
 }
@@ -60,14 +58,12 @@ template <int METHOD> static int go_kda(const SolveArgs& a)
     const GdnArgs& f = a.f;
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {
-        hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+        return launch_kernel(f.dry, k_kda_tri_solve<OP, NB, METHOD, WPB, 1>, grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
                            f.map, f.H, f.d_k, f.k_dt, f.iters, WPB > 1 ? head_spread(f.H) : 0);
-        return 0;
     }
     if constexpr (HAS_PAIR) {
-        hipLaunchKernelGGL((k_kda_tri_solve<OP, NB, METHOD, WPB, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+        return launch_kernel(f.dry, k_kda_tri_solve<OP, NB, METHOD, WPB, 2>, grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
                            f.map, f.H, f.d_k, f.k_dt, f.iters, WPB > 1 ? head_spread(f.H) : 0);
-        return 0;
     }
     return 1;
 }
@@ -79,12 +75,11 @@ template <int KD, int METHOD> static int go_any_dk(const SolveArgs& a)
     const GdnArgs& f = a.f;
     const dim3 grid((unsigned)f.n_mat), block(64);
     if (a.n_rhs == 1)
-        hipLaunchKernelGGL((k_gdn_any_dk_tri_solve<KD, OP, NB, METHOD, 1>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+        return launch_kernel(f.dry, k_gdn_any_dk_tri_solve<KD, OP, NB, METHOD, 1>, grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
                            f.map, f.H, f.d_k, f.iters);
     else
-        hipLaunchKernelGGL((k_gdn_any_dk_tri_solve<KD, OP, NB, METHOD, 2>), grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
-                           f.map, f.H, f.d_k, f.iters);
-    return 0;
+        return launch_kernel(f.dry, k_gdn_any_dk_tri_solve<KD, OP, NB, METHOD, 2>, grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
+                             f.map, f.H, f.d_k, f.iters);
 }
 
 template <int KD> static int any_dk_method(const SolveArgs& a)

@@ -211,10 +211,12 @@ def test_binding_refuses_host_tensors_and_missing_library(monkeypatch, L):
         tri.lib()
 
 
-def test_no_kernel_spills_at_the_full_register_budget():
-    """A build whose Neumann kernel for C = 128 spilled registers while using all 512 of them
-    aborted on the GPU; such kernels must not be in the library (that path reports
-    'combination not built' instead)."""
+def test_no_kernel_uses_scratch_memory_or_spills():
+    """Every kernel in the library keeps its whole state in registers and LDS: no per-lane scratch memory (a stack array
+    the compiler could not keep in registers, or spilled registers) and no spilled vector registers.  A build whose
+    Neumann kernel for C = 128 spilled at the full 512-register budget aborted on the GPU; combinations that do not fit
+    are routed to another kernel or report 'combination not built' instead.  The report is written by the build from the
+    compiler's resource remarks."""
     import json
 
     path = os.path.join(os.path.dirname(tri.binding.LIB_PATH), "kernel_resources.json")
@@ -222,5 +224,5 @@ def test_no_kernel_spills_at_the_full_register_budget():
         pytest.skip("no compiler resource report beside the library")
     res = json.load(open(path))
     assert len(res) > 50
-    bad = [k for k, v in res.items() if v.get("vgpr_spill", 0) > 0 and v.get("vgpr", 0) + v.get("agpr", 0) >= 500]
+    bad = {k: v for k, v in res.items() if v.get("scratch", 0) > 0}
     assert not bad, bad

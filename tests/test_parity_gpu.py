@@ -1107,33 +1107,6 @@ def test_solve_multi_limits():
     assert torch.equal(W1, tri.gdn_chunk_tri_solve(K, beta, None, X, 128, gate_kind=tri.GATE_NONE))
 
 
-@pytest.mark.parametrize("C,H", [(64, 8), (64, 4), (128, 3)])
-def test_probe_mover_moves_what_it_says(C, H):
-    """The benchmark's data mover (libtriinv_probe.so) reads exactly the key rows the fused kernel reads and writes exactly
-    the bytes of its result: every 16-byte piece of the output is a known 16-byte piece of the input."""
-    import ctypes
-    from paper_2605_21325_amd import build as tri_build
-    P = ctypes.CDLL(tri_build.PROBE_LIB)
-    P.triinv_probe_mover.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_uint, ctypes.c_int,
-                                     ctypes.c_void_p]
-    P.triinv_probe_mover.restype = ctypes.c_int
-    n_chunk = 11
-    K = torch.randint(-30000, 30000, (n_chunk * C, H, 128), dtype=torch.int16, device=DEV)       # any 16-bit pattern
-    Kc = K.view(n_chunk, C, H, 4, 4, 8).cpu()                             # [chunk, row, head, s, q, 8 x int16]
-    nreg = C // 4
-    for kind in (0, 1):                                                   # buffer stores, global stores
-        T = torch.full((n_chunk * H, C, C), -1.0, device=DEV)
-        assert P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, H, C, 0, kind, None) == 0
-        torch.cuda.synchronize()
-        out = T.view(torch.int16).view(n_chunk, H, -1, 64, 8).cpu()      # [chunk, head, register, lane, 8 x int16]
-        for k in range(nreg * (C // 64)):
-            i, s = (k % nreg) >> 2, (k % nreg) & 3
-            for q in range(4):
-                want = Kc[:, 16 * i:16 * i + 16, :, s, q].permute(0, 2, 1, 3)   # [chunk, head, n, 8]
-                assert torch.equal(out[:, :, k, 16 * q:16 * q + 16], want), (kind, k, q)
-    assert P.triinv_probe_mover(K.data_ptr(), T.data_ptr(), n_chunk, 6, 64, 0, 0, None) == -1   # C = 64 needs H % 4 == 0
-
-
 # ------------------------------------------------------------------ combinations without a fused kernel: build A, invert in place
 @pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
 @pytest.mark.parametrize("case", ["kda_c128_neumann", "kda_c128_ns", "f32keys_c128_neumann", "f32keys_c128_ns", "dk96_mixed", "dk96_ns",
