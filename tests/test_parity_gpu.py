@@ -17,6 +17,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 TOL = {tri.F32: 1e-5, tri.F16: 2e-2, tri.BF16: 2e-2}
 MFMA_METHODS = [tri.BLOCK_RECURSIVE, tri.BLOCK_DIRECT, tri.MIXED, tri.NEUMANN]
+_OPS = (tri.F32, tri.F16, tri.BF16)
 ALL = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in MFMA_METHODS for o in (tri.F32, tri.F16, tri.BF16)]
 
 
@@ -24,13 +25,66 @@ def ids(mo):
     return f"{tri.METHOD_NAMES[mo[0]]}-{tri.DTYPE_NAMES[mo[1]]}"
 
 
-def check(T_gpu: torch.Tensor, T_ref: np.ndarray, tol: float, what: str):
+# Unit roundoff of the matrix-core operand types (round to nearest even).
+UNIT = {tri.F32: 2.0 ** -24, tri.F16: 2.0 ** -11, tri.BF16: 2.0 ** -8}
+SKIP = "skip"
+
+
+def elementwise_bound(T_ref: np.ndarray, op: int, key_abs=None, ns_iters=None) -> np.ndarray:
+    """First-order worst-case bound on every element of T_gpu - T for the blocked methods (and, with its C sequential
+    fp32 multiply-adds per element, forward substitution).  One level of the 2 x 2 recursion forms -T22 (A21 T11): two
+    chained products, both operands of each rounded to the operand type (unit roundoff u), so a level contributes at
+    most 4u relative to the magnitudes it multiplies; log2 C levels; fp32 accumulation adds C 2^-24.  A right residual
+    R = X(I + A) - I with |R| <= c |X| |I + A| gives |X - T| = |R T| <= c |T| |I + A| |T|:
+        E = (4 log2(C) u + C 2^-24) |T| |I + A| |T| + 1e-6.
+    key_abs (per-channel gate with 16-bit operands): the gated keys themselves are rounded, which perturbs A by at most
+    2u beta_i sum_c |k_ic k_jc| exp(g_ic - g_jc) -- not proportional to |A_ij| when the dot product cancels -- and T by
+    |T| dA |T|; key_abs is that sum (the oracle's build of A on |K|).
+    ns_iters (Newton-Schulz, m iterations from X0 = I / C): the iterate is not the inverse but, in exact arithmetic,
+    X_m = T (I - R0^(2^m)) with R0 = I - (I + A) / C (paper Eq. 8); that truncation |T R0^(2^m)| is added."""
+    C = T_ref.shape[-1]
+    Ta = np.abs(T_ref)
+    M = np.abs(np.linalg.inv(T_ref))                      # |I + A|: unit lower triangular, kappa <= C^2, exact enough in fp64
+    u = UNIT[op]
+    E = (4 * np.log2(C) * u + C * 2.0 ** -24) * (Ta @ M @ Ta) + 1e-6
+    if key_abs is not None:
+        E = E + 2 * u * (Ta @ np.abs(key_abs) @ Ta)
+    if ns_iters is not None:
+        R = np.eye(C) - np.linalg.inv(T_ref) / C
+        for _ in range(ns_iters):
+            R = R @ R
+        E = E + np.abs(T_ref @ R)
+    return E
+
+
+def key_abs_term(inp, gate_kind, C):
+    """The matrix beta_i sum_c |k_ic k_jc| exp(g_ic - g_jc) for the per-channel gate (None for the other kinds)."""
+    if gate_kind != tri.GATE_PER_CHANNEL:
+        return None
+    return oracle.build_A_ragged(inp["K"].abs(), inp["beta"], inp["g"], gate_kind, C)
+
+
+def check(T_gpu: torch.Tensor, T_ref: np.ndarray, tol: float, what: str, op=None, key_abs=None, method=None):
+    """Exact structure, the per-matrix relative Frobenius tolerance, and -- for the two standard tolerances -- the
+    elementwise bound above (op: operand type; by default fp32 for the 1e-5 tolerance, bf16 for 2e-2).
+    key_abs = SKIP leaves the elementwise bound out (per-channel gate with 16-bit operands where the caller has no
+    inputs at hand to form the rounded-key term)."""
     torch.cuda.synchronize()
     Tg = T_gpu.cpu().numpy()
     assert metrics.structure_ok(Tg), f"{what}: not exactly unit lower triangular"
-    err = metrics.forward_errors(T_ref, Tg.astype(np.float64))["rel_fro"]
+    Tg = Tg.astype(np.float64)
+    err = metrics.forward_errors(T_ref, Tg)["rel_fro"]
     assert np.isfinite(err).all(), f"{what}: non-finite output"
     assert err.max() <= tol, f"{what}: rel_fro max {err.max():.3e} > {tol}"
+    if tol in (1e-5, 2e-2) and key_abs is not SKIP:
+        if op is None:
+            op = tri.F32 if tol == 1e-5 else tri.BF16
+        C = T_ref.shape[-1]
+        ns_iters = 2 * int(np.log2(C)) if method == tri.NEWTON_SCHULZ else None      # the library's default count
+        ratio = np.abs(Tg - T_ref) / elementwise_bound(T_ref, op, key_abs, ns_iters)
+        worst = np.unravel_index(np.argmax(ratio), ratio.shape)
+        assert ratio.max() <= 1.0, (f"{what}: element {worst} off by {abs(Tg[worst] - T_ref[worst]):.3e}, "
+                                    f"{ratio.max():.2f} x its bound")
     return err.max()
 
 
@@ -43,7 +97,7 @@ def cases():
         inp = si.make_inputs(si.workload(idx, **kw))
         w = inp["workload"]
         A = oracle.build_A(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
-        out[idx] = dict(inp=inp, w=w, A=A, T=oracle.tri_inv(A))
+        out[idx] = dict(inp=inp, w=w, A=A, T=oracle.tri_inv(A), key_abs=key_abs_term(inp, w.gate_kind, w.C))
     return out
 
 
@@ -58,7 +112,7 @@ def test_tri_inv_fp32_input(cases, idx, mo):
     A32 = torch.from_numpy(c["A"].astype(np.float32))
     T_ref = oracle.tri_inv(A32)                      # oracle on the values as stored
     T = tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op)
-    check(T, T_ref, TOL[op], f"cfg{idx} {ids(mo)}")
+    check(T, T_ref, TOL[op], f"cfg{idx} {ids(mo)}", op=op)
 
 
 @pytest.mark.parametrize("dt", [torch.float16, torch.bfloat16])
@@ -140,7 +194,7 @@ def test_fused_matches_oracle(cases, idx, mo):
     g = None if inp["g"] is None else inp["g"].to(DEV)
     T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, w.C, gate_kind=w.gate_kind,
                                  method=method, op_dtype=op)
-    check(T, c["T"], TOL[op], f"fused cfg{idx} {ids(mo)}")
+    check(T, c["T"], TOL[op], f"fused cfg{idx} {ids(mo)}", op=op, key_abs=c["key_abs"])
 
 
 def test_fused_short_form_and_f16_keys(cases):
@@ -180,7 +234,8 @@ def test_per_channel_gate_reduces_to_scalar_gate(cases):
     for method, op in [(tri.BLOCK_RECURSIVE, tri.F32), (tri.FWD_SUBST, tri.F32), (tri.NEUMANN, tri.F32), (tri.MIXED, tri.BF16),
                        (tri.BLOCK_DIRECT, tri.F32)]:
         T = tri.gdn_chunk_tri_inv_ex(K, beta, g4, w.C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
-        check(T, c["T"], TOL[op], f"per-channel == scalar {ids((method, op))}")
+        check(T, c["T"], TOL[op], f"per-channel == scalar {ids((method, op))}", op=op,
+              key_abs=oracle.build_A(inp["K"].abs(), inp["beta"], inp["g"], w.gate_kind, w.C))
 
 
 def test_per_channel_gate_fp32_and_fp16_keys(cases):
@@ -208,6 +263,27 @@ def test_other_head_dimensions(C, d_k):
                            (tri.BLOCK_DIRECT, tri.F16), (tri.FWD_SUBST, tri.F32)]:
             T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate, method=method, op_dtype=op)
             check(T, ref, TOL[op], f"d_k={d_k} C={C} {k_dtype} {ids((method, op))}")
+
+
+FP32_KEY_METHODS = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in (tri.BLOCK_RECURSIVE, tri.BLOCK_DIRECT, tri.MIXED, tri.MIXED_B32,
+                                                                  tri.NEUMANN, tri.NEWTON_SCHULZ) for o in _OPS]
+
+
+@pytest.mark.parametrize("mo", FP32_KEY_METHODS, ids=ids)
+@pytest.mark.parametrize("C", [64, 128])
+def test_fp32_keys_with_128_channels(C, mo):
+    """Keys stored in fp32 (paper Sec. 4.1: fp32 inputs) at d_k = 128, every method and operand type.  At C = 128 a
+    chunk's keys alone are 256 registers per lane: that combination runs the channel-loop kernels (blocked, direct-leaf
+    recursion, forward substitution) or the two-launch path (the others), never a kernel with scratch memory."""
+    method, op = mo
+    inp = si.make_inputs(si.workload(1, B=1, Tlen=3 * C + 17, H=3, C=C, d_k=128, k_dtype="f32"))
+    assert inp["K"].dtype == torch.float32
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 0, C)
+    n_mat = T_ref.shape[0]
+    guard = torch.full((n_mat + 1, C, C), 7.0, device=DEV)
+    tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), C, T=guard[:n_mat], method=method, op_dtype=op)
+    check(guard[:n_mat], T_ref, TOL[op], f"fp32 keys d_k=128 C={C} {ids(mo)}", op=op, method=method)
+    assert bool((guard[n_mat] == 7.0).all()), "wrote past the last matrix"
 
 
 def test_group_counts_that_are_not_multiples_of_eight(cases):
@@ -250,9 +326,10 @@ def test_refinement_step_with_the_per_channel_gate(cases):
     K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
     for method in (tri.MIXED, tri.BLOCK_RECURSIVE):
         for op in (tri.F32, tri.F16, tri.BF16):
-            e0 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=1, method=method, op_dtype=op), c["T"], TOL[op], "per-channel")
+            e0 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=1, method=method, op_dtype=op), c["T"], TOL[op], "per-channel",
+                       op=op, key_abs=c["key_abs"])
             e1 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=1, method=method, op_dtype=op, flags=1), c["T"], TOL[op],
-                       "per-channel, refined")
+                       "per-channel, refined", op=op, key_abs=c["key_abs"])
             assert e1 <= 2.5 * e0 + 1e-7, (method, op, e0, e1)
 
 
@@ -329,15 +406,17 @@ def test_newton_schulz(cases, op):
         c = cases[idx]
         w, inp = c["w"], c["inp"]
         A32 = torch.from_numpy(c["A"].astype(np.float32))
-        check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), oracle.tri_inv(A32), TOL[op], f"NS cfg{idx}")
+        check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), oracle.tri_inv(A32), TOL[op], f"NS cfg{idx}", op=op,
+              method=tri.NEWTON_SCHULZ)
         g = None if inp["g"] is None else inp["g"].to(DEV)
         Tf = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, w.C, gate_kind=w.gate_kind,
                                       method=tri.NEWTON_SCHULZ, op_dtype=op)
-        check(Tf, c["T"], TOL[op], f"NS fused cfg{idx}")
+        check(Tf, c["T"], TOL[op], f"NS fused cfg{idx}", op=op, key_abs=c["key_abs"], method=tri.NEWTON_SCHULZ)
     inp = si.make_inputs(si.workload(4, Tlen=512, H=3, C=64))
     A = oracle.build_A(inp["K"], inp["beta"], None, si.GATE_NONE, 64)
     A32 = torch.from_numpy(A.astype(np.float32))
-    check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), oracle.tri_inv(A32), TOL[op], "NS stress blocks")
+    check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), oracle.tri_inv(A32), TOL[op], "NS stress blocks", op=op,
+          method=tri.NEWTON_SCHULZ)
 
 
 @pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
@@ -348,14 +427,16 @@ def test_newton_schulz_c128(op, capsys):
     inp = si.make_inputs(si.workload(1, Tlen=128 * 3 + 40, H=3, C=128))
     T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 0, 128)
     K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
-    check(tri.gdn_chunk_tri_inv_ex(K, beta, g, 128, method=tri.NEWTON_SCHULZ, op_dtype=op), T_ref, TOL[op], "NS C=128 fused")
+    check(tri.gdn_chunk_tri_inv_ex(K, beta, g, 128, method=tri.NEWTON_SCHULZ, op_dtype=op), T_ref, TOL[op], "NS C=128 fused", op=op,
+          method=tri.NEWTON_SCHULZ)
     T_ref2 = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], None, 2, 128)
     check(tri.gdn_chunk_tri_inv_ex(K, beta, None, 128, gate_kind=tri.GATE_NONE, method=tri.NEWTON_SCHULZ, op_dtype=op), T_ref2,
           TOL[op], "NS C=128 fused, no gate")
     A = oracle.build_A_ragged(inp["K"], inp["beta"], inp["g"], 0, 128)
     A32 = torch.from_numpy(A.astype(np.float32))
     T32 = oracle.tri_inv(A32)
-    check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), T32, TOL[op], "NS C=128 standalone")
+    check(tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op), T32, TOL[op], "NS C=128 standalone", op=op,
+          method=tri.NEWTON_SCHULZ)
     few = tri.tri_inv_ex(A32.to(DEV), method=tri.NEWTON_SCHULZ, op_dtype=op, flags=tri.flag_iters(5)).cpu().numpy()
     e_few = metrics.forward_errors(T32, few.astype(np.float64))["rel_fro"].max()
     assert e_few > 1e-1, "five iterations cannot have converged from X0 = I / 128"
@@ -434,34 +515,64 @@ def _sample(n_mat, k=48, seed=0):
     return np.unique(np.concatenate([[0, 1, n_mat - 1], rng.integers(0, n_mat, size=k)])).tolist()
 
 
-@pytest.mark.parametrize("idx,mo", [(1, (tri.BLOCK_RECURSIVE, tri.BF16)), (1, (tri.FWD_SUBST, tri.F32)),
-                                    (2, (tri.BLOCK_RECURSIVE, tri.BF16)), (2, (tri.BLOCK_RECURSIVE, tri.F32)),
-                                    (2, (tri.MIXED, tri.F16)), (2, (tri.NEUMANN, tri.BF16)), (2, (tri.FWD_SUBST, tri.F32)),
-                                    (2, (tri.BLOCK_DIRECT, tri.F32)), (2, (tri.BLOCK_DIRECT, tri.BF16)),
-                                    (3, (tri.BLOCK_DIRECT, tri.F32)), (4, (tri.BLOCK_DIRECT, tri.F32)),
-                                    (3, (tri.BLOCK_RECURSIVE, tri.BF16)), (3, (tri.BLOCK_RECURSIVE, tri.F32)),
-                                    (3, (tri.FWD_SUBST, tri.F32)),
-                                    (4, (tri.BLOCK_RECURSIVE, tri.F32)), (4, (tri.BLOCK_RECURSIVE, tri.BF16)),
-                                    (4, (tri.FWD_SUBST, tri.F32))],
-                         ids=lambda v: ids(v) if isinstance(v, tuple) else f"cfg{v}")
-def test_full_size_workload_sampled(idx, mo):
+# The precision matrix at full size (paper Sec. 4.1 protocol: every method in fp32, fp16 and bf16 operand modes):
+# configs[2] x {forward substitution, blocked, direct-leaf, mixed recursion, Neumann product} and configs[4] (the stress
+# workload) x {forward substitution, blocked, direct-leaf, mixed (b0 = 16 and 32) recursion, Newton-Schulz}, every operand
+# type; configs[1] and configs[3] with the methods their kernels differ in.  The Neumann product on configs[4] is run and
+# its error printed, not asserted (the paper predicts its failure there, Sec. 3.2 / 4.1).
+FULL_MATRIX = ([(1, (tri.BLOCK_RECURSIVE, tri.BF16)), (1, (tri.FWD_SUBST, tri.F32))]
+               + [(2, (tri.FWD_SUBST, tri.F32))]
+               + [(2, (m, o)) for m in (tri.BLOCK_RECURSIVE, tri.BLOCK_DIRECT, tri.MIXED, tri.NEUMANN) for o in _OPS]
+               + [(3, (tri.FWD_SUBST, tri.F32)), (3, (tri.BLOCK_DIRECT, tri.F32))]
+               + [(3, (tri.BLOCK_RECURSIVE, o)) for o in _OPS]
+               + [(4, (tri.FWD_SUBST, tri.F32))]
+               + [(4, (m, o)) for m in (tri.BLOCK_RECURSIVE, tri.BLOCK_DIRECT, tri.MIXED, tri.MIXED_B32, tri.NEWTON_SCHULZ, tri.NEUMANN)
+                  for o in _OPS])
+
+_full_cache = {}
+
+
+def full_size(idx):
+    """Inputs of one full-size workload on the device, the sampled matrices and the oracle's results for them; one workload
+    is kept at a time (configs[3] alone holds 1.6 GB of inputs)."""
+    if _full_cache.get("idx") != idx:
+        _full_cache.clear()
+        w = si.WORKLOADS[idx]
+        inp = si.make_inputs(w)
+        sel = _sample(w.n_mat)
+        T_ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C, sel=sel)
+        key_abs = None
+        if w.gate_kind == tri.GATE_PER_CHANNEL:
+            key_abs = oracle.build_A(inp["K"].abs(), inp["beta"], inp["g"], w.gate_kind, w.C, sel=sel)
+        _full_cache.update(idx=idx, w=w, sel=sel, T_ref=T_ref, key_abs=key_abs, K=inp["K"].to(DEV), beta=inp["beta"].to(DEV),
+                           g=None if inp["g"] is None else inp["g"].to(DEV))
+    return _full_cache
+
+
+@pytest.mark.parametrize("idx,mo", FULL_MATRIX, ids=lambda v: ids(v) if isinstance(v, tuple) else f"cfg{v}")
+def test_full_size_workload_sampled(idx, mo, capsys):
     """The launch configuration the benchmark times, at the workload's full size; the oracle
     recomputes a sample of the output matrices one by one, and the structural property is
     checked on every matrix."""
     method, op = mo
-    w = si.WORKLOADS[idx]
-    inp = si.make_inputs(w)
-    g = None if inp["g"] is None else inp["g"].to(DEV)
-    T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, w.C, gate_kind=w.gate_kind,
-                                 method=method, op_dtype=op)
+    f = full_size(idx)
+    w, sel = f["w"], f["sel"]
+    T = tri.gdn_chunk_tri_inv_ex(f["K"], f["beta"], f["g"], w.C, gate_kind=w.gate_kind, method=method, op_dtype=op)
     torch.cuda.synchronize()
-    sel = _sample(w.n_mat)
-    T_ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C, sel=sel)
-    check(T[sel], T_ref, TOL[op], f"full cfg{idx} {ids(mo)}")
-    # every matrix: exact unit lower triangle, entries bounded by one (Cor. 2.1 and its source)
     diag = torch.diagonal(T, dim1=1, dim2=2)
     assert bool((diag == 1).all())
     assert bool((torch.triu(T, 1) == 0).all())
+    if idx == 4 and method == tri.NEUMANN:
+        Ts = T[sel].cpu().numpy().astype(np.float64)
+        with np.errstate(invalid="ignore"):
+            e = metrics.forward_errors(f["T_ref"], Ts)["rel_fro"]
+        bad = int((~np.isfinite(e)).sum())
+        with capsys.disabled():
+            print(f"\nneumann {tri.DTYPE_NAMES[op]} on configs[4] at full size: rel_fro max "
+                  f"{np.nanmax(e) if bad < len(e) else float('nan'):.3e}, non-finite matrices {bad}/{len(e)} (reported, not asserted)")
+        return
+    check(T[sel], f["T_ref"], TOL[op], f"full cfg{idx} {ids(mo)}", op=op, key_abs=f["key_abs"], method=method)
+    # every matrix: entries bounded by one (Cor. 2.1 and its source)
     assert float(T.abs().max()) <= 1.0 + (1e-4 if op == tri.F32 else 5e-2)
 
 
@@ -573,7 +684,7 @@ def test_sequence_lengths_that_are_not_multiples_of_the_chunk(C, Tlen, gate_kind
     tol = TOL[op]
     if idx == 4 and method == tri.NEUMANN:
         return  # the Neumann product on the stress recipe is reported elsewhere, not asserted
-    check(guard[:n_mat], T_ref, tol, f"ragged C={C} Tlen={Tlen} gate={gate_kind} {ids(mo)}")
+    check(guard[:n_mat], T_ref, tol, f"ragged C={C} Tlen={Tlen} gate={gate_kind} {ids(mo)}", op=op, key_abs=key_abs_term(inp, gate_kind, C))
 
 
 @pytest.mark.parametrize("d_k", [96, 128])
@@ -603,7 +714,8 @@ def test_packed_variable_length_sequences(C, gate_kind, d_k):
         T = tri.gdn_chunk_tri_inv_varlen(K.to(DEV), beta.to(DEV), None if g is None else g.to(DEV), seqlens, C,
                                          gate_kind=gate_kind, method=method, op_dtype=op)
         assert T.shape[0] == T_ref.shape[0]
-        check(T, T_ref, TOL[op], f"varlen C={C} gate={gate_kind} d_k={d_k} {ids((method, op))}")
+        check(T, T_ref, TOL[op], f"varlen C={C} gate={gate_kind} d_k={d_k} {ids((method, op))}", op=op,
+              key_abs=SKIP if gate_kind == 1 and op != tri.F32 else None)
 
 
 def test_packed_sequences_with_no_tokens_are_a_no_op():
@@ -625,7 +737,7 @@ def test_small_chunk_sizes_standalone(C, mo):
     A = si.random_strict_lower(37, C, 0.15, seed=3)
     T_ref = oracle.tri_inv(A)
     T = tri.tri_inv_ex(A.to(DEV), method=method, op_dtype=op)
-    check(T, T_ref, TOL[op], f"standalone C={C} {ids(mo)}")
+    check(T, T_ref, TOL[op], f"standalone C={C} {ids(mo)}", op=op, method=method)
 
 
 @pytest.mark.parametrize("mo", SMALL_C_METHODS, ids=ids)
@@ -638,7 +750,7 @@ def test_small_chunk_sizes_fused(C, gate_kind, mo):
     T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)
     g = None if inp["g"] is None else inp["g"].to(DEV)
     T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate_kind, method=method, op_dtype=op)
-    check(T, T_ref, TOL[op], f"fused C={C} gate={gate_kind} {ids(mo)}")
+    check(T, T_ref, TOL[op], f"fused C={C} gate={gate_kind} {ids(mo)}", op=op, key_abs=key_abs_term(inp, gate_kind, C), method=method)
 
 
 @pytest.mark.parametrize("C", [16, 32])
@@ -766,7 +878,7 @@ def test_entry_points_replay_from_a_captured_graph():
         torch.cuda.synchronize()
         assert torch.equal(T1, E1) and torch.equal(T2, E2) and torch.equal(W, E3), f"replay {rep} differs from the eager launch"
         check_solve(W, oracle.gdn_chunk_tri_solve(src["K"], src["beta"], src["g"], rhs[rep % 3]["X"], rhs[rep % 3]["row_scale"], 0, C),
-                    2e-2, f"graph replay {rep} (solve)")
+                    2e-2, f"graph replay {rep} (solve)", C=C)
         check(T1, oracle.gdn_chunk_tri_inv_ragged(src["K"], src["beta"], src["g"], 0, C), 2e-2, f"graph replay {rep}")
 
 
@@ -784,12 +896,12 @@ def test_mixed_recursion_b32(cases, C, op):
         g = None if inp["g"] is None else inp["g"].to(DEV)
         T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate_kind, method=tri.MIXED_B32,
                                      op_dtype=op)
-        check(T, T_ref, TOL[op], f"mixed_b32 fused C={C} gate={gate_kind}")
+        check(T, T_ref, TOL[op], f"mixed_b32 fused C={C} gate={gate_kind}", op=op, key_abs=key_abs_term(inp, gate_kind, C))
     A = si.random_strict_lower(21, C, 0.15, seed=5)
     T32 = oracle.tri_inv(A)
     for r in (0, 1, 2):
         T = tri.tri_inv_ex(A.to(DEV), method=tri.MIXED_B32, op_dtype=op, flags=tri.flag_mxr_r(r))
-        check(T, T32, TOL[op], f"mixed_b32 standalone C={C} r={r}")
+        check(T, T32, TOL[op], f"mixed_b32 standalone C={C} r={r}", op=op)
         if op == tri.F32:
             want = np.stack([methods.mxr(np.tril(A[m].numpy().astype(np.float64), -1), 32, r, "f32") for m in range(3)])
             got = T.cpu().numpy().astype(np.float64)[:3]
@@ -799,7 +911,7 @@ def test_mixed_recursion_b32(cases, C, op):
         T_ref = oracle.gdn_chunk_tri_inv(st["K"], st["beta"], None, 2, C)
         T = tri.gdn_chunk_tri_inv_ex(st["K"].to(DEV), st["beta"].to(DEV), None, C, gate_kind=tri.GATE_NONE, method=tri.MIXED_B32,
                                      op_dtype=op)
-        check(T, T_ref, TOL[op], f"mixed_b32 stress C={C}")
+        check(T, T_ref, TOL[op], f"mixed_b32 stress C={C}", op=op)
 
 
 def test_mixed_recursion_b32_needs_c32():
@@ -827,7 +939,10 @@ def test_per_channel_gate_with_a_strong_decay(C, op):
     K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
     for method in (tri.BLOCK_RECURSIVE, tri.FWD_SUBST, tri.MIXED_B32 if C >= 32 else tri.MIXED, tri.NEUMANN):
         T = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
-        check(T, T_ref, TOL[op] if method != tri.FWD_SUBST or op == tri.F32 else 2e-2, f"strong decay C={C} {tri.METHOD_NAMES[method]}")
+        # fp32 operands: the gate's exponent g - a reaches ~80 here, and its fp32 rounding alone (80 x 1.44 x 2^-24) puts a
+        # relative error of ~5e-6 on the gated keys -- above the elementwise model's fp32 term, so norms only in that mode
+        check(T, T_ref, TOL[op] if method != tri.FWD_SUBST or op == tri.F32 else 2e-2, f"strong decay C={C} {tri.METHOD_NAMES[method]}",
+              op=op, key_abs=SKIP if op == tri.F32 else key_abs_term(inp, 1, C))
 
 
 # ------------------------------------------------------------------ the chunk matrices alone
@@ -870,16 +985,49 @@ XDT = {tri.F32: torch.float32, tri.F16: torch.float16, tri.BF16: torch.bfloat16}
 SOLVE_TOL = {tri.F32: 1e-5, tri.F16: 2e-2, tri.BF16: 2e-2}
 
 
-def check_solve(W_gpu, W_ref, tol, what):
+def check_solve(W_gpu, W_ref, tol, what, C=None, seqlens=None, ctx=None):
+    """W_gpu, W_ref: [B, rows, H, d_x].  The relative Frobenius error is taken per chunk and head (C: chunk size; seqlens: row
+    counts of the packed sequences, each chunked on its own; without C the rows passed are taken as one chunk per head),
+    so that one bad row in a long sequence cannot hide in the norm.  ctx = dict(inp, rhs, gate_kind, op, [scale]) adds the
+    elementwise bound: |dW| <= (E_T + 2u B)|s X| + u |W| + 1e-6, with E_T the elementwise bound of the inverse, B =
+    |T||I + A||T| >= |T| (the scaled inverse is rounded to the operand type once more) and the last term the rounding of
+    W to its storage type."""
     torch.cuda.synchronize()
     Wg = W_gpu.float().cpu().numpy().astype(np.float64)
     assert np.isfinite(Wg).all(), f"{what}: non-finite output"
-    B, Tlen, H, d_x = Wg.shape
-    # relative Frobenius error per (batch, head) over all of that head's rows
-    num = np.sqrt(((Wg - W_ref) ** 2).sum(axis=(1, 3)))
-    den = np.sqrt((W_ref ** 2).sum(axis=(1, 3)))
-    err = (num / den).max()
-    assert err <= tol, f"{what}: rel_fro max {err:.3e} > {tol}"
+    B, rows, H, d_x = Wg.shape
+    if C is None:
+        starts = [0]
+    else:
+        starts, t0 = [], 0
+        for n in (seqlens if seqlens is not None else [rows]):
+            starts += [t0 + c0 for c0 in range(0, int(n), C)]
+            t0 += int(n)
+    if rows:
+        num = np.sqrt(np.add.reduceat(((Wg - W_ref) ** 2).sum(axis=3), starts, axis=1))      # [B, chunks, H]
+        den = np.sqrt(np.add.reduceat((W_ref ** 2).sum(axis=3), starts, axis=1))
+        err = (num / den).max()
+    else:
+        err = 0.0
+    assert err <= tol, f"{what}: rel_fro max {err:.3e} > {tol} (per chunk and head)"
+    if ctx is not None and seqlens is None and C is not None:
+        inp, rhs, gate_kind, op = ctx["inp"], ctx["rhs"], ctx["gate_kind"], ctx["op"]
+        T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], gate_kind, C)        # [B * n_chunk * H, C, C]
+        u = UNIT[op]
+        Ta = np.abs(T_ref)
+        E = elementwise_bound(T_ref, op, key_abs_term(inp, gate_kind, C)) + 2 * u * (Ta @ np.abs(np.linalg.inv(T_ref)) @ Ta)
+        n_chunk = -(-rows // C)
+        E = E.reshape(B, n_chunk, H, C, C)
+        sX = rhs["X"].double().numpy()
+        if ctx.get("scale", True) and rhs.get("row_scale") is not None:
+            sX = sX * rhs["row_scale"].double().numpy()[..., None]
+        pad = np.zeros((B, n_chunk * C, H, d_x))
+        pad[:, :rows] = np.abs(sX)
+        pad = pad.reshape(B, n_chunk, C, H, d_x).transpose(0, 1, 3, 2, 4)                              # [B, n_chunk, H, C, d_x]
+        bound = (E @ pad).transpose(0, 1, 3, 2, 4).reshape(B, n_chunk * C, H, d_x)[:, :rows] + u * np.abs(W_ref) + 1e-6
+        ratio = np.abs(Wg - W_ref) / bound
+        worst = np.unravel_index(np.argmax(ratio), ratio.shape)
+        assert ratio.max() <= 1.0, f"{what}: element {worst} off by {abs(Wg[worst] - W_ref[worst]):.3e}, {ratio.max():.2f} x its bound"
     return err
 
 
@@ -899,7 +1047,8 @@ def test_solve_matches_oracle(idx, kw, method, op):
     g = None if inp["g"] is None else inp["g"].to(DEV)
     W = tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), g, rhs["X"].to(DEV), w.C,
                                 row_scale=rhs["row_scale"].to(DEV), gate_kind=w.gate_kind, method=method)
-    check_solve(W, W_ref, SOLVE_TOL[op], f"cfg{idx} {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}")
+    check_solve(W, W_ref, SOLVE_TOL[op], f"cfg{idx} {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}", C=w.C,
+                ctx=dict(inp=inp, rhs=rhs, gate_kind=w.gate_kind, op=op))
 
 
 @pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
@@ -914,7 +1063,8 @@ def test_solve_c128_stress_recipe(Tlen, method, op):
         W = torch.full(rhs["X"].shape, float("nan"), dtype=XDT[op], device=DEV)
         tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), g, rhs["X"].to(DEV), w.C, row_scale=rhs["row_scale"].to(DEV),
                                 W=W, gate_kind=w.gate_kind, method=method)
-        check_solve(W, W_ref, SOLVE_TOL[op], f"C=128 cfg{idx} Tlen={Tlen} {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}")
+        check_solve(W, W_ref, SOLVE_TOL[op], f"C=128 cfg{idx} Tlen={Tlen} {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}", C=w.C,
+                    ctx=dict(inp=inp, rhs=rhs, gate_kind=w.gate_kind, op=op))
 
 
 @pytest.mark.parametrize("d_x", [8, 64, 72, 128, 200, 256, 512])
@@ -925,7 +1075,8 @@ def test_solve_column_counts(d_x, op):
     W_ref = oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], None, w.gate_kind, w.C)
     W = torch.full(rhs["X"].shape, float("nan"), dtype=XDT[op], device=DEV)
     tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV), rhs["X"].to(DEV), w.C, W=W)
-    check_solve(W, W_ref, SOLVE_TOL[op], f"d_x={d_x}")          # every element written (no NaN left), none beyond
+    check_solve(W, W_ref, SOLVE_TOL[op], f"d_x={d_x}", C=w.C,   # every element written (no NaN left), none beyond
+                ctx=dict(inp=inp, rhs=rhs, gate_kind=w.gate_kind, op=op, scale=False))
 
 
 @pytest.mark.parametrize("C", [16, 32, 64])
@@ -942,7 +1093,7 @@ def test_solve_chunk_sizes_and_short_last_chunk(C, Tlen, gate_kind):
     W = buf[pad:pad + rhs["X"].numel()].view(rhs["X"].shape)
     tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), g, rhs["X"].to(DEV), C, row_scale=rhs["row_scale"].to(DEV),
                             W=W, gate_kind=gate_kind)
-    check_solve(W, W_ref, 2e-2, f"C={C} Tlen={Tlen} gate={gate_kind}")
+    check_solve(W, W_ref, 2e-2, f"C={C} Tlen={Tlen} gate={gate_kind}", C=C, ctx=dict(inp=inp, rhs=rhs, gate_kind=gate_kind, op=tri.BF16))
     assert (buf[:pad] == -7.0).all() and (buf[pad + rhs["X"].numel():] == -7.0).all()
 
 
@@ -1007,7 +1158,7 @@ def test_solve_packed_variable_length_sequences(C, gate_kind):
     W = torch.full(X.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
     tri.gdn_chunk_tri_solve_varlen(K.to(DEV), beta.to(DEV), None if g is None else g.to(DEV), X.to(DEV), seqlens, C,
                                    row_scale=s.to(DEV), W=W, gate_kind=gate_kind)
-    check_solve(W[None], W_ref[None], 2e-2, f"solve varlen C={C} gate={gate_kind}")
+    check_solve(W[None], W_ref[None], 2e-2, f"solve varlen C={C} gate={gate_kind}", C=C, seqlens=seqlens)
 
 
 def test_solve_packed_sequences_with_no_tokens_are_a_no_op():
@@ -1085,9 +1236,9 @@ def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
         E2 = tri.gdn_chunk_tri_solve(K, beta, g, X2, w.C, row_scale=s2, gate_kind=w.gate_kind, method=method)
         torch.cuda.synchronize()
         assert torch.equal(W1, E1) and torch.equal(W2, E2)
-        check_solve(W1, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], None, w.gate_kind, w.C), SOLVE_TOL[op], "rhs 0")
+        check_solve(W1, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], None, w.gate_kind, w.C), SOLVE_TOL[op], "rhs 0", C=w.C)
         check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], r2["row_scale"], w.gate_kind, w.C),
-                    SOLVE_TOL[op], "rhs 1")
+                    SOLVE_TOL[op], "rhs 1", C=w.C)
 
 
 def test_solve_multi_limits():
@@ -1137,7 +1288,7 @@ def test_composed_combinations_match_oracle(case, op):
     assert torch.equal(T, E)
     assert bool((guard[n_mat] == 7.0).all())
     T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], w.gate_kind, w.C)
-    check(T, T_ref, TOL[op], f"composed {case} {tri.DTYPE_NAMES[op]}")
+    check(T, T_ref, TOL[op], f"composed {case} {tri.DTYPE_NAMES[op]}", op=op, key_abs=key_abs_term(inp, w.gate_kind, w.C), method=method)
 
 
 @pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
@@ -1158,9 +1309,9 @@ def test_solve_other_head_dimensions(d_k, C, Tlen, op):
             torch.cuda.synchronize()
             assert torch.equal(W, W1)
             check_solve(W, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], r1["row_scale"], w.gate_kind, C),
-                        SOLVE_TOL[op], f"d_k={d_k} C={C} cfg{idx} rhs 0")
+                        SOLVE_TOL[op], f"d_k={d_k} C={C} cfg{idx} rhs 0", C=C)
             check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], None, w.gate_kind, C),
-                        SOLVE_TOL[op], f"d_k={d_k} C={C} cfg{idx} rhs 1")
+                        SOLVE_TOL[op], f"d_k={d_k} C={C} cfg{idx} rhs 1", C=C)
     with pytest.raises(tri.TriInvError) as e:                               # C = 128 keeps to d_k = 64 / 128
         w = si.workload(1, B=1, Tlen=128, H=2, d_k=96, C=128)
         inp = si.make_inputs(w)
@@ -1187,16 +1338,17 @@ def test_refinement_step_after_every_method(cases, idx, method, op):
         pytest.skip("Neumann product on the stress input: reported, not asserted")
     A32 = torch.from_numpy(c["A"].astype(np.float32))
     T32 = oracle.tri_inv(A32)
-    e0 = check(tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op), T32, TOL[op], "standalone")
-    e1 = check(tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op, flags=tri.FLAG_REFINE1), T32, TOL[op], "standalone + refine")
+    e0 = check(tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op), T32, TOL[op], "standalone", op=op, method=method)
+    e1 = check(tri.tri_inv_ex(A32.to(DEV), method=method, op_dtype=op, flags=tri.FLAG_REFINE1), T32, TOL[op], "standalone + refine", op=op, method=method)
     assert e1 <= max(1.5 * e0, floor), (e0, e1)
     K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
     g = None if inp["g"] is None else inp["g"].to(DEV)
     if w.gate_kind == tri.GATE_PER_CHANNEL and w.C == 128:
         return
-    f0 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=w.gate_kind, method=method, op_dtype=op), c["T"], TOL[op], "fused")
+    f0 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=w.gate_kind, method=method, op_dtype=op), c["T"], TOL[op], "fused",
+               op=op, key_abs=c["key_abs"], method=method)
     f1 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, w.C, gate_kind=w.gate_kind, method=method, op_dtype=op, flags=tri.FLAG_REFINE1),
-               c["T"], TOL[op], "fused + refine")
+               c["T"], TOL[op], "fused + refine", op=op, key_abs=c["key_abs"], method=method)
     assert f1 <= max(1.5 * f0, floor), (f0, f1)
 
 
@@ -1230,13 +1382,13 @@ def test_few_heads_workgroup_map_covers_every_matrix_once(H, n_chunk):
         T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], w.gate_kind, C)
         T = torch.full((n_chunk * H + 1, C, C), 7.0, device=DEV)
         tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=T[:-1], gate_kind=w.gate_kind)
-        check(T[:-1], T_ref, 2e-2, f"H={H} n_chunk={n_chunk} cfg{idx}")
+        check(T[:-1], T_ref, 2e-2, f"H={H} n_chunk={n_chunk} cfg{idx}", key_abs=key_abs_term(inp, w.gate_kind, C))
         assert bool((T[-1] == 7.0).all())
         rhs = si.make_rhs(w, 64, torch.bfloat16)
         W = torch.full(rhs["X"].shape, float("nan"), dtype=torch.bfloat16, device=DEV)
         tri.gdn_chunk_tri_solve(K, beta, g, rhs["X"].to(DEV), C, W=W, gate_kind=w.gate_kind)
         check_solve(W, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], None, w.gate_kind, C), 2e-2,
-                    f"solve H={H} n_chunk={n_chunk} cfg{idx}")
+                    f"solve H={H} n_chunk={n_chunk} cfg{idx}", C=C)
     # packed sequences: the same tensors read as two sequences
     w = si.workload(1, B=1, Tlen=n_chunk * C - 5, H=H, C=C, d_k=d_k)
     inp = si.make_inputs(w)
