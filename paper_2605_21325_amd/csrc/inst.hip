@@ -4,6 +4,9 @@
 // keys of the per-channel kernel still use TRIINV_INST_OP as their operand type).
 #include "dispatch.hpp"
 #include "kernels.hpp"
+#if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
+#include "c128.hpp"
+#endif
 
 #ifndef TRIINV_INST_NB
 #error "compile with -DTRIINV_INST_NB=1|2|4|8 -DTRIINV_INST_OP=0|1|2 [-DTRIINV_INST_FWD=1]"
@@ -113,6 +116,12 @@ template <int METHOD> constexpr unsigned occupancy_pad_bytes()
 
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
+#if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
+    // C = 128, the recursions: one matrix per workgroup of two wavefronts (c128.hpp)
+    if constexpr (!REFINE && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT))
+        return launch_kernel(a.dry, k_gdn_tri_inv_c128<KD, OP, METHOD, DKS>, dim3((unsigned)a.n_mat), dim3(128), 0, a.stream, a.K, a.beta,
+                             a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
+#endif
     return launch_kernel(a.dry, k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
                        dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
                        a.iters, a.out_dt, WPB > 1 ? head_spread(a.H) : 0);

@@ -217,9 +217,10 @@ struct NoHook {
 
 // after_last_fetch: called in the last merge once its tiles of A have been fetched, i.e. when A is no longer needed
 // (a source that builds its tiles from keys held in registers has those registers free from here on).
+// leaves_out: if not null, receives the 16 x 16 diagonal blocks of the result in both orientations ([2 d] = N, [2 d + 1] = T).
 template <int OP, int NB, bool ROOT_T, int LEAF, class ASrc, class Hook = NoHook>
 __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (NB + 1) / 2], float* patch, Lane ln, int leaf_r = 0,
-                                                Hook after_last_fetch = Hook())
+                                                Hook after_last_fetch = Hook(), v4f* leaves_out = nullptr)
 {
     v4f leafN[NB], leafT[NB];
     if constexpr (LEAF == LEAF_FORWARD) {
@@ -332,6 +333,13 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
     }
 #pragma unroll
     for (int d = 0; d < NB; ++d) Tt[tix(d, d)] = result_is_T<NB, ROOT_T>(d, d) ? leafT[d] : leafN[d];
+    if (leaves_out != nullptr) {
+#pragma unroll
+        for (int d = 0; d < NB; ++d) {
+            leaves_out[2 * d] = leafN[d];
+            leaves_out[2 * d + 1] = leafT[d];
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
