@@ -212,14 +212,14 @@ __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t r
 #pragma unroll
             for (int d = 0; d < 4; ++d)
                 if (d >= c) acc = tn<OP>(a21[b][d], t11[tix(d, c)], acc);
-            P[b] = pack<OP>(acc);
+            P[b] = negated<OP>(pack<OP>(acc));  // the sign of -T22 (A21 T11)
         }
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             v4f acc = zero4();
 #pragma unroll
             for (int b = 0; b <= a; ++b) acc = tn<OP>(t22[tix(a, b)], P[b], acc);
-            Wc[k][a] = -acc;
+            Wc[k][a] = acc;
         }
     }
 }
@@ -245,13 +245,14 @@ __device__ __forceinline__ void c128_invert_and_store(char* lds, const void* Kc,
             for (int a = 0; a < 4; ++a) mail[(4 * k + a) * 64 + lane] = Wc[k][a];
     }
     __syncthreads();  // wave 0's tiles of W are in LDS, and nobody reads the keys any more
+    zero_strip_patch(strip, ln);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         v4f row[8];
         if (W == 0) {
 #pragma unroll
             for (int j = 0; j <= i; ++j) row[j] = D[tix(i, j)];
-            store_strip<8>(Tm, i, row, [](int) { return false; }, strip, ln);
+            store_strip<8, true>(Tm, i, row, [](int) { return false; }, strip, ln);
         } else {
             row[0] = mail[i * 64 + lane];
             row[1] = Wc[0][i];
@@ -259,7 +260,7 @@ __device__ __forceinline__ void c128_invert_and_store(char* lds, const void* Kc,
             row[3] = mail[(4 + i) * 64 + lane];
 #pragma unroll
             for (int j = 0; j <= i; ++j) row[4 + j] = D[tix(i, j)];
-            store_strip<8>(Tm, 4 + i, row, [](int j) { return j >= 4; }, strip, ln);
+            store_strip<8, true>(Tm, 4 + i, row, [](int j) { return j >= 4; }, strip, ln);
         }
     }
 }

@@ -22,7 +22,7 @@ namespace triinv {
 template <int OP>
 __device__ __forceinline__ void leaf_block_recursive(v4f LN, v4f LT, v4f& XN, v4f& XT, Lane ln)
 {
-    const Opnd<OP> LNo = pack<OP>(LN), LTo = pack<OP>(LT);
+    const Opnd<OP> LNo = negated<OP>(pack<OP>(LN)), LTo = negated<OP>(pack<OP>(LT));  // -A: every level subtracts D_o A D_e
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int a = 4 * ln.q + r, b = ln.n;  // XN[r] = X[a][b], XT[r] = X[b][a]
@@ -47,10 +47,10 @@ __device__ __forceinline__ void leaf_block_recursive(v4f LN, v4f LT, v4f& XN, v4
         const Opnd<OP> eNo = masked<OP>(pack<OP>(XN), Me);     // D_e        (N)
         const Opnd<OP> oTo = masked<OP>(pack<OP>(XT), Mo);     // D_o^T      (T)
         // A restricted to the 2b-block diagonal: D_o A D_e then has no entry outside those blocks
-        const v4f P1 = tn<OP>(masked<OP>(LTo, Ms), eNo, zero4());   // A D_e
-        const v4f P2 = tn<OP>(masked<OP>(LNo, Ms), oTo, zero4());   // A^T D_o^T = (D_o A)^T
-        XN -= tn<OP>(oTo, pack<OP>(P1), zero4());                   // D_o A D_e
-        XT -= tn<OP>(eNo, pack<OP>(P2), zero4());                   // (D_o A D_e)^T
+        const v4f P1 = tn<OP>(masked<OP>(LTo, Ms), eNo, zero4());   // -A D_e
+        const v4f P2 = tn<OP>(masked<OP>(LNo, Ms), oTo, zero4());   // -A^T D_o^T = -(D_o A)^T
+        XN = tn<OP>(oTo, pack<OP>(P1), XN);                         // X - D_o A D_e
+        XT = tn<OP>(eNo, pack<OP>(P2), XT);                         // (X - D_o A D_e)^T
     }
 }
 
@@ -289,14 +289,14 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
                         v4f acc = zero4();
 #pragma unroll
                         for (int d = c; d < h; ++d) acc = tn<OP>(a21[b * h + d], t11[tix(d, c)], acc);
-                        P[b] = pack<OP>(acc);
+                        P[b] = negated<OP>(pack<OP>(acc));  // the sign of -T22 (A21 T11)
                     }
 #pragma unroll
                     for (int a = 0; a < h; ++a) {
                         v4f acc = zero4();
 #pragma unroll
                         for (int b = 0; b <= a; ++b) acc = tn<OP>(t22[tix(a, b)], P[b], acc);
-                        Tt[tix(mid + a, lo + c)] = -acc;
+                        Tt[tix(mid + a, lo + c)] = acc;
                     }
                 }
             } else {
@@ -309,14 +309,14 @@ __device__ __forceinline__ void block_recursive(const ASrc& A, v4f (&Tt)[NB * (N
                         v4f acc = zero4();
 #pragma unroll
                         for (int b = 0; b <= a; ++b) acc = tn<OP>(a21[b * h + d], t22[tix(a, b)], acc);
-                        Q[d] = pack<OP>(acc);
+                        Q[d] = negated<OP>(pack<OP>(acc));
                     }
 #pragma unroll
                     for (int c = 0; c < h; ++c) {
                         v4f acc = zero4();
 #pragma unroll
                         for (int d = c; d < h; ++d) acc = tn<OP>(t11[tix(d, c)], Q[d], acc);
-                        Tt[tix(mid + a, lo + c)] = -acc;
+                        Tt[tix(mid + a, lo + c)] = acc;
                     }
                 }
             }

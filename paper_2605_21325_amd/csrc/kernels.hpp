@@ -107,9 +107,11 @@ template <> __device__ __forceinline__ v4f gram_step<OP_BF16>(v8bf a, v8bf b, v4
 // beta / g of one chunk's tokens in the two index patterns a lane needs (by its column n, by its
 // rows 4q + r), and the scalar gate applied to a Gram tile:
 //   A_ij = beta_i exp(g_i - g_j) S_ij for i > j, else 0      (paper Table 1, GDN / DeltaNet rows).
+// g is kept multiplied by log2(e) (done once per token when the values are staged), so that the gate of an element is
+// one subtraction and one exp2; without a gate g = 0 and exp2(0) = 1 exactly, so that kind needs no code of its own.
 template <int NB> struct GateVec {
     static constexpr int C = 16 * NB;
-    float beta_n[NB], g_n[NB];
+    float beta_n[NB], g_n[NB];   // g_*: g log2(e)
     v4f beta_q[NB], g_q[NB];
     bool gated;
 
@@ -151,7 +153,7 @@ template <int NB> struct GateVec {
         for (int k = 0; k < RAW; ++k) {
             if (C < 64 && l >= C) continue;
             lds[l + 64 * k] = raw_b[k];
-            lds[C + l + 64 * k] = gated ? raw_g[k] : 0.f;
+            lds[C + l + 64 * k] = gated ? raw_g[k] * 1.44269504088896340736f : 0.f;
         }
         wave_lds_sync();
 #pragma unroll
@@ -178,11 +180,8 @@ template <int NB> struct GateVec {
         for (int r = 0; r < 4; ++r) {
             // N: element (row 16i + 4q + r, col 16j + n);  T: element (row 16i + n, col 16j + 4q + r)
             const float b = TR ? beta_n[i] : beta_q[i][r];
-            float w = b;
-            if (gated) {
-                const float d = TR ? (g_n[i] - g_q[j][r]) : (g_q[i][r] - g_n[j]);
-                w = b * __builtin_amdgcn_exp2f(d * 1.44269504088896340736f);  // exp(d) = exp2(d log2 e)
-            }
+            const float d = TR ? (g_n[i] - g_q[j][r]) : (g_q[i][r] - g_n[j]);  // (g_i - g_j) log2 e
+            const float w = b * __builtin_amdgcn_exp2f(d);                      // beta_i exp(g_i - g_j)
             const bool low = (i != j) || (TR ? (ln.n > 4 * ln.q + r) : (4 * ln.q + r > ln.n));
             a[r] = low ? w * s[r] : 0.f;
         }
@@ -581,21 +580,36 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_buffer(Out Tm, int C)
 {
     return __builtin_amdgcn_make_buffer_rsrc(Tm.base, 0, C * C * (Tm.dt == OP_F32 ? 4 : 2), 0x00020000);  // raw buffer
 }
-__device__ __forceinline__ void stream_store(v4u v, __amdgpu_buffer_rsrc_t out, int byte_offset)
+// byte offset = lane_offset (a vector register, the same for every store of a strip) + uniform_offset (a scalar)
+__device__ __forceinline__ void stream_store(v4u v, __amdgpu_buffer_rsrc_t out, int lane_offset, int uniform_offset = 0)
 {
-    __builtin_amdgcn_raw_buffer_store_b128(v, out, byte_offset, 0, CACHE_SC0_SC1_NT);
+    __builtin_amdgcn_raw_buffer_store_b128(v, out, lane_offset, uniform_offset, CACHE_SC0_SC1_NT);
 }
-__device__ __forceinline__ void stream_store(v4f v, __amdgpu_buffer_rsrc_t out, int byte_offset)
+__device__ __forceinline__ void stream_store(v4f v, __amdgpu_buffer_rsrc_t out, int lane_offset, int uniform_offset = 0)
 {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), out, byte_offset, 0, CACHE_SC0_SC1_NT);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), out, lane_offset, uniform_offset, CACHE_SC0_SC1_NT);
 }
 __device__ __forceinline__ void stream_store(float v, float* p) { __builtin_nontemporal_store(v, p); }
 
 constexpr int STORE_LD = 16 * 8 + 4;                  // row stride of the patch (fits C = 128), floats
 constexpr int STORE_LDS_FLOATS = 16 * STORE_LD;
 
+// Zero the strip patch.  Strips stored afterwards in ascending order then find zeros right of their diagonal tile (strip
+// i only writes tiles 0..i), which spares them a select per stored element.
+__device__ __forceinline__ void zero_strip_patch(float* lds, Lane ln)
+{
+    const int lane = 16 * ln.q + ln.n;
+#pragma unroll
+    for (int k = 0; k < (STORE_LDS_FLOATS / 4 + 63) / 64; ++k) {
+        const int p = 64 * k + lane;
+        if (p < STORE_LDS_FLOATS / 4) *reinterpret_cast<v4f*>(&lds[4 * p]) = zero4();
+    }
+    wave_lds_sync();
+}
+
 // One strip: tiles (i, 0..i) in row[0..i], tile j in T orientation when row_is_t(j).
-template <int NB, class RowIsT>
+// ZEROED: the patch holds zeros right of tile i (zero_strip_patch, then strips in ascending order).
+template <int NB, bool ZEROED = false, class RowIsT>
 __device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB], RowIsT row_is_t, float* lds, Lane ln,
                                             float diag = 1.f)
 {
@@ -634,8 +648,8 @@ __device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB],
             const int rr = RPI * k + lane / LPR, cc = 4 * (lane % LPR);
             // unconditional read (columns right of the diagonal tile hold stale patch contents), then a select
             v4f v = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc]);
-            if (cc >= 16 * (i + 1)) v = zero4();
-            stream_store(v, out, ((16 * i + rr) * C + cc) * 4);
+            if (!ZEROED && cc >= 16 * (i + 1)) v = zero4();
+            stream_store(v, out, ((lane / LPR) * C + cc) * 4, (16 * i + RPI * k) * C * 4);
         }
     } else {
         // 16-bit result: 8 elements (16 bytes) per lane, C/8 lanes per row
@@ -646,11 +660,11 @@ __device__ __forceinline__ void store_strip(Out Tm, int i, const v4f (&row)[NB],
             if (RPI > 16 && rr >= 16) continue;  // C = 16: more lanes than the strip has 16-byte pieces
             v4f a = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc]);
             v4f b = *reinterpret_cast<const v4f*>(&lds[rr * STORE_LD + cc + 4]);
-            if (cc >= 16 * (i + 1)) a = zero4();
-            if (cc + 4 >= 16 * (i + 1)) b = zero4();
+            if (!ZEROED && cc >= 16 * (i + 1)) a = zero4();
+            if (!ZEROED && cc + 4 >= 16 * (i + 1)) b = zero4();
             const v4u p = Tm.dt == OP_F16 ? v4u{pack2_f16(a[0], a[1]), pack2_f16(a[2], a[3]), pack2_f16(b[0], b[1]), pack2_f16(b[2], b[3])}
                                           : v4u{pack2_bf16(a[0], a[1]), pack2_bf16(a[2], a[3]), pack2_bf16(b[0], b[1]), pack2_bf16(b[2], b[3])};
-            stream_store(p, out, ((16 * i + rr) * C + cc) * 2);
+            stream_store(p, out, ((lane / LPR) * C + cc) * 2, (16 * i + RPI * k) * C * 2);
         }
     }
     wave_lds_sync();
@@ -660,12 +674,13 @@ template <int NB, class IsT>
 __device__ __forceinline__ void store_result(Out Tm, const v4f (&Tt)[NB * (NB + 1) / 2], IsT is_t, float* lds, Lane ln,
                                              float diag = 1.f)
 {
+    zero_strip_patch(lds, ln);
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         v4f row[NB];
 #pragma unroll
         for (int j = 0; j <= i; ++j) row[j] = Tt[tix(i, j)];
-        store_strip<NB>(Tm, i, row, [&](int j) { return is_t(i, j); }, lds, ln, diag);
+        store_strip<NB, true>(Tm, i, row, [&](int j) { return is_t(i, j); }, lds, ln, diag);
     }
 }
 
