@@ -104,10 +104,12 @@ template <int W> __host__ __device__ constexpr int c128_col(int k) { return W ==
 // keys_loaded(): called between the issue of the key loads and their first use (a place for further independent memory
 // operations).  block_done(): called right after the workgroup barrier that follows the diagonal blocks, when this
 // wave's block D is final (a place to send it on its way while the off-diagonal block is formed).
-template <int KD, int OP, int METHOD, int DKS, int W, class Hook, class Hook2>
+// keys_done(): called in the second phase once this wave's tiles of A21 exist: the keys' registers and the gate's are
+// free from there on, and 40 tile products follow (a place to start loads whose data is needed after them).
+template <int KD, int OP, int METHOD, int DKS, int W, class Hook, class Hook2, class Hook3 = NoHook>
 __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
                                             int64_t tok_stride, int valid, int aux, Lane ln, v4f (&D)[10], v4f (&Wc)[2][4],
-                                            Hook keys_loaded, Hook2 block_done)
+                                            Hook keys_loaded, Hook2 block_done, Hook3 keys_done = Hook3())
 {
     typedef typename KeyVec<KD>::type kvec;
     typedef C128Lds<KD, OP, DKS, METHOD> LY;
@@ -187,6 +189,7 @@ __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t r
             }
         }
     }
+    keys_done();
     // the factors: own block from registers, the other wave's from LDS
     Opnd<OP> t11[10], t22[10];
 #pragma unroll

@@ -1,0 +1,318 @@
+// C = 128, the inverse applied instead of stored (W = (I + A)^{-1} diag(s) X, paper Sec. 1 Eq. 3; direction of the fused
+// layer kernel of Sec. 5.2) on the two-wavefront layout of c128.hpp.  After the recursion the 36 lower tiles of the
+// inverse are spread over the two waves; each wave scales its 18 tiles' columns by s, rounds them to the operand type
+// and publishes them in LDS (row-major 16 x 16 tiles: a tile written in either orientation is read back in T
+// orientation, the left-factor form of tn(), with one access per lane).  The right-hand side is split by COLUMNS: a
+// lane owns the 8 bytes of consecutive columns one load brings (4 for 16-bit elements, 2 for fp32), 16 lanes cover one
+// 128-byte line of a row, and the 64- (32-) column groups go to the two waves alternately, so that at d_x = 128 each
+// wave reads half of every row of X, multiplies all 36 tiles into it and writes half of every row of W: the same
+// bytes and the same number of tile products on both waves.
+#pragma once
+#include <type_traits>
+#include "c128.hpp"
+#include "solve.hpp"
+
+namespace triinv {
+
+// Eight bytes of one row of X as stored.
+template <int OP> struct XHalf;
+template <> struct XHalf<OP_F32> { v2f f; };
+template <> struct XHalf<OP_F16> { v2u u; };
+template <> struct XHalf<OP_BF16> { v2u u; };
+
+template <int OP> __device__ __forceinline__ XHalf<OP> load_xh(const char* p)
+{
+    if constexpr (OP == OP_F32) {
+        return {*reinterpret_cast<const v2f*>(p)};
+    } else {
+        return {*reinterpret_cast<const v2u*>(p)};
+    }
+}
+
+// Column tile c of a 16-row tile row of X as a matrix-core operand: rows 4q + r of this lane's column VEC n + c.
+template <int OP> __device__ __forceinline__ Opnd<OP> xh_operand(const XHalf<OP> (&row)[4], int c)
+{
+    if constexpr (OP == OP_F32) {
+        return {v4f{row[0].f[c], row[1].f[c], row[2].f[c], row[3].f[c]}};
+    } else {
+        const int d = c >> 1;
+        uint32_t lo, hi;
+        if (c & 1) {
+            lo = (row[0].u[d] >> 16) | (row[1].u[d] & 0xffff0000u);
+            hi = (row[2].u[d] >> 16) | (row[3].u[d] & 0xffff0000u);
+        } else {
+            lo = (row[0].u[d] & 0xffffu) | (row[1].u[d] << 16);
+            hi = (row[2].u[d] & 0xffffu) | (row[3].u[d] << 16);
+        }
+        Opnd<OP> o;
+        o.x = __builtin_bit_cast(decltype(o.x), v2u{lo, hi});
+        return o;
+    }
+}
+
+// One right-hand side, seen by one wave: 128 rows, column groups of 16 * VEC columns.  X and W are addressed through
+// buffer descriptors based at the chunk's first row of this head with 32-bit byte offsets (128 rows of H * d_x elements
+// stay far below 2^31 bytes; the launcher checks): one offset register per row instead of a 64-bit pointer.
+template <int OP> struct RhsHalf {
+    static constexpr int ESZ = OP == OP_F32 ? 4 : 2;
+    static constexpr int VEC = 8 / ESZ;
+    static constexpr int GW = 16 * VEC;
+    static constexpr int CACHE_NT = 2;  // non-temporal stores of W (the streaming policy of T's stores measured slower here)
+    __amdgpu_buffer_rsrc_t xb, wb;
+    int row_bytes;
+    int d_x, valid;
+    Lane ln;
+    XHalf<OP> raw[8][4];
+
+    __device__ __forceinline__ void init(const RhsArgs& a, int64_t tok0, int h, int H, int valid_, Lane ln_)
+    {
+        ln = ln_;
+        d_x = a.d_x;
+        valid = valid_;
+        row_bytes = H * d_x * ESZ;
+        const int64_t e0 = (tok0 * H + h) * (int64_t)d_x * ESZ;
+        // the descriptors span the chunk's real rows: whatever lies beyond is neither read nor written
+        const int span = (valid - 1) * row_bytes + d_x * ESZ;
+        xb = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(a.X)) + e0, 0, span, 0x00020000);
+        wb = __builtin_amdgcn_make_buffer_rsrc(static_cast<char*>(a.W) + e0, 0, span, 0x00020000);
+    }
+    __device__ __forceinline__ bool active(int gi) const { return GW * gi + VEC * ln.n < d_x; }
+    __device__ __forceinline__ int n_group() const { return (d_x + GW - 1) / GW; }
+
+    // Byte offset of (row 16 j + 4 q + r, this lane's columns) = lane part (one register) + uniform part (a scalar; the
+    // hardware's range check does not see it, so it is only used for tile rows that lie inside the chunk entirely).
+    // The one tile row a short last chunk may cut is handled lane by lane (rows beyond the last token read that token:
+    // they only meet zero columns of the inverse); tile rows beyond it are not touched at all.
+    __device__ __forceinline__ int lane_offset(int gi) const
+    {
+        return 4 * ln.q * row_bytes + (active(gi) ? (GW * gi + VEC * ln.n) * ESZ : 0);
+    }
+
+    __device__ __forceinline__ void issue(int gi)
+    {
+        const int lo = lane_offset(gi);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (16 * j + 16 <= valid) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    raw[j][r] = __builtin_bit_cast(XHalf<OP>, __builtin_amdgcn_raw_buffer_load_b64(xb, lo, (16 * j + r) * row_bytes, 0));
+            } else if (16 * j < valid) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = 16 * j + 4 * ln.q + r;
+                    const int rc = row < valid ? row : valid - 1;
+                    raw[j][r] = __builtin_bit_cast(XHalf<OP>, __builtin_amdgcn_raw_buffer_load_b64(xb, lo + (rc - 4 * ln.q) * row_bytes, 0, 0));
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) raw[j][r] = __builtin_bit_cast(XHalf<OP>, v2u{0u, 0u});
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store(int gi, int i, const v4f (&acc)[VEC])
+    {
+        if (!active(gi) || 16 * i >= valid) return;
+        const int lo = lane_offset(gi);
+        const bool whole = 16 * i + 16 <= valid;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            v2u v;
+            if constexpr (OP == OP_F32) {
+                v = __builtin_bit_cast(v2u, v2f{acc[0][r], acc[1][r]});
+            } else if constexpr (OP == OP_F16) {
+                v = v2u{pack2_f16(acc[0][r], acc[1][r]), pack2_f16(acc[2][r], acc[3][r])};
+            } else {
+                v = v2u{pack2_bf16(acc[0][r], acc[1][r]), pack2_bf16(acc[2][r], acc[3][r])};
+            }
+            if (whole || 16 * i + 4 * ln.q + r < valid) __builtin_amdgcn_raw_buffer_store_b64(v, wb, lo, (16 * i + r) * row_bytes, CACHE_NT);
+        }
+    }
+};
+
+// Published tiles: element type = operand type, 16 rows of TILE_LD elements.
+template <int OP> struct TileLds {
+    typedef typename std::conditional<OP == OP_F32, float, uint16_t>::type elem;
+    static constexpr int TILE_LD = 20;
+    static constexpr int TILE_ELEMS = 16 * TILE_LD;
+    static constexpr int BYTES = 36 * TILE_ELEMS * (int)sizeof(elem);
+
+    static __device__ __forceinline__ elem narrow(float x)
+    {
+        if constexpr (OP == OP_F32) {
+            return x;
+        } else if constexpr (OP == OP_F16) {
+            return (uint16_t)(pack2_f16(x, 0.f) & 0xffffu);
+        } else {
+            return (uint16_t)(pack2_bf16(x, 0.f) & 0xffffu);
+        }
+    }
+    // t in N orientation (t[r] = M[4q + r][n])
+    static __device__ __forceinline__ void write_n(elem* tile, v4f t, Lane ln)
+    {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tile[(4 * ln.q + r) * TILE_LD + ln.n] = narrow(t[r]);
+    }
+    // t in T orientation (t[r] = M[n][4q + r])
+    static __device__ __forceinline__ void write_t(elem* tile, v4f t, Lane ln)
+    {
+        const Opnd<OP> o = pack<OP>(t);
+        *reinterpret_cast<Opnd<OP>*>(&tile[ln.n * TILE_LD + 4 * ln.q]) = o;
+    }
+    static __device__ __forceinline__ Opnd<OP> read_t(const elem* tile, Lane ln)
+    {
+        return *reinterpret_cast<const Opnd<OP>*>(&tile[ln.n * TILE_LD + 4 * ln.q]);
+    }
+};
+
+template <int KD, int OP, int DKS, int METHOD, int NRHS> struct C128SolveLds {
+    typedef C128Lds<KD, OP, DKS, METHOD> INV;
+    static constexpr int TILES = 0;  // after the recursion, in place of the keys: one set of 36 tiles per right-hand side
+    static constexpr int SCALE = INV::BYTES > NRHS * TileLds<OP>::BYTES ? INV::BYTES : NRHS * TileLds<OP>::BYTES;  // 128 floats per wave
+    static constexpr int BYTES = SCALE + 2 * 128 * 4;
+};
+
+// NRHS right-hand sides share the inverse: its tiles are published once per right-hand side (their columns scaled by
+// that side's s), all sets before the one barrier, so that nothing of the inverse stays in registers afterwards.
+template <int KD, int OP, int METHOD, int DKS, int W, int NRHS>
+__device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
+                                                      int64_t tok_stride, const RhsList& rhs, int64_t tok0, int h, int H, int valid,
+                                                      int aux, Lane ln)
+{
+    typedef C128SolveLds<KD, OP, DKS, METHOD, NRHS> LY;
+    typedef TileLds<OP> TL;
+    typedef typename TL::elem elem;
+    const int lane = 16 * ln.q + ln.n;
+    // the row scales of this lane's two tokens, every right-hand side: in flight while the chunk is inverted
+    float raw_s[NRHS][2];
+#pragma unroll
+    for (int k = 0; k < NRHS; ++k)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int row = lane + 64 * t;
+            const int rc = row < valid ? row : valid - 1;
+            raw_s[k][t] = rhs.r[k].scale ? rhs.r[k].scale[(tok0 + rc) * H + h] : 1.f;
+        }
+    v4f D[10], Wc[2][4];
+    RhsHalf<OP> x;
+    x.init(rhs.r[0], tok0, h, H, valid, ln);
+    c128_invert<KD, OP, METHOD, DKS, W>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
+        // X's first column group: requested as soon as the keys' registers are free, in flight during the last 40 tile
+        // products of the recursion and while the inverse's tiles are published
+        __builtin_amdgcn_sched_barrier(0);
+        if (W < x.n_group()) x.issue(W);
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    // the diagonal tiles in exact unit-triangular form
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int rr = W == 0 ? 4 * ln.q + r : ln.n, cc = W == 0 ? ln.n : 4 * ln.q + r;
+            D[tix(d, d)][r] = (rr == cc) ? 1.f : ((rr > cc) ? D[tix(d, d)][r] : 0.f);
+        }
+    elem* tiles = reinterpret_cast<elem*>(lds + LY::TILES);
+    float* sc = reinterpret_cast<float*>(lds + LY::SCALE) + 128 * W;
+    constexpr int VEC = RhsHalf<OP>::VEC;
+    __syncthreads();  // nobody reads the keys any more
+#pragma unroll
+    for (int k = 0; k < NRHS; ++k) {
+        // s by the two index patterns
+        sc[lane] = raw_s[k][0];
+        sc[lane + 64] = raw_s[k][1];
+        wave_lds_sync();
+        float s_n[8];
+        v4f s_q[4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s_n[j] = sc[16 * j + ln.n];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s_q[j] = *reinterpret_cast<const v4f*>(&sc[64 + 16 * j + 4 * ln.q]);
+        wave_lds_sync();
+        // this wave's 18 tiles, columns scaled by s, rounded to the operand type
+        elem* set = tiles + k * 36 * TL::TILE_ELEMS;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                if (W == 0)
+                    TL::write_n(set + tix(i, j) * TL::TILE_ELEMS, D[tix(i, j)] * s_n[j], ln);
+                else
+                    TL::write_t(set + tix(4 + i, 4 + j) * TL::TILE_ELEMS, D[tix(i, j)] * s_q[j], ln);
+            }
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int col = c128_col<W>(c);
+                TL::write_n(set + tix(4 + i, col) * TL::TILE_ELEMS, Wc[c][i] * s_n[col], ln);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // tile row by tile row: scaled all at once the tiles take twice their registers
+        }
+    }
+    __syncthreads();  // every tile is in LDS
+#pragma unroll
+    for (int k = 0; k < NRHS; ++k) {
+        if (k > 0) {
+            x.init(rhs.r[k], tok0, h, H, valid, ln);
+            __builtin_amdgcn_sched_barrier(0);
+            if (W < x.n_group()) x.issue(W);
+        }
+        const int n_group = x.n_group();
+#pragma unroll 1
+        for (int gi = W; gi < n_group;) {
+            Opnd<OP> xo[8][VEC];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) xo[j][c] = xh_operand<OP>(x.raw[j], c);
+            const int cur = gi;
+            gi += 2;
+            // the tiles are read back strip by strip (held in registers they would cost a wavefront per SIMD; the opaque
+            // pointer keeps the reads inside this loop)
+            const elem* set = tiles + k * 36 * TL::TILE_ELEMS;
+            asm volatile("" : "+v"(set));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                v4f acc[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = zero4();
+#pragma unroll
+                for (int j = 0; j <= i; ++j) {
+                    const Opnd<OP> t = TL::read_t(set + tix(i, j) * TL::TILE_ELEMS, ln);
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(t, xo[j][c], acc[c]);
+                }
+                x.store(cur, i, acc);
+                __builtin_amdgcn_sched_barrier(0);  // one strip's tile reads at a time (all 36 hoisted to the top cost 72 registers)
+            }
+            if (gi < n_group) x.issue(gi);  // (d_x > 128 only; started earlier it would cost the registers of a second group)
+        }
+    }
+}
+
+// Fused kernel, scalar / no-gate kinds, C = 128, d_k = 64 or 128: blocked or mixed recursion, then the inverse applied to
+// one or two right-hand sides.  One workgroup of two wavefronts per chunk matrix.
+template <int KD, int OP, int METHOD, int DKS, int NRHS>
+__global__ __launch_bounds__(128) void k_gdn_tri_solve_c128(const void* __restrict__ K, const float* __restrict__ beta,
+                                                            const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
+                                                            int H, int d_k, int aux)
+{
+    constexpr int C = 128;
+    __shared__ __attribute__((aligned(16))) char lds[C128SolveLds<KD, OP, DKS, METHOD, NRHS>::BYTES];
+    const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
+    const uint32_t bc = (uint32_t)m / (uint32_t)H;
+    const int h = (int)((uint32_t)m - bc * (uint32_t)H);
+    const ChunkPos pos = locate_chunk<C>(map, bc);
+    const int64_t tok0 = pos.tok0;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const Lane ln = lane_id();
+    const int64_t esz = (KD == OP_F32) ? 4 : 2;
+    const void* Kc = static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz;
+    const float* bcp = beta + tok0 * H + h;
+    const float* gcp = g ? g + tok0 * H + h : nullptr;
+    if (w == 0)
+        c128_invert_and_apply<KD, OP, METHOD, DKS, 0, NRHS>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
+    else
+        c128_invert_and_apply<KD, OP, METHOD, DKS, 1, NRHS>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
+}
+
+}  // namespace triinv

@@ -2,6 +2,9 @@
 // operand type TRIINV_INST_OP) pair: blocked and mixed recursion.
 #include "dispatch.hpp"
 #include "solve.hpp"
+#if TRIINV_INST_NB == 8
+#include "c128_solve.hpp"
+#endif
 
 #ifndef TRIINV_INST_NB
 #error "compile with -DTRIINV_INST_NB=1|2|4|8 -DTRIINV_INST_OP=0|1|2"
@@ -34,6 +37,21 @@ constexpr bool HAS_PAIR = NB <= 4;
 template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
 {
     const GdnArgs& f = a.f;
+#if TRIINV_INST_NB == 8
+    // C = 128, two right-hand sides: one chunk per workgroup of two wavefronts with the right-hand sides split by columns
+    // (c128_solve.hpp).  A single right-hand side keeps the one-wavefront kernel below: its 256-byte row pieces stream
+    // faster than the 128-byte pieces of the column split (data movers with the two access patterns: 142 against 176 us
+    // on the stress workload; the kernels: 165 against 179 us).
+    if (a.n_rhs == 2) {
+        for (int k = 0; k < a.n_rhs; ++k)  // its 32-bit row offsets: 128 rows of H * d_x elements
+            if ((int64_t)f.H * a.d_x[k] * (OP == OP_F32 ? 4 : 2) * 128 >= (1LL << 31)) return 1;
+        if constexpr (OP != OP_F32)  // two sets of fp32 tiles do not fit the LDS budget of three workgroups per compute unit
+            return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K,
+                                 f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+        return 1;
+    }
+#endif
+    {
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {
         return launch_kernel(f.dry, k_gdn_tri_solve<KD, OP, NB, METHOD, DKS, WPB, XPOS, 1>, grid, block, 0, f.stream, f.K, f.beta, f.g,
@@ -44,6 +62,7 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
                            rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters, WPB > 1 ? head_spread(f.H) : 0);
     }
     return 1;
+    }
 }
 
 template <int KD, int DKS> static int gdn_method(const SolveArgs& a)

@@ -1220,11 +1220,13 @@ def test_solve_full_size_workload(idx):
 
 @pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
 @pytest.mark.parametrize("idx,kw", [(1, dict(Tlen=300, H=4)), (3, dict(B=2, Tlen=128, H=3)), (4, dict(Tlen=200, H=4, C=32)),
-                                    (1, dict(Tlen=96, H=2, C=16))])
+                                    (1, dict(Tlen=96, H=2, C=16)), (4, dict(Tlen=300, H=3)), (1, dict(Tlen=256, H=2, C=128, d_k=64))])
 def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
     # two right-hand sides of different widths and scales in one launch: each result is what a launch of its own gives
-    # (bit for bit: the same kernels' arithmetic), and matches the oracle
+    # (bit for bit at C <= 64: the same kernels' arithmetic), and matches the oracle
     w = si.workload(idx, **kw)
+    if w.C == 128 and op == tri.F32:
+        pytest.skip("two right-hand sides at C = 128 are built for 16-bit operands (two sets of fp32 tiles do not fit the LDS)")
     inp = si.make_inputs(w)
     r1, r2 = si.make_rhs(w, 128, XDT[op]), si.make_rhs(w, 72, XDT[op], seed_offset=1)
     K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
@@ -1235,7 +1237,8 @@ def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
         E1 = tri.gdn_chunk_tri_solve(K, beta, g, X1, w.C, gate_kind=w.gate_kind, method=method)
         E2 = tri.gdn_chunk_tri_solve(K, beta, g, X2, w.C, row_scale=s2, gate_kind=w.gate_kind, method=method)
         torch.cuda.synchronize()
-        assert torch.equal(W1, E1) and torch.equal(W2, E2)
+        if w.C < 128:       # (at C = 128 the pair runs on two wavefronts per chunk, the single launch on one: same method, other kernel)
+            assert torch.equal(W1, E1) and torch.equal(W2, E2)
         check_solve(W1, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], None, w.gate_kind, w.C), SOLVE_TOL[op], "rhs 0", C=w.C)
         check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], r2["row_scale"], w.gate_kind, w.C),
                     SOLVE_TOL[op], "rhs 1", C=w.C)
@@ -1244,8 +1247,8 @@ def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
 def test_solve_multi_limits():
     w, inp, rhs = solve_case(4, 64, tri.BF16, Tlen=256, H=2)
     K, beta, X = inp["K"].to(DEV), inp["beta"].to(DEV), rhs["X"].to(DEV)
-    with pytest.raises(tri.TriInvError) as e:                                 # two right-hand sides at C = 128
-        tri.gdn_chunk_tri_solve_multi(K, beta, None, [X, X.clone()], 128, gate_kind=tri.GATE_NONE)
+    with pytest.raises(tri.TriInvError) as e:                                 # two right-hand sides at C = 128, fp32 operands
+        tri.gdn_chunk_tri_solve_multi(K, beta, None, [X.float(), X.float()], 128, gate_kind=tri.GATE_NONE)
     assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:                                 # three
         tri.gdn_chunk_tri_solve_multi(K, beta, None, [X, X.clone(), X.clone()], 64, gate_kind=tri.GATE_NONE)
