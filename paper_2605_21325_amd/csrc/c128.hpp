@@ -100,6 +100,37 @@ template <int METHOD> constexpr int c128_leaf()
 // {0, 3}, wave 1 columns {1, 2} (k = 0, 1 in that order).
 template <int W> __host__ __device__ constexpr int c128_col(int k) { return W == 0 ? (k == 0 ? 0 : 3) : (k == 0 ? 1 : 2); }
 
+template <int OP, int W>
+__device__ __forceinline__ void c128_merge(const Opnd<OP> (&a21)[4][4], const v4f (&D)[10], v4f (&Wc)[2][4], const Opnd<OP>* t11_lds,
+                                           const Opnd<OP>* t22_lds, Lane ln);
+
+// A wave's own 64 x 64 diagonal block: the C = 64 recursion on the tile source `diag`; wave 0 produces an N block (the
+// right factor of the merge), wave 1 a T block (the left factor); the packed tiles the other wave needs go to LDS (no
+// barrier here).  small: the wave's private LDS area.
+template <int OP, int METHOD, int W, class DiagSrc>
+__device__ __forceinline__ void c128_diagonal_block(const DiagSrc& diag, v4f (&D)[10], float* small, Opnd<OP>* t11_lds, Opnd<OP>* t22_lds,
+                                                    int aux, Lane ln)
+{
+    const int lane = 16 * ln.q + ln.n;
+    v4f leaves[8];
+    block_recursive<OP, 4, W == 1, c128_leaf<METHOD>()>(diag, D, small, ln, aux, NoHook(), leaves);
+    if (W == 0) {
+        D[tix(3, 2)] = transpose_tile(D[tix(3, 2)], small, ln);  // the odd child of the block came out in T orientation
+#pragma unroll
+        for (int d = 0; d < 4; ++d) D[tix(d, d)] = leaves[2 * d];
+#pragma unroll
+        for (int c = 1; c <= 2; ++c)
+#pragma unroll
+            for (int d = c; d < 4; ++d) t11_lds[c128_t11_slot(d, c) * 64 + lane] = pack<OP>(D[tix(d, c)]);
+    } else {
+        D[tix(1, 0)] = transpose_tile(D[tix(1, 0)], small, ln);  // the even child came out in N orientation
+#pragma unroll
+        for (int d = 0; d < 4; ++d) D[tix(d, d)] = leaves[2 * d + 1];
+#pragma unroll
+        for (int t = 0; t < 10; ++t) t22_lds[t * 64 + lane] = pack<OP>(D[t]);
+    }
+}
+
 // Everything up to the two waves' shares of the inverse.  lds: the workgroup's C128Lds bytes.
 // keys_loaded(): called between the issue of the key loads and their first use (a place for further independent memory
 // operations).  block_done(): called right after the workgroup barrier that follows the diagonal blocks, when this
@@ -135,25 +166,8 @@ __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t r
                 keys_top[((i - 1) * DKS + s) * 64 + lane] = hk.k[i][s];
         }
 
-    // own diagonal block: the C = 64 recursion; wave 0 produces an N block (right factor of the merge), wave 1 a T block
     const DiagA<KD, DKS, W> diag{hk, gate, ln};
-    v4f leaves[8];
-    block_recursive<OP, 4, W == 1, c128_leaf<METHOD>()>(diag, D, small, ln, aux, NoHook(), leaves);
-    if (W == 0) {
-        D[tix(3, 2)] = transpose_tile(D[tix(3, 2)], small, ln);  // the odd child of the block came out in T orientation
-#pragma unroll
-        for (int d = 0; d < 4; ++d) D[tix(d, d)] = leaves[2 * d];
-#pragma unroll
-        for (int c = 1; c <= 2; ++c)
-#pragma unroll
-            for (int d = c; d < 4; ++d) t11_lds[c128_t11_slot(d, c) * 64 + lane] = pack<OP>(D[tix(d, c)]);
-    } else {
-        D[tix(1, 0)] = transpose_tile(D[tix(1, 0)], small, ln);  // the even child came out in N orientation
-#pragma unroll
-        for (int d = 0; d < 4; ++d) D[tix(d, d)] = leaves[2 * d + 1];
-#pragma unroll
-        for (int t = 0; t < 10; ++t) t22_lds[t * 64 + lane] = pack<OP>(D[t]);
-    }
+    c128_diagonal_block<OP, METHOD, W>(diag, D, small, t11_lds, t22_lds, aux, ln);
     __syncthreads();  // the keys and the diagonal-block inverses the other wave needs are in LDS
     block_done();
 
@@ -190,6 +204,16 @@ __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t r
         }
     }
     keys_done();
+    c128_merge<OP, W>(a21, D, Wc, t11_lds, t22_lds, ln);
+}
+
+// The off-diagonal block: this wave's two tile columns of W = -T22 (A21 T11), from its tiles of A21 (a21[b][d] =
+// A(4 + b, d) in T orientation, columns d >= its smallest column), its own diagonal block D and the other wave's in LDS.
+template <int OP, int W>
+__device__ __forceinline__ void c128_merge(const Opnd<OP> (&a21)[4][4], const v4f (&D)[10], v4f (&Wc)[2][4], const Opnd<OP>* t11_lds,
+                                           const Opnd<OP>* t22_lds, Lane ln)
+{
+    const int lane = 16 * ln.q + ln.n;
     // the factors: own block from registers, the other wave's from LDS
     Opnd<OP> t11[10], t22[10];
 #pragma unroll
@@ -231,16 +255,26 @@ __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t r
 // rows 0..63, wave 1 rows 64..127 with wave 0's tiles of W fetched from LDS): 32 KB per wave.  Measured slower: wave 0
 // storing its rows as soon as T11 is final (149 against 142 us on the stress workload), and 256-byte half rows written
 // as soon as each 64 x 64 block is final (148 us).
+template <int W>
+__device__ __forceinline__ void c128_store_result(v4f* mail, float* strip, Out Tm, const v4f (&D)[10], const v4f (&Wc)[2][4], Lane ln);
+
 template <int KD, int OP, int METHOD, int DKS, int W>
 __device__ __forceinline__ void c128_invert_and_store(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
                                                       int64_t tok_stride, int valid, int aux, Out Tm, Lane ln)
 {
     typedef C128Lds<KD, OP, DKS, METHOD> LY;
-    const int lane = 16 * ln.q + ln.n;
-    v4f* mail = reinterpret_cast<v4f*>(lds + LY::MAIL);
-    float* strip = reinterpret_cast<float*>(lds + LY::STRIPS) + W * STORE_LDS_FLOATS;
     v4f D[10], Wc[2][4];
     c128_invert<KD, OP, METHOD, DKS, W>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook());
+    c128_store_result<W>(reinterpret_cast<v4f*>(lds + LY::MAIL), reinterpret_cast<float*>(lds + LY::STRIPS) + W * STORE_LDS_FLOATS, Tm, D,
+                         Wc, ln);
+}
+
+// mail: 8 KB of LDS for wave 0's tiles of W; strip: this wave's store strip (may take the place of anything the waves have
+// finished with before the barrier inside).
+template <int W>
+__device__ __forceinline__ void c128_store_result(v4f* mail, float* strip, Out Tm, const v4f (&D)[10], const v4f (&Wc)[2][4], Lane ln)
+{
+    const int lane = 16 * ln.q + ln.n;
     if (W == 0) {
 #pragma unroll
         for (int k = 0; k < 2; ++k)

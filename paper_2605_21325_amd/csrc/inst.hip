@@ -6,6 +6,7 @@
 #include "kernels.hpp"
 #if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
 #include "c128.hpp"
+#include "c128_kda.hpp"
 #endif
 
 #ifndef TRIINV_INST_NB
@@ -121,10 +122,11 @@ template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(co
     if constexpr (!REFINE && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT))
         return launch_kernel(a.dry, k_gdn_tri_inv_c128<KD, OP, METHOD, DKS>, dim3((unsigned)a.n_mat), dim3(128), 0, a.stream, a.K, a.beta,
                              a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
+    else
 #endif
-    return launch_kernel(a.dry, k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
-                       dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
-                       a.iters, a.out_dt, WPB > 1 ? head_spread(a.H) : 0);
+        return launch_kernel(a.dry, k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),
+                             dim3(64 * WPB), occupancy_pad_bytes<METHOD>(), a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k,
+                             a.iters, a.out_dt, WPB > 1 ? head_spread(a.H) : 0);
 }
 
 template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
@@ -186,9 +188,16 @@ template <int KD, int DKS> static int gdn_method(const GdnArgs& a)
 
 template <int METHOD, bool REFINE = false> static int go_kda(const GdnArgs& a)
 {
-    return launch_kernel(a.dry, k_kda_tri_inv<OP, NB, METHOD, WPB, REFINE>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
-                       a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt,
-                       WPB > 1 ? head_spread(a.H) : 0);
+#if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
+    // C = 128, the recursions: one matrix per workgroup of two wavefronts (c128_kda.hpp)
+    if constexpr (!REFINE && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT))
+        return launch_kernel(a.dry, k_kda_tri_inv_c128<OP, METHOD>, dim3((unsigned)a.n_mat), dim3(128), 0, a.stream, a.K, a.beta, a.g, a.T,
+                             a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt);
+    else
+#endif
+        return launch_kernel(a.dry, k_kda_tri_inv<OP, NB, METHOD, WPB, REFINE>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)), dim3(64 * WPB), 0,
+                             a.stream, a.K, a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt,
+                             WPB > 1 ? head_spread(a.H) : 0);
 }
 
 static int kda_method(const GdnArgs& a)

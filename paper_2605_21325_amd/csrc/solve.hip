@@ -41,15 +41,22 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     // C = 128, two right-hand sides: one chunk per workgroup of two wavefronts with the right-hand sides split by columns
     // (c128_solve.hpp).  A single right-hand side keeps the one-wavefront kernel below: its 256-byte row pieces stream
     // faster than the 128-byte pieces of the column split (data movers with the two access patterns: 142 against 176 us
-    // on the stress workload; the kernels: 165 against 179 us).
-    if (a.n_rhs == 2) {
+    // on the stress workload; the kernels: 165 against 179 us).  16-bit keys of d_k = 64 take the two-wavefront kernel for a
+    // single right-hand side as well (the one-wavefront build of that case does not fit the register file without spilling).
+    constexpr bool SINGLE_ON_TWO_WAVES = KD != OP_F32 && DKS == 2;
+    if (a.n_rhs == 2 || SINGLE_ON_TWO_WAVES) {
         for (int k = 0; k < a.n_rhs; ++k)  // its 32-bit row offsets: 128 rows of H * d_x elements
             if ((int64_t)f.H * a.d_x[k] * (OP == OP_F32 ? 4 : 2) * 128 >= (1LL << 31)) return 1;
+        if constexpr (SINGLE_ON_TWO_WAVES)
+            if (a.n_rhs == 1)
+                return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 1>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
+                                     f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
         if constexpr (OP != OP_F32)  // two sets of fp32 tiles do not fit the LDS budget of three workgroups per compute unit
             return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K,
                                  f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
         return 1;
     }
+    if constexpr (!SINGLE_ON_TWO_WAVES)
 #endif
     {
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
@@ -63,6 +70,7 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     }
     return 1;
     }
+    return 1;
 }
 
 template <int KD, int DKS> static int gdn_method(const SolveArgs& a)

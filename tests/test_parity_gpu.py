@@ -925,7 +925,7 @@ def test_mixed_recursion_b32_needs_c32():
 
 # ------------------------------------------------------------------ per-channel gate with a strong decay
 @pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
-@pytest.mark.parametrize("C", [16, 32, 64])
+@pytest.mark.parametrize("C", [16, 32, 64, 128])
 def test_per_channel_gate_with_a_strong_decay(C, op):
     """g falls by ~2.4 per token (~150 over a chunk of 64): exp(+-(g - one anchor per chunk)) would overflow
     fp32; with one anchor per 16 rows every exponent stays small and the result is inside the tolerance."""
@@ -937,7 +937,11 @@ def test_per_channel_gate_with_a_strong_decay(C, op):
     assert C < 64 or half > 89.0, half            # exp(g - g_mid) with one anchor per chunk overflows fp32 here
     T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 1, C)
     K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
-    for method in (tri.BLOCK_RECURSIVE, tri.FWD_SUBST, tri.MIXED_B32 if C >= 32 else tri.MIXED, tri.NEUMANN):
+    # C = 128: the recursions (two wavefronts per chunk, tile-row anchors); forward substitution and the two-launch methods
+    # build A with a single anchor per chunk there and are bound by the decay over the whole chunk
+    methods = (tri.BLOCK_RECURSIVE, tri.FWD_SUBST, tri.MIXED_B32 if C >= 32 else tri.MIXED, tri.NEUMANN) if C < 128 else \
+        (tri.BLOCK_RECURSIVE, tri.MIXED, tri.MIXED_B32, tri.BLOCK_DIRECT)
+    for method in methods:
         T = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
         # fp32 operands: the gate's exponent g - a reaches ~80 here, and its fp32 rounding alone (80 x 1.44 x 2^-24) puts a
         # relative error of ~5e-6 on the gated keys -- above the elementwise model's fp32 term, so norms only in that mode
