@@ -580,14 +580,19 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_buffer(Out Tm, int C)
 {
     return __builtin_amdgcn_make_buffer_rsrc(Tm.base, 0, C * C * (Tm.dt == OP_F32 ? 4 : 2), 0x00020000);  // raw buffer
 }
-// byte offset = lane_offset (a vector register, the same for every store of a strip) + uniform_offset (a scalar)
+// byte offset = lane_offset (the same for every store of a strip) + uniform_offset (a constant of the strip and row group).
+// Both go into the vector offset, the instruction's scalar offset stays the immediate zero.  A 16-byte store whose scalar
+// offset is a register is not safe here: the compiler places no wait state between such a store and a vector-ALU write
+// of its data registers (it guards only the immediate form), and with a write in the very next slot the store now and
+// then sent the new value of its first data register: about one matrix in 10^6 came out with the next strip's values
+// in 16 of its elements.  With the immediate form the compiler inserts the wait state itself.
 __device__ __forceinline__ void stream_store(v4u v, __amdgpu_buffer_rsrc_t out, int lane_offset, int uniform_offset = 0)
 {
-    __builtin_amdgcn_raw_buffer_store_b128(v, out, lane_offset, uniform_offset, CACHE_SC0_SC1_NT);
+    __builtin_amdgcn_raw_buffer_store_b128(v, out, lane_offset + uniform_offset, 0, CACHE_SC0_SC1_NT);
 }
 __device__ __forceinline__ void stream_store(v4f v, __amdgpu_buffer_rsrc_t out, int lane_offset, int uniform_offset = 0)
 {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), out, lane_offset, uniform_offset, CACHE_SC0_SC1_NT);
+    stream_store(__builtin_bit_cast(v4u, v), out, lane_offset, uniform_offset);
 }
 __device__ __forceinline__ void stream_store(float v, float* p) { __builtin_nontemporal_store(v, p); }
 
@@ -1043,12 +1048,9 @@ __global__ __launch_bounds__(64 * WPB) void k_kda_tri_inv(const void* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-// Neumann product at C = 128: one workgroup of four wavefronts per matrix.
-// The running power Y = A^(2^k) lives in LDS as 36 fp32 tiles (16 x 20 floats each, N orientation);
-// a tile is read back in either orientation (four 4-byte reads, or one 16-byte read of the
-// transposed tile) and rounded to the operand type at every product, as in the one-wave kernel.
-// Wave w owns tile rows w and 7 - w of both Y and X^T; X^T stays in its registers.  Per iteration:
-// new Y tiles into registers -> barrier -> overwrite LDS -> barrier -> X^T += Y^T X^T.
+// C = 128 on one workgroup of four wavefronts per matrix (Neumann product, Newton-Schulz, refinement pass):
+// wave w owns tile rows w and 7 - w of every matrix involved.  The refinement pass keeps its Y in LDS as 36 fp32
+// tiles (16 x 20 floats each), readable in either orientation.
 // ---------------------------------------------------------------------------------------------
 constexpr int N128_NB = 8;
 constexpr int N128_NT = 36;
@@ -1061,89 +1063,9 @@ __device__ __forceinline__ v4f lds_tile_read_n(const float* t, Lane ln)
     for (int r = 0; r < 4; ++r) v[r] = t[(4 * ln.q + r) * XPOSE_LD + ln.n];
     return v;
 }
-__device__ __forceinline__ v4f lds_tile_read_t(const float* t, Lane ln)
-{
-    return *reinterpret_cast<const v4f*>(&t[ln.n * XPOSE_LD + 4 * ln.q]);
-}
-// registers in N orientation -> the tile stored transposed (read it back in N orientation with lds_tile_read_t)
-__device__ __forceinline__ void lds_tile_write_transposed(float* t, v4f v, Lane ln)
-{
-    *reinterpret_cast<v4f*>(&t[ln.n * XPOSE_LD + 4 * ln.q]) = v;
-}
-__device__ __forceinline__ void lds_tile_write_n(float* t, v4f v, Lane ln)
-{
-#pragma unroll
-    for (int r = 0; r < 4; ++r) t[(4 * ln.q + r) * XPOSE_LD + ln.n] = v[r];
-}
-
 // slot s of wave W: tile (i, j) with i = W for s <= W, else i = 7 - W
 template <int W> __host__ __device__ constexpr int n128_row(int s) { return s <= W ? W : 7 - W; }
 template <int W> __host__ __device__ constexpr int n128_col(int s) { return s <= W ? s : s - (W + 1); }
-
-template <int OP, int W, class ASrc>
-__device__ __forceinline__ void n128_init(const ASrc& A, v4f (&Xt)[9], float* Y, Lane ln)
-{
-#pragma unroll
-    for (int s = 0; s < 9; ++s) {
-        const int i = n128_row<W>(s), j = n128_col<W>(s);
-        lds_tile_write_n(Y + tix(i, j) * XPOSE_FLOATS, A.template get<false>(i, j), ln);
-        const v4f at = A.template get<true>(i, j);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) Xt[s][r] = ((i == j && 4 * ln.q + r == ln.n) ? 1.f : 0.f) - at[r];
-    }
-}
-
-template <int OP, int W>
-__device__ __forceinline__ void n128_square(v4f (&Yn)[9], const float* Y, int p, Lane ln)
-{
-#pragma unroll
-    for (int s = 0; s < 9; ++s) {
-        const int i = n128_row<W>(s), j = n128_col<W>(s);
-        v4f acc = zero4();
-#pragma unroll
-        for (int k = 0; k < N128_NB; ++k) {
-            if (k < j || k > i) continue;
-            // structural zeros of A^p (tile (a, b) vanishes when 16 (a - b) + 15 < p); p is uniform
-            if (16 * (i - k) + 15 < p || 16 * (k - j) + 15 < p) continue;
-            const Opnd<OP> l = pack<OP>(lds_tile_read_t(Y + tix(i, k) * XPOSE_FLOATS, ln));
-            const Opnd<OP> r = pack<OP>(lds_tile_read_n(Y + tix(k, j) * XPOSE_FLOATS, ln));
-            acc = tn<OP>(l, r, acc);
-        }
-        Yn[s] = acc;
-    }
-}
-
-template <int W> __device__ __forceinline__ void n128_publish(const v4f (&Yn)[9], float* Y, Lane ln)
-{
-#pragma unroll
-    for (int s = 0; s < 9; ++s) lds_tile_write_n(Y + tix(n128_row<W>(s), n128_col<W>(s)) * XPOSE_FLOATS, Yn[s], ln);
-}
-
-template <int OP, int W>
-__device__ __forceinline__ void n128_update_x(v4f (&Xt)[9], const float* Y, int pn, Lane ln)
-{
-    // X^T(i,j) += sum_k Y(k,j)^T X(i,k)^T over this wave's two tile rows; the packed old row first
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int i = half == 0 ? W : 7 - W, s0 = half == 0 ? 0 : W + 1;
-        Opnd<OP> xo[N128_NB];
-#pragma unroll
-        for (int k = 0; k < N128_NB; ++k)
-            if (k <= i) xo[k] = pack<OP>(Xt[s0 + k]);
-#pragma unroll
-        for (int j = 0; j < N128_NB; ++j) {
-            if (j > i) continue;
-            v4f acc = Xt[s0 + j];
-#pragma unroll
-            for (int k = 0; k < N128_NB; ++k) {
-                if (k < j || k > i) continue;
-                if (16 * (k - j) + 15 < pn) continue;
-                acc = tn<OP>(pack<OP>(lds_tile_read_n(Y + tix(k, j) * XPOSE_FLOATS, ln)), xo[k], acc);
-            }
-            Xt[s0 + j] = acc;
-        }
-    }
-}
 
 template <int W>
 __device__ __forceinline__ void n128_store(Out Tm, const v4f (&Xt)[9], float* patch, Lane ln)
@@ -1167,53 +1089,54 @@ __device__ __forceinline__ void n128_store(Out Tm, const v4f (&Xt)[9], float* pa
     default: { constexpr int W = 3; CALL; } break; \
     }
 
-template <int OP, class ASrc>
-__device__ __forceinline__ void neumann_c128_workgroup(const ASrc& A, Out Tm, float* Y, Lane ln, int w)
-{
-    v4f Xt[9];
-    TRIINV_PER_WAVE(w, (n128_init<OP, W>(A, Xt, Y, ln)))
-    __syncthreads();
-#pragma unroll 1
-    for (int it = 0; it < 6; ++it) {  // log2(128 / 2)
-        const int p = 1 << it, pn = 2 << it;
-        v4f Yn[9];
-        TRIINV_PER_WAVE(w, (n128_square<OP, W>(Yn, Y, p, ln)))
-        __syncthreads();
-        TRIINV_PER_WAVE(w, (n128_publish<W>(Yn, Y, ln)))
-        __syncthreads();
-        TRIINV_PER_WAVE(w, (n128_update_x<OP, W>(Xt, Y, pn, ln)))
-    }
-    __syncthreads();  // Y is dead: its memory becomes the four store patches
-    TRIINV_PER_WAVE(w, (n128_store<W>(Tm, Xt, Y + w * STORE_LDS_FLOATS, ln)))
-}
-
 // ---------------------------------------------------------------------------------------------
 // Newton-Schulz at C = 128 (paper Alg. 3, Eq. 8, for I + A): the same four-wavefront workgroup.
 //   X <- I / C;  n_iter times:  Y <- X + A X;  X <- 2 X - X Y.
-// X and Y live in LDS as 36 fp32 tiles each, stored transposed so that a tile leaves the accumulator
-// layout and comes back as a right factor with one 16-byte access per lane (92 KB together, one workgroup
-// per compute unit); wave w owns tile rows w and 7 - w: it keeps its rows of A (T orientation, packed operands) and of
-// X (both orientations, fp32) in registers and reads the other factor of every product from LDS.
+// Wave w owns tile rows w and 7 - w: it keeps its rows of A (T orientation, packed operands) and of X (both
+// orientations, fp32) in registers and reads the right factor of every product (a tile of X, then of Y, in N
+// orientation) from LDS.  A right factor in N orientation is exactly the register image its producer holds,
+// so a tile crosses between waves as a mailbox: 64 consecutive slots of one packed operand each, lane l of the
+// reader taking what lane l of the writer left.  No transposition, no bank conflicts, and the rounding to the
+// operand type happens once, at the writer.  X and Y take 2 x 36 tiles: 36 KB for 16-bit operands, 72 KB for fp32.
 // ---------------------------------------------------------------------------------------------
-constexpr int NS128_LDS_FLOATS = 2 * N128_LDS_FLOATS;
+template <int OP> struct MailTiles {
+    static constexpr int TILE_BYTES = 64 * (int)sizeof(Opnd<OP>);
+    static constexpr int BYTES = N128_NT * TILE_BYTES;
+    static __device__ __forceinline__ void put(char* base, int tile, Opnd<OP> v, Lane ln)
+    {
+        *reinterpret_cast<Opnd<OP>*>(base + tile * TILE_BYTES + (16 * ln.q + ln.n) * (int)sizeof(Opnd<OP>)) = v;
+    }
+    static __device__ __forceinline__ Opnd<OP> get(const char* base, int tile, Lane ln)
+    {
+        return *reinterpret_cast<const Opnd<OP>*>(base + tile * TILE_BYTES + (16 * ln.q + ln.n) * (int)sizeof(Opnd<OP>));
+    }
+};
+
+template <int OP> constexpr int ns128_lds_bytes()
+{
+    return 2 * MailTiles<OP>::BYTES > 4 * STORE_LDS_FLOATS * 4 ? 2 * MailTiles<OP>::BYTES : 4 * STORE_LDS_FLOATS * 4;
+}
 
 template <int W> __host__ __device__ constexpr int n128_slot(int i, int k) { return i == W ? k : (W + 1) + k; }
 
-template <int OP, int W, class ASrc>
-__device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float* Y, Lane ln, int n_iter, int w)
+// At: this wave's nine tiles of A in T orientation (slot order of n128_row / n128_col).  lds: ns128_lds_bytes<OP>() bytes
+// that no wave uses for anything else any more.
+template <int OP, int W>
+__device__ __forceinline__ void ns128_run(const Opnd<OP> (&At)[9], Out Tm, char* lds, Lane ln, int n_iter, int w)
 {
-    Opnd<OP> At[9];
+    typedef MailTiles<OP> Mail;
+    char* const X = lds;
+    char* const Y = lds + Mail::BYTES;
     v4f Xn[9], Xt[9];
 #pragma unroll
     for (int s = 0; s < 9; ++s) {
         const int i = n128_row<W>(s), j = n128_col<W>(s);
-        At[s] = pack<OP>(A.template get<true>(i, j));
         v4f x;
 #pragma unroll
         for (int r = 0; r < 4; ++r) x[r] = (i == j && 4 * ln.q + r == ln.n) ? 1.f / 128.f : 0.f;
         Xn[s] = x;
         Xt[s] = x;
-        lds_tile_write_transposed(X + tix(i, j) * XPOSE_FLOATS, x, ln);
+        Mail::put(X, tix(i, j), pack<OP>(x), ln);
     }
     __syncthreads();
 #pragma unroll 1
@@ -1222,13 +1145,9 @@ __device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float
 #pragma unroll
         for (int s = 0; s < 9; ++s) {
             const int i = n128_row<W>(s), j = n128_col<W>(s);
-            v4f acc = Xn[s];
-#pragma unroll
-            for (int k = 0; k < N128_NB; ++k) {
-                if (k < j || k > i) continue;
-                acc = tn<OP>(At[n128_slot<W>(i, k)], pack<OP>(lds_tile_read_t(X + tix(k, j) * XPOSE_FLOATS, ln)), acc);
-            }
-            lds_tile_write_transposed(Y + tix(i, j) * XPOSE_FLOATS, acc, ln);
+            const v4f acc = tn_sum<OP>(
+                j, i, [&](int k) { return At[n128_slot<W>(i, k)]; }, [&](int k) { return Mail::get(X, tix(k, j), ln); }, Xn[s]);
+            Mail::put(Y, tix(i, j), pack<OP>(acc), ln);
         }
         __syncthreads();  // Y complete; nobody reads X from LDS any more in this iteration
         // X(i,j) <- 2 X(i,j) - sum_k X(i,k) Y(k,j), both orientations; the packed old row first
@@ -1242,22 +1161,171 @@ __device__ __forceinline__ void ns128_run(const ASrc& A, Out Tm, float* X, float
 #pragma unroll
             for (int j = 0; j < N128_NB; ++j) {
                 if (j > i) continue;
-                v4f pn = zero4(), pt = zero4();
+                Opnd<OP> y[N128_NB];
 #pragma unroll
-                for (int k = 0; k < N128_NB; ++k) {
-                    if (k < j || k > i) continue;
-                    const Opnd<OP> y = pack<OP>(lds_tile_read_t(Y + tix(k, j) * XPOSE_FLOATS, ln));
-                    pn = tn<OP>(xo[k], y, pn);
-                    pt = tn<OP>(y, xo[k], pt);
-                }
+                for (int k = 0; k < N128_NB; ++k)
+                    if (k >= j && k <= i) y[k] = Mail::get(Y, tix(k, j), ln);
+                const v4f pn = tn_sum<OP>(j, i, [&](int k) { return xo[k]; }, [&](int k) { return y[k]; }, zero4());
+                const v4f pt = tn_sum<OP>(j, i, [&](int k) { return y[k]; }, [&](int k) { return xo[k]; }, zero4());
                 Xn[s0 + j] = 2.f * Xn[s0 + j] - pn;
                 Xt[s0 + j] = 2.f * Xt[s0 + j] - pt;
-                lds_tile_write_transposed(X + tix(i, j) * XPOSE_FLOATS, Xn[s0 + j], ln);
+                Mail::put(X, tix(i, j), pack<OP>(Xn[s0 + j]), ln);
             }
         }
         __syncthreads();  // X complete; nobody reads Y any more
     }
-    n128_store<W>(Tm, Xt, Y + w * STORE_LDS_FLOATS, ln);  // Y is dead: its memory becomes the four store patches
+    // X and Y in LDS are dead: their memory becomes the four store patches
+    n128_store<W>(Tm, Xt, reinterpret_cast<float*>(lds) + w * STORE_LDS_FLOATS, ln);
+}
+
+// The fused kernel's tiles of A: the four waves load the chunk's keys once between them (wave w its tile rows w and
+// 7 - w), pass them through LDS in mailbox form (slot [tile row][k-step][lane], one 16-byte
+// key vector each) and every wave forms only its own nine tiles.
+template <int KD, int DKS> struct SharedKeys128 {
+    typedef typename KeyVec<KD>::type kvec;
+    static constexpr int KSTEP = (KD == OP_F32) ? 16 : 32;
+    static constexpr int BYTES = 8 * DKS * 64 * 16;
+    kvec own[2][DKS];
+
+    // Kc: first key element of (chunk row 0, this head); row_stride in elements; rows beyond valid read the last real token and become zero.
+    __device__ __forceinline__ void load(const void* Kc, int64_t row_stride, int valid, int w, Lane ln)
+    {
+        constexpr int per_lane = (KD == OP_F32) ? 4 : 8;
+        const kvec zero = __builtin_bit_cast(kvec, v4u{0u, 0u, 0u, 0u});
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int s = 0; s < DKS; ++s) {
+                const int row = 16 * (h == 0 ? w : 7 - w) + ln.n;
+                const int64_t off = (int64_t)(row < valid ? row : valid - 1) * row_stride + KSTEP * s + per_lane * ln.q;
+                kvec v;
+                if (KD == OP_F32)
+                    v = *reinterpret_cast<const kvec*>(static_cast<const float*>(Kc) + off);
+                else
+                    v = *reinterpret_cast<const kvec*>(static_cast<const uint16_t*>(Kc) + off);
+                own[h][s] = row < valid ? v : zero;
+            }
+    }
+    __device__ __forceinline__ void publish(char* lds, int w, Lane ln) const
+    {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int s = 0; s < DKS; ++s)
+                *reinterpret_cast<kvec*>(lds + (((h == 0 ? w : 7 - w) * DKS + s) * 64 + 16 * ln.q + ln.n) * 16) = own[h][s];
+    }
+    // Tile s of wave W (slot order of n128_row / n128_col) in N (TR = false) or T orientation; after a barrier that
+    // follows every wave's publish().
+    template <int W, bool TR>
+    __device__ __forceinline__ v4f tile(const char* lds, const GateVec<N128_NB>& gate, int s, Lane ln) const
+    {
+        const int i = n128_row<W>(s), j = n128_col<W>(s);
+        v4f acc = zero4();
+#pragma unroll
+        for (int t = 0; t < DKS; ++t) {
+            // both from LDS: the loaded keys' registers are free again once they are published
+            const kvec kj = *reinterpret_cast<const kvec*>(lds + ((j * DKS + t) * 64 + 16 * ln.q + ln.n) * 16);
+            const kvec ki = *reinterpret_cast<const kvec*>(lds + ((i * DKS + t) * 64 + 16 * ln.q + ln.n) * 16);
+            acc = TR ? gram_step<KD>(kj, ki, acc) : gram_step<KD>(ki, kj, acc);
+        }
+        return gate.template apply<TR>(i, j, acc, ln);
+    }
+};
+
+// SharedKeys128 behind the tile-source interface, for the tiles of wave W only.
+template <int KD, int DKS, int W> struct SharedA128 {
+    const SharedKeys128<KD, DKS>& keys;
+    const GateVec<N128_NB>& gate;
+    const char* lds;
+    Lane ln;
+    template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const
+    {
+        return keys.template tile<W, TR>(lds, gate, i == W ? j : (W + 1) + j, ln);
+    }
+};
+
+template <int OP, int W, class ASrc> __device__ __forceinline__ void ns128_tiles_of(const ASrc& A, Opnd<OP> (&At)[9])
+{
+#pragma unroll
+    for (int s = 0; s < 9; ++s) At[s] = pack<OP>(A.template get<true>(n128_row<W>(s), n128_col<W>(s)));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Neumann product at C = 128, (I + A)^-1 = (I - A) (I + A^2) (I + A^4) ... (I + A^64): the four-wavefront workgroup
+// and the mailbox tiles of the Newton-Schulz kernel above.  Wave w owns tile rows w and 7 - w.  It keeps X^T (fp32)
+// and its rows of the running power Y = A^(2^k) in T orientation (packed) in registers; every product takes its
+// other factor, a tile of Y in N orientation, from the mailbox.  Squaring forms both orientations of the new tile
+// (two matrix-core instructions per product instead of one transposing read through LDS); the N image goes to the
+// other of two mailbox buffers, which leaves one barrier per iteration:
+//   Y' <- Y Y (cur -> nxt);  barrier;  X^T += Y'^T X^T (reads nxt);  swap.
+// ---------------------------------------------------------------------------------------------
+// Wave W's share of the start: X^T = I - A^T and Y = A in T orientation into registers, Y in N orientation into the mailbox.
+template <int OP, int W, class ASrc>
+__device__ __forceinline__ void neumann128_prepare(const ASrc& A, v4f (&Xt)[9], Opnd<OP> (&yt)[9], char* cur, Lane ln)
+{
+#pragma unroll
+    for (int s = 0; s < 9; ++s) {
+        const int i = n128_row<W>(s), j = n128_col<W>(s);
+        MailTiles<OP>::put(cur, tix(i, j), pack<OP>(A.template get<false>(i, j)), ln);
+        const v4f at = A.template get<true>(i, j);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Xt[s][r] = ((i == j && 4 * ln.q + r == ln.n) ? 1.f : 0.f) - at[r];
+        yt[s] = pack<OP>(at);
+    }
+}
+
+// cur, nxt: the two mailbox buffers (MailTiles<OP>::BYTES each), cur filled by neumann128_prepare; patch: this wave's
+// store patch, anywhere in LDS that no wave uses for anything but the two buffers.
+template <int OP, int W>
+__device__ __forceinline__ void neumann128_run(v4f (&Xt)[9], Opnd<OP> (&yt)[9], Out Tm, char* cur, char* nxt, float* patch, Lane ln)
+{
+    typedef MailTiles<OP> Mail;
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < 6; ++it) {  // log2(128 / 2)
+        const int p = 1 << it, pn = 2 << it;
+        Opnd<OP> ytn[9];
+#pragma unroll
+        for (int s = 0; s < 9; ++s) {
+            const int i = n128_row<W>(s), j = n128_col<W>(s);
+            // structural zeros of A^p (tile (a, b) vanishes when 16 (a - b) + 15 < p); p is uniform
+            const auto live = [&](int k) { return 16 * (i - k) + 15 >= p && 16 * (k - j) + 15 >= p; };
+            const auto mine = [&](int k) { return yt[n128_slot<W>(i, k)]; };
+            Opnd<OP> y[N128_NB];
+#pragma unroll
+            for (int k = 0; k < N128_NB; ++k)
+                if (k >= j && k <= i) y[k] = Mail::get(cur, tix(k, j), ln);
+            const auto theirs = [&](int k) { return y[k]; };
+            const v4f an = tn_sum_if<OP>(j, i, mine, theirs, live, zero4());
+            const v4f at = tn_sum_if<OP>(j, i, theirs, mine, live, zero4());
+            ytn[s] = pack<OP>(at);
+            Mail::put(nxt, tix(i, j), pack<OP>(an), ln);
+        }
+#pragma unroll
+        for (int s = 0; s < 9; ++s) yt[s] = ytn[s];
+        __syncthreads();  // the new power is complete; nobody reads the old one any more
+        // X^T(i,j) += sum_k Y(k,j)^T X(i,k)^T over this wave's two tile rows; the packed old row first
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int i = half == 0 ? W : 7 - W, s0 = half == 0 ? 0 : W + 1;
+            Opnd<OP> xo[N128_NB];
+#pragma unroll
+            for (int k = 0; k < N128_NB; ++k)
+                if (k <= i) xo[k] = pack<OP>(Xt[s0 + k]);
+#pragma unroll
+            for (int j = 0; j < N128_NB; ++j) {
+                if (j > i) continue;
+                Xt[s0 + j] = tn_sum_if<OP>(
+                    j, i, [&](int k) { return Mail::get(nxt, tix(k, j), ln); }, [&](int k) { return xo[k]; },
+                    [&](int k) { return 16 * (k - j) + 15 >= pn; }, Xt[s0 + j]);
+            }
+        }
+        char* const t = cur;
+        cur = nxt;
+        nxt = t;
+    }
+    __syncthreads();  // both mailbox buffers are dead: their memory becomes the four store patches
+    n128_store<W>(Tm, Xt, patch, ln);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1364,9 +1432,9 @@ __global__ __launch_bounds__(256) void k_gdn_tri_inv_refine128(const void* __res
 }
 
 template <int OP>
-__global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* A, float* T, int64_t n_mat, int in_dt, int n_iter, int out_dt)  // may run in place
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OP == OP_F32 ? 2 : 3))) void k_tri_inv_ns128(const void* A, float* T, int64_t n_mat, int in_dt, int n_iter, int out_dt)  // may run in place
 {
-    __shared__ __attribute__((aligned(16))) float XY[NS128_LDS_FLOATS];
+    __shared__ __attribute__((aligned(16))) char lds[ns128_lds_bytes<OP>()];
     const int64_t m = blockIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Lane ln = lane_id();
@@ -1375,16 +1443,22 @@ __global__ __launch_bounds__(256) void k_tri_inv_ns128(const void* A, float* T, 
     src.dt = in_dt;
     src.ln = ln;
     (void)n_mat;
-    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, out_matrix(T, m, 128, out_dt), XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
+    Opnd<OP> At[9];
+    TRIINV_PER_WAVE(w, (ns128_tiles_of<OP, W>(src, At)))
+    // in place: every wave has read its rows of A before any wave stores (the iteration's barriers lie between)
+    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(At, out_matrix(T, m, 128, out_dt), lds, ln, n_iter, w)))
 }
 
 template <int KD, int OP, int DKS>
-__global__ __launch_bounds__(256) void k_gdn_tri_inv_ns128(const void* __restrict__ K, const float* __restrict__ beta,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OP == OP_F32 ? 2 : 3))) void k_gdn_tri_inv_ns128(const void* __restrict__ K, const float* __restrict__ beta,
                                                            const float* __restrict__ g, float* __restrict__ T,
                                                            int64_t n_chunk, ChunkMap map, int H, int d_k, int n_iter, int out_dt)
 {
     constexpr int C = 128;
-    __shared__ __attribute__((aligned(16))) float XY[NS128_LDS_FLOATS];
+    typedef SharedKeys128<KD, DKS> Keys;
+    constexpr int GATE_BYTES = 4 * 2 * C * 4;  // beta and g of the chunk, staged by every wave for itself
+    constexpr int LDS_BYTES = ns128_lds_bytes<OP>() > Keys::BYTES + GATE_BYTES ? ns128_lds_bytes<OP>() : Keys::BYTES + GATE_BYTES;
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
     const uint32_t bc = (uint32_t)m / (uint32_t)H;
     const int h = (int)((uint32_t)m - bc * (uint32_t)H);
@@ -1392,20 +1466,24 @@ __global__ __launch_bounds__(256) void k_gdn_tri_inv_ns128(const void* __restric
     const int64_t tok0 = pos.tok0;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Lane ln = lane_id();
-    GramA<KD, N128_NB, DKS> src;
-    src.ln = ln;
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
-    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
-    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
-    src.stage_gate(XY + w * 2 * C);  // a private 2 * C floats inside the (not yet used) X buffer
+    GateVec<N128_NB> gate;
+    Keys keys;
+    gate.issue(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, ln, pos.valid);
+    keys.load(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid, w, ln);
+    gate.stage(reinterpret_cast<float*>(lds + Keys::BYTES) + w * 2 * C, ln);
+    keys.publish(lds, w, ln);
     __syncthreads();
-    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(src, out_matrix(T, m, C, out_dt), XY, XY + N128_LDS_FLOATS, ln, n_iter, w)))
+    Opnd<OP> At[9];
+    TRIINV_PER_WAVE(w, (ns128_tiles_of<OP, W>(SharedA128<KD, DKS, W>{keys, gate, lds, ln}, At)))
+    __syncthreads();  // the keys in LDS are dead: X and Y take their place
+    TRIINV_PER_WAVE(w, (ns128_run<OP, W>(At, out_matrix(T, m, C, out_dt), lds, ln, n_iter, w)))
 }
 
 template <int OP>
-__global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* A, float* T, int64_t n_mat, int in_dt, int out_dt)  // may run in place
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OP == OP_F32 ? 2 : 3))) void k_tri_inv_neumann128(const void* A, float* T, int64_t n_mat, int in_dt, int out_dt)  // may run in place
 {
-    __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
+    __shared__ __attribute__((aligned(16))) char lds[ns128_lds_bytes<OP>()];
     const int64_t m = blockIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Lane ln = lane_id();
@@ -1414,16 +1492,29 @@ __global__ __launch_bounds__(256) void k_tri_inv_neumann128(const void* A, float
     src.dt = in_dt;
     src.ln = ln;
     (void)n_mat;
-    neumann_c128_workgroup<OP>(src, out_matrix(T, m, 128, out_dt), Y, ln, w);
+    v4f Xt[9];
+    Opnd<OP> yt[9];
+    char* const nxt = lds + MailTiles<OP>::BYTES;
+    float* const patch = reinterpret_cast<float*>(lds) + w * STORE_LDS_FLOATS;
+    TRIINV_PER_WAVE(w, (neumann128_prepare<OP, W>(src, Xt, yt, lds, ln)))
+    // in place: every wave has read its rows of A before any wave stores (the iteration's barriers lie between)
+    TRIINV_PER_WAVE(w, (neumann128_run<OP, W>(Xt, yt, out_matrix(T, m, 128, out_dt), lds, nxt, patch, ln)))
 }
 
 template <int KD, int OP, int DKS>
-__global__ __launch_bounds__(256) void k_gdn_tri_inv_neumann128(const void* __restrict__ K, const float* __restrict__ beta,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OP == OP_F32 ? 2 : 3))) void k_gdn_tri_inv_neumann128(const void* __restrict__ K, const float* __restrict__ beta,
                                                                 const float* __restrict__ g, float* __restrict__ T,
                                                                 int64_t n_chunk, ChunkMap map, int H, int d_k, int out_dt)
 {
     constexpr int C = 128;
-    __shared__ __attribute__((aligned(16))) float Y[N128_LDS_FLOATS];
+    typedef SharedKeys128<KD, DKS> Keys;
+    typedef MailTiles<OP> Mail;
+    // [keys | first mailbox buffer]; the second buffer takes the keys' place (first written after the barrier that ends
+    // the keys' use), beta and g are staged, by every wave for itself, where the first buffer will be
+    constexpr int CUR = Keys::BYTES > Mail::BYTES ? Keys::BYTES : Mail::BYTES;
+    constexpr int LDS_BYTES = CUR + Mail::BYTES;
+    static_assert(4 * 2 * C * 4 <= Mail::BYTES && 4 * STORE_LDS_FLOATS * 4 <= LDS_BYTES, "staging area and store patches fit");
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     const int64_t m = head_group_swizzle(blockIdx.x, n_chunk, H);
     const uint32_t bc = (uint32_t)m / (uint32_t)H;
     const int h = (int)((uint32_t)m - bc * (uint32_t)H);
@@ -1431,15 +1522,19 @@ __global__ __launch_bounds__(256) void k_gdn_tri_inv_neumann128(const void* __re
     const int64_t tok0 = pos.tok0;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const Lane ln = lane_id();
-    GramA<KD, N128_NB, DKS> src;
-    src.ln = ln;
     const int64_t esz = (KD == OP_F32) ? 4 : 2;
-    src.issue_gate(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, pos.valid);
-    src.load_keys(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid);
-    // every wave stages beta / g for itself: a private 2 * C floats inside the (not yet used) Y buffer
-    src.stage_gate(Y + w * 2 * C);
-    __syncthreads();
-    neumann_c128_workgroup<OP>(src, out_matrix(T, m, C, out_dt), Y, ln, w);
+    GateVec<N128_NB> gate;
+    Keys keys;
+    gate.issue(beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, ln, pos.valid);
+    keys.load(static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz, (int64_t)H * d_k, pos.valid, w, ln);
+    gate.stage(reinterpret_cast<float*>(lds + CUR) + w * 2 * C, ln);
+    keys.publish(lds, w, ln);
+    __syncthreads();  // keys published, and every wave is done with its staging area
+    v4f Xt[9];
+    Opnd<OP> yt[9];
+    float* const patch = reinterpret_cast<float*>(lds) + w * STORE_LDS_FLOATS;
+    TRIINV_PER_WAVE(w, (neumann128_prepare<OP, W>(SharedA128<KD, DKS, W>{keys, gate, lds, ln}, Xt, yt, lds + CUR, ln)))
+    TRIINV_PER_WAVE(w, (neumann128_run<OP, W>(Xt, yt, out_matrix(T, m, C, out_dt), lds + CUR, lds, patch, ln)))
 }
 
 }  // namespace triinv

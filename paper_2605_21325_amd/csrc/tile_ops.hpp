@@ -142,6 +142,23 @@ template <> __device__ __forceinline__ v4f tn<OP_BF16>(Opnd<OP_BF16> x, Opnd<OP_
     return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(x.x, y.x, acc, 0, 0, 0);
 }
 
+// acc + sum over k in [lo, hi] of X(k)^T * Y(k); live(k): a wave-uniform run-time test that may drop terms whose tiles
+// are known to hold zeros.
+template <int OP, class FX, class FY, class Live>
+__device__ __forceinline__ v4f tn_sum_if(int lo, int hi, FX x, FY y, Live live, v4f acc)
+{
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (k < lo || k > hi) continue;
+        if (live(k)) acc = tn<OP>(x(k), y(k), acc);
+    }
+    return acc;
+}
+template <int OP, class FX, class FY> __device__ __forceinline__ v4f tn_sum(int lo, int hi, FX x, FY y, v4f acc)
+{
+    return tn_sum_if<OP>(lo, hi, x, y, [](int) { return true; }, acc);
+}
+
 __device__ __forceinline__ v4f zero4() { return v4f{0.f, 0.f, 0.f, 0.f}; }
 
 // Index of lower tile (i, j), i >= j, in a packed array of NB*(NB+1)/2 tiles.
