@@ -118,7 +118,6 @@ int check_fused(const void* K, const float* beta, const float* g, float* T, uint
     if (need_g && overlap(g, n_tok * 4 * (gate_kind == TRIINV_GATE_PER_CHANNEL ? d_k : 1), T, t_bytes)) return TRIINV_ERR_ALIAS;
     if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
     if (flags & TRIINV_FLAG_FWD_SHUFFLE) return TRIINV_ERR_UNSUPPORTED;  // a variant of the standalone entry point
-    if (method == TRIINV_FWD_SUBST && out_dt != TRIINV_F32) return TRIINV_ERR_UNSUPPORTED;
     (void)H;
     return TRIINV_OK;
 }
@@ -198,7 +197,7 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
     const uint64_t n_el = (uint64_t)n_mat * C * C;
     if (overlap(A, n_el * esize(in_dtype), T, n_el * esize(out_dt))) return TRIINV_ERR_ALIAS;
     if (flags & ~KNOWN_FLAGS) return TRIINV_ERR_UNSUPPORTED;
-    if (method == TRIINV_FWD_SUBST && out_dt != TRIINV_F32) return TRIINV_ERR_UNSUPPORTED;  // stores element by element
+    if (method == TRIINV_FWD_SUBST && (flags & TRIINV_FLAG_FWD_SHUFFLE) && out_dt != TRIINV_F32) return TRIINV_ERR_UNSUPPORTED;
     if (method == TRIINV_FWD_SUBST) op_dtype = TRIINV_F32;
 
     TriInvArgs a{A, T, n_mat, in_dtype, method, static_cast<hipStream_t>(hip_stream), (flags & TRIINV_FLAG_REFINE1) != 0,

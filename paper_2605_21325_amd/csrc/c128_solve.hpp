@@ -173,19 +173,10 @@ template <int KD, int OP, int DKS, int METHOD, int NRHS> struct C128SolveLds {
     static constexpr int BYTES = SCALE + 2 * 128 * 4;
 };
 
-// NRHS right-hand sides share the inverse: its tiles are published once per right-hand side (their columns scaled by
-// that side's s), all sets before the one barrier, so that nothing of the inverse stays in registers afterwards.
-template <int KD, int OP, int METHOD, int DKS, int W, int NRHS>
-__device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
-                                                      int64_t tok_stride, const RhsList& rhs, int64_t tok0, int h, int H, int valid,
-                                                      int aux, Lane ln)
+// The row scales of this lane's two tokens, every right-hand side.
+template <int NRHS>
+__device__ __forceinline__ void c128_load_scales(float (&raw_s)[NRHS][2], const RhsList& rhs, int64_t tok0, int h, int H, int valid, int lane)
 {
-    typedef C128SolveLds<KD, OP, DKS, METHOD, NRHS> LY;
-    typedef TileLds<OP> TL;
-    typedef typename TL::elem elem;
-    const int lane = 16 * ln.q + ln.n;
-    // the row scales of this lane's two tokens, every right-hand side: in flight while the chunk is inverted
-    float raw_s[NRHS][2];
 #pragma unroll
     for (int k = 0; k < NRHS; ++k)
 #pragma unroll
@@ -194,16 +185,22 @@ __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc,
             const int rc = row < valid ? row : valid - 1;
             raw_s[k][t] = rhs.r[k].scale ? rhs.r[k].scale[(tok0 + rc) * H + h] : 1.f;
         }
-    v4f D[10], Wc[2][4];
-    RhsHalf<OP> x;
-    x.init(rhs.r[0], tok0, h, H, valid, ln);
-    c128_invert<KD, OP, METHOD, DKS, W>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
-        // X's first column group: requested as soon as the keys' registers are free, in flight during the last 40 tile
-        // products of the recursion and while the inverse's tiles are published
-        __builtin_amdgcn_sched_barrier(0);
-        if (W < x.n_group()) x.issue(W);
-        __builtin_amdgcn_sched_barrier(0);
-    });
+}
+
+// The inverse (D: this wave's diagonal block, Wc: its two tile columns of the off-diagonal block, as the recursion leaves
+// them) applied to NRHS right-hand sides.  The sides share the inverse: its tiles are published once per right-hand side
+// (their columns scaled by that side's s), all sets before the one barrier, so that nothing of the inverse stays in
+// registers afterwards.  x: initialised for the first right-hand side, its first column group (W) already requested
+// (taken by value: through a reference its row registers ended up in scratch memory for fp32 operands).
+// tiles_lds: NRHS * TileLds<OP>::BYTES that both waves are done with when they arrive here (a barrier comes first);
+// scale_lds: 128 floats per wave.
+template <int OP, int W, int NRHS>
+__device__ __forceinline__ void c128_apply(char* tiles_lds, char* scale_lds, v4f (&D)[10], v4f (&Wc)[2][4], const float (&raw_s)[NRHS][2],
+                                           RhsHalf<OP> x, const RhsList& rhs, int64_t tok0, int h, int H, int valid, Lane ln)
+{
+    typedef TileLds<OP> TL;
+    typedef typename TL::elem elem;
+    const int lane = 16 * ln.q + ln.n;
     // the diagonal tiles in exact unit-triangular form
 #pragma unroll
     for (int d = 0; d < 4; ++d)
@@ -212,10 +209,10 @@ __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc,
             const int rr = W == 0 ? 4 * ln.q + r : ln.n, cc = W == 0 ? ln.n : 4 * ln.q + r;
             D[tix(d, d)][r] = (rr == cc) ? 1.f : ((rr > cc) ? D[tix(d, d)][r] : 0.f);
         }
-    elem* tiles = reinterpret_cast<elem*>(lds + LY::TILES);
-    float* sc = reinterpret_cast<float*>(lds + LY::SCALE) + 128 * W;
+    elem* tiles = reinterpret_cast<elem*>(tiles_lds);
+    float* sc = reinterpret_cast<float*>(scale_lds) + 128 * W;
     constexpr int VEC = RhsHalf<OP>::VEC;
-    __syncthreads();  // nobody reads the keys any more
+    __syncthreads();  // nobody reads what the recursion kept where the tiles go
 #pragma unroll
     for (int k = 0; k < NRHS; ++k) {
         // s by the two index patterns
@@ -287,6 +284,27 @@ __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc,
             if (gi < n_group) x.issue(gi);  // (d_x > 128 only; started earlier it would cost the registers of a second group)
         }
     }
+}
+
+template <int KD, int OP, int METHOD, int DKS, int W, int NRHS>
+__device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
+                                                      int64_t tok_stride, const RhsList& rhs, int64_t tok0, int h, int H, int valid,
+                                                      int aux, Lane ln)
+{
+    typedef C128SolveLds<KD, OP, DKS, METHOD, NRHS> LY;
+    float raw_s[NRHS][2];  // in flight while the chunk is inverted
+    c128_load_scales<NRHS>(raw_s, rhs, tok0, h, H, valid, 16 * ln.q + ln.n);
+    v4f D[10], Wc[2][4];
+    RhsHalf<OP> x;
+    x.init(rhs.r[0], tok0, h, H, valid, ln);
+    c128_invert<KD, OP, METHOD, DKS, W>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
+        // X's first column group: requested as soon as the keys' registers are free, in flight during the last 40 tile
+        // products of the recursion and while the inverse's tiles are published
+        __builtin_amdgcn_sched_barrier(0);
+        if (W < x.n_group()) x.issue(W);
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    c128_apply<OP, W, NRHS>(lds + LY::TILES, lds + LY::SCALE, D, Wc, raw_s, x, rhs, tok0, h, H, valid, ln);
 }
 
 // Fused kernel, scalar / no-gate kinds, C = 128, d_k = 64 or 128: blocked or mixed recursion, then the inverse applied to

@@ -3,7 +3,7 @@
 #include "dispatch.hpp"
 #include "solve.hpp"
 #if TRIINV_INST_NB == 8
-#include "c128_solve.hpp"
+#include "c128_kda_solve.hpp"
 #endif
 
 #ifndef TRIINV_INST_NB
@@ -31,6 +31,14 @@ static RhsList rhs_of(const SolveArgs& a)
     return l;
 }
 
+// The two-wavefront kernels address a right-hand side with 32-bit row offsets: 128 rows of H * d_x elements.
+[[maybe_unused]] static bool rows_fit_32_bits(const SolveArgs& a)
+{
+    for (int k = 0; k < a.n_rhs; ++k)
+        if ((int64_t)a.f.H * a.d_x[k] * (OP == OP_F32 ? 4 : 2) * 128 >= (1LL << 31)) return false;
+    return true;
+}
+
 // Two right-hand sides per launch are built at C <= 64.
 constexpr bool HAS_PAIR = NB <= 4;
 
@@ -45,8 +53,7 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     // single right-hand side as well (the one-wavefront build of that case does not fit the register file without spilling).
     constexpr bool SINGLE_ON_TWO_WAVES = KD != OP_F32 && DKS == 2;
     if (a.n_rhs == 2 || SINGLE_ON_TWO_WAVES) {
-        for (int k = 0; k < a.n_rhs; ++k)  // its 32-bit row offsets: 128 rows of H * d_x elements
-            if ((int64_t)f.H * a.d_x[k] * (OP == OP_F32 ? 4 : 2) * 128 >= (1LL << 31)) return 1;
+        if (!rows_fit_32_bits(a)) return 1;
         if constexpr (SINGLE_ON_TWO_WAVES)
             if (a.n_rhs == 1)
                 return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 1>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
@@ -83,6 +90,17 @@ template <int KD, int DKS> static int gdn_method(const SolveArgs& a)
 template <int METHOD> static int go_kda(const SolveArgs& a)
 {
     const GdnArgs& f = a.f;
+#if TRIINV_INST_NB == 8
+    // C = 128: one chunk per workgroup of two wavefronts (c128_kda_solve.hpp)
+    if (!rows_fit_32_bits(a)) return 1;
+    if (a.n_rhs == 1)
+        return launch_kernel(f.dry, k_kda_tri_solve_c128<OP, METHOD, 1>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K, f.beta, f.g,
+                             rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.k_dt, f.iters);
+    if constexpr (OP != OP_F32)  // two sets of fp32 tiles do not fit the LDS budget of three workgroups per compute unit
+        return launch_kernel(f.dry, k_kda_tri_solve_c128<OP, METHOD, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K, f.beta, f.g,
+                             rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.k_dt, f.iters);
+    return 1;
+#else
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {
         return launch_kernel(f.dry, k_kda_tri_solve<OP, NB, METHOD, WPB, 1>, grid, block, 0, f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk,
@@ -93,6 +111,7 @@ template <int METHOD> static int go_kda(const SolveArgs& a)
                            f.map, f.H, f.d_k, f.k_dt, f.iters, WPB > 1 ? head_spread(f.H) : 0);
     }
     return 1;
+#endif
 }
 
 #if TRIINV_INST_NB <= 4
@@ -123,11 +142,9 @@ int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a
     if (f.refine) return 1;
     if (a.n_rhs < 1 || a.n_rhs > MAX_RHS) return 1;
     if (f.gate == G_CHANNEL) {
-#if TRIINV_INST_NB <= 4
         if (f.method == M_BLOCK) return go_kda<M_BLOCK>(a);
         if (f.method == M_MIXED) return go_kda<M_MIXED>(a);
-#endif
-        return 1;  // C = 128: the per-channel Gram passes and the right-hand sides do not fit one wavefront's registers
+        return 1;
     }
     if (f.k_dt == OP_F32) {
         if (f.d_k == 64) return gdn_method<OP_F32, 4>(a);

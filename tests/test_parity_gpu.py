@@ -785,7 +785,7 @@ def test_sixteen_bit_result(C, out):
     T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 0, C)
     K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
     for method, op in [(tri.BLOCK_RECURSIVE, tri.BF16), (tri.MIXED, tri.F16), (tri.BLOCK_DIRECT, tri.F32), (tri.NEUMANN, tri.F32),
-                       (tri.NEWTON_SCHULZ, tri.F32)]:
+                       (tri.NEWTON_SCHULZ, tri.F32), (tri.FWD_SUBST, tri.F32)]:
         n_mat = T_ref.shape[0]
         guard = torch.full((n_mat + 1, C, C), 7.0, device=DEV, dtype=out)
         tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=guard[:n_mat], method=method, op_dtype=op)
@@ -796,9 +796,10 @@ def test_sixteen_bit_result(C, out):
         check(guard[:n_mat].float(), T_ref, TOL[op] + OUT_U[out], f"16-bit out C={C} {ids((method, op))}")
     # standalone entry point and the per-channel gate
     A32 = torch.from_numpy(oracle.build_A_ragged(inp["K"], inp["beta"], inp["g"], 0, C).astype(np.float32)).to(DEV)
-    Ts = tri.tri_inv_ex(A32, method=tri.BLOCK_RECURSIVE, op_dtype=tri.F32, out_dtype=out)
-    assert Ts.dtype == out
-    check(Ts.float(), oracle.tri_inv(A32.cpu()), 1e-5 + OUT_U[out], f"16-bit out standalone C={C}")
+    for method in (tri.BLOCK_RECURSIVE, tri.FWD_SUBST):
+        Ts = tri.tri_inv_ex(A32, method=method, op_dtype=tri.F32, out_dtype=out)
+        assert Ts.dtype == out
+        check(Ts.float(), oracle.tri_inv(A32.cpu()), 1e-5 + OUT_U[out], f"16-bit out standalone {tri.METHOD_NAMES[method]} C={C}")
     inp3 = si.make_inputs(si.workload(3, B=1, Tlen=2 * C + 5, H=3, C=C))
     T3 = tri.gdn_chunk_tri_inv_ex(inp3["K"].to(DEV), inp3["beta"].to(DEV), inp3["g"].to(DEV), C, gate_kind=tri.GATE_PER_CHANNEL,
                                   out_dtype=out)
@@ -808,8 +809,8 @@ def test_sixteen_bit_result(C, out):
 
 def test_sixteen_bit_result_argument_errors():
     A = torch.zeros(2, 64, 64, device=DEV)
-    with pytest.raises(tri.TriInvError) as e:     # forward substitution stores element by element: fp32 only
-        tri.tri_inv_ex(A, method=tri.FWD_SUBST, out_dtype=torch.bfloat16)
+    with pytest.raises(tri.TriInvError) as e:     # the shuffle variant of forward substitution: fp32 result only
+        tri.tri_inv_ex(A, method=tri.FWD_SUBST, out_dtype=torch.bfloat16, flags=tri.FLAG_FWD_SHUFFLE)
     assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:     # both output types at once
         tri.lib()  # loaded
@@ -1065,7 +1066,8 @@ def test_solve_matches_oracle(idx, kw, method, op):
 @pytest.mark.parametrize("Tlen", [512, 300])
 def test_solve_c128_stress_recipe(Tlen, method, op):
     # the C = 128 stress recipe (large growth in the inverse), full and short last chunk, scalar-gated variant included
-    for idx, kw in ((4, dict(Tlen=Tlen, H=3)), (1, dict(Tlen=Tlen, H=3, C=128))):
+    # and the per-channel gate (two wavefronts per chunk, the right-hand side requested after the recursion)
+    for idx, kw in ((4, dict(Tlen=Tlen, H=3)), (1, dict(Tlen=Tlen, H=3, C=128)), (3, dict(B=1, Tlen=Tlen, H=3, C=128))):
         w, inp, rhs = solve_case(idx, 128, op, **kw)
         W_ref = oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], rhs["row_scale"], w.gate_kind, w.C)
         g = None if inp["g"] is None else inp["g"].to(DEV)
@@ -1088,7 +1090,7 @@ def test_solve_column_counts(d_x, op):
                 ctx=dict(inp=inp, rhs=rhs, gate_kind=w.gate_kind, op=op, scale=False))
 
 
-@pytest.mark.parametrize("C", [16, 32, 64])
+@pytest.mark.parametrize("C", [16, 32, 64, 128])
 @pytest.mark.parametrize("Tlen", [1, 50, 64, 150])
 @pytest.mark.parametrize("gate_kind", [tri.GATE_SCALAR, tri.GATE_PER_CHANNEL, tri.GATE_NONE])
 def test_solve_chunk_sizes_and_short_last_chunk(C, Tlen, gate_kind):
@@ -1126,10 +1128,11 @@ def test_solve_rejects_what_it_does_not_build():
         with pytest.raises(tri.TriInvError) as e:
             tri.gdn_chunk_tri_solve(K, beta, g, X, 64, **kwargs)
         assert e.value.status == -9
-    w3, inp3, rhs3 = solve_case(3, 128, tri.BF16, B=1, Tlen=128, H=2)
-    with pytest.raises(tri.TriInvError) as e:                                           # per-channel gate at C = 128
-        tri.gdn_chunk_tri_solve(inp3["K"].to(DEV), inp3["beta"].to(DEV), inp3["g"].to(DEV), rhs3["X"].to(DEV), 128,
-                                gate_kind=tri.GATE_PER_CHANNEL)
+    w3, inp3, rhs3 = solve_case(3, 128, tri.F32, B=1, Tlen=128, H=2)
+    X3 = rhs3["X"].to(DEV)
+    with pytest.raises(tri.TriInvError) as e:                                           # two fp32 right-hand sides at C = 128
+        tri.gdn_chunk_tri_solve_multi(inp3["K"].to(DEV), inp3["beta"].to(DEV), inp3["g"].to(DEV), [X3, X3.clone()], 128,
+                                      gate_kind=tri.GATE_PER_CHANNEL)
     assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:                                           # in place
         tri.gdn_chunk_tri_solve(K, beta, g, X, 64, W=X)
@@ -1142,8 +1145,6 @@ def test_solve_rejects_what_it_does_not_build():
 @pytest.mark.parametrize("gate_kind", [0, 1, 2])
 @pytest.mark.parametrize("C", [32, 64, 128])
 def test_solve_packed_variable_length_sequences(C, gate_kind):
-    if C == 128 and gate_kind == 1:
-        pytest.skip("the per-channel gate of the applied-inverse kernels is built at C <= 64")
     H, d_k, d_x = 3, 128, 72
     seqlens = [C, 1, 0, 2 * C + 5, C - 1, 3 * C, 0, 17]
     total = sum(seqlens)
@@ -1229,7 +1230,8 @@ def test_solve_full_size_workload(idx):
 
 @pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
 @pytest.mark.parametrize("idx,kw", [(1, dict(Tlen=300, H=4)), (3, dict(B=2, Tlen=128, H=3)), (4, dict(Tlen=200, H=4, C=32)),
-                                    (1, dict(Tlen=96, H=2, C=16)), (4, dict(Tlen=300, H=3)), (1, dict(Tlen=256, H=2, C=128, d_k=64))])
+                                    (1, dict(Tlen=96, H=2, C=16)), (4, dict(Tlen=300, H=3)), (1, dict(Tlen=256, H=2, C=128, d_k=64)),
+                                    (3, dict(B=1, Tlen=300, H=2, C=128))])
 def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
     # two right-hand sides of different widths and scales in one launch: each result is what a launch of its own gives
     # (bit for bit at C <= 64: the same kernels' arithmetic), and matches the oracle
@@ -1246,7 +1248,8 @@ def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
         E1 = tri.gdn_chunk_tri_solve(K, beta, g, X1, w.C, gate_kind=w.gate_kind, method=method)
         E2 = tri.gdn_chunk_tri_solve(K, beta, g, X2, w.C, row_scale=s2, gate_kind=w.gate_kind, method=method)
         torch.cuda.synchronize()
-        if w.C < 128:       # (at C = 128 the pair runs on two wavefronts per chunk, the single launch on one: same method, other kernel)
+        if w.C < 128 or w.gate_kind == tri.GATE_PER_CHANNEL:
+            # (scalar / no gate at C = 128: the pair runs on two wavefronts per chunk, the single launch on one: same method, other kernel)
             assert torch.equal(W1, E1) and torch.equal(W2, E2)
         check_solve(W1, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], None, w.gate_kind, w.C), SOLVE_TOL[op], "rhs 0", C=w.C)
         check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], r2["row_scale"], w.gate_kind, w.C),
