@@ -32,8 +32,8 @@ METRIC = "64x64 tri-inversions/sec + effective TFLOP/s & GB/s vs roofline; rel e
 # cannot be read from inside the process): a profiled constant with the summary it was read from, keyed by
 # (workload index, method, op_dtype).  Absent = not profiled for that configuration (reported as null).
 PROFILED_TRAFFIC = {(2, 1, 2): (545.4e6, "profiles/k_gdn_tri_inv_block_bf16_workload2.txt"),
-                    (3, 1, 2): (2149.9e6, "profiles/k_kda_tri_inv_block_bf16_workload3.txt"),
-                    (4, 1, 2): (809.9e6, "profiles/k_gdn_tri_inv_block_bf16_workload4.txt")}
+                    (3, 1, 2): (2150.0e6, "profiles/k_kda_tri_inv_block_bf16_workload3.txt"),
+                    (4, 1, 2): (810.0e6, "profiles/k_gdn_tri_inv_c128_block_bf16_workload4.txt")}
 
 
 def algorithmic_bytes_per_matrix(w, fused: bool, in_bytes: int = 4, out_bytes: int = 4) -> int:

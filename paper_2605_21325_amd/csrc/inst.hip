@@ -118,8 +118,10 @@ template <int METHOD> constexpr unsigned occupancy_pad_bytes()
 template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(const GdnArgs& a)
 {
 #if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
-    // C = 128, the recursions: one matrix per workgroup of two wavefronts (c128.hpp)
-    if constexpr (!REFINE && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT))
+    // C = 128, the recursions with 16-bit operands: one matrix per workgroup of two wavefronts (c128.hpp).  fp32 operands
+    // keep one wavefront per matrix: their four-instruction tile products make the kernel matrix-core bound, and the
+    // exchange of fp32 tiles through LDS costs more than the second wavefront returns (250 against 226 us on the stress workload).
+    if constexpr (!REFINE && OP != OP_F32 && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT))
         return launch_kernel(a.dry, k_gdn_tri_inv_c128<KD, OP, METHOD, DKS>, dim3((unsigned)a.n_mat), dim3(128), 0, a.stream, a.K, a.beta,
                              a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
     else
