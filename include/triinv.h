@@ -94,8 +94,9 @@ typedef enum {
                                     the scalar / no-gate kinds only.  Anything else returns TRIINV_ERR_UNSUPPORTED */
 #define TRIINV_FLAG_OUT_F16 0x2u  /* T holds fp16 elements: [n_mat][C][C], 2 bytes each (pass the buffer as float*) */
 #define TRIINV_FLAG_OUT_BF16 0x4u /* T holds bf16 elements.  The fp32 result is rounded to nearest even on the way
-                                     out; the diagonal is still exactly 1, the upper triangle exactly 0.  Not
-                                     built for TRIINV_FWD_SUBST; both flags at once: TRIINV_ERR_BAD_DTYPE */
+                                     out; the diagonal is still exactly 1, the upper triangle exactly 0.  Every
+                                     method (not with TRIINV_FLAG_FWD_SHUFFLE); both flags at once:
+                                     TRIINV_ERR_BAD_DTYPE */
 
 #define TRIINV_FLAG_FWD_SHUFFLE 0x8u /* tri_inv_ex, TRIINV_FWD_SUBST, C = 64: broadcast the entries of A with wavefront
                                        shuffles instead of through LDS (the plain shuffle baseline; slower) */
@@ -163,8 +164,11 @@ int gdn_chunk_tri_inv(const void* K, const float* beta, const float* g, float* T
  *              to op_dtype, a = an anchor row of g.  C <= 64: one anchor per 16 rows, so only the
  *              fall of g within any 16 consecutive tokens must stay below ~80 (fp32, bf16 operands)
  *              or ~10 (fp16 operands), however strong the decay over the whole chunk is (g is taken
- *              to fall along the chunk, as a cumulative log-decay does).  C = 128: one anchor, the
- *              chunk's middle row, and the bound applies to the fall of g over the whole chunk.
+ *              to fall along the chunk, as a cumulative log-decay does).  C = 128: the recursions
+ *              (TRIINV_BLOCK_RECURSIVE, _MIXED, _MIXED_B32, _BLOCK_DIRECT) use one anchor per 16 rows inside
+ *              the two 64 x 64 diagonal blocks and row 64 for the block below them, so the bound applies to
+ *              the fall of g over 64 tokens; the other methods use one anchor, the chunk's middle row, and
+ *              the bound applies to the fall of g over the whole chunk.
  *   gate_kind  triinv_gate (KDA row of Table 1 for TRIINV_GATE_PER_CHANNEL).
  *   method, op_dtype, hip_stream, flags: as in tri_inv_ex.
  */
@@ -228,9 +232,10 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
  *              call (rows of a short last chunk's padding do not exist and are not written).  Must
  *              not overlap X.  Caller-owned.
  *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
- *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R).  C = 128 takes the scalar /
- *              no-gate kinds with d_k = 64 or 128 only (not fp32 keys with d_k = 128); C <= 64 takes every
- *              gate kind and every supported d_k.
+ *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R).  C <= 64 takes every gate kind
+ *              and every supported d_k.  C = 128 takes the scalar / no-gate kinds with d_k = 64 or 128 (not
+ *              fp32 keys with d_k = 128) and the per-channel gate with any supported d_k; there H * d_x *
+ *              128 elements of X must stay below 2^31 bytes.
  *              Anything else returns TRIINV_ERR_UNSUPPORTED.
  *   flags      TRIINV_FLAG_MXR_R only.
  * Accuracy: that of the method's inverse (see tri_inv_ex) plus one rounding of the scaled inverse
@@ -246,7 +251,8 @@ int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g,
  * gdn_chunk_tri_solve_multi: gdn_chunk_tri_solve for one or two right-hand sides that share the inverse,
  *     W_k = (I + A)^{-1} diag(s_k) X_k,   k = 0 .. n_rhs - 1,
  * with A built and inverted once per chunk (e.g. the key-side and the value-side product of a layer in one pass).
- *   n_rhs       1 or 2 (TRIINV_ERR_BAD_SHAPE otherwise); 2 at C <= 64 only (TRIINV_ERR_UNSUPPORTED at C = 128).
+ *   n_rhs       1 or 2 (TRIINV_ERR_BAD_SHAPE otherwise); 2 at C = 128 for op_dtype fp16 / bf16 only
+ *               (TRIINV_ERR_UNSUPPORTED for fp32).
  *   X, row_scale, W, d_x   HOST arrays of n_rhs entries: device pointers (row_scale[k] may be NULL) and column
  *               counts, each as in gdn_chunk_tri_solve; read during the call only.  No W_k may overlap any
  *               input, scale or other result.

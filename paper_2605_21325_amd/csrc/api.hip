@@ -358,6 +358,6 @@ const char* triinv_status_string(int status)
     }
 }
 
-int triinv_version(void) { return 100; }
+int triinv_version(void) { return 200; }
 
 }  // extern "C"

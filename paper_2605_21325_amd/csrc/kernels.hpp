@@ -585,7 +585,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_buffer(Out Tm, int C)
 // offset is a register is not safe here: the compiler places no wait state between such a store and a vector-ALU write
 // of its data registers (it guards only the immediate form), and with a write in the very next slot the store now and
 // then sent the new value of its first data register: about one matrix in 10^6 came out with the next strip's values
-// in 16 of its elements.  With the immediate form the compiler inserts the wait state itself.
+// in 16 of its elements.  With the immediate form the compiler inserts the wait state itself.  (The scalar form followed by
+// an explicit two-slot wait that keeps the data registers alive measured the same: +0.9 % at C = 64, -0.9 % at C = 128.)
 __device__ __forceinline__ void stream_store(v4u v, __amdgpu_buffer_rsrc_t out, int lane_offset, int uniform_offset = 0)
 {
     __builtin_amdgcn_raw_buffer_store_b128(v, out, lane_offset + uniform_offset, 0, CACHE_SC0_SC1_NT);
