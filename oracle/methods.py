@@ -183,3 +183,48 @@ def forward_substitution(L, op: Optional[str] = None):
         row[i] = 1.0
         T[i, :] = row
     return T
+
+
+# ----------------------------------------------------------------------------- closed forms of the same methods
+# What each iteration above must equal in exact arithmetic, written from the closed form rather than from the
+# iteration: the pins hold the algorithm statements above against these.
+def neumann_factor_product(L, k_max: Optional[int] = None):
+    """prod_{k=0}^{k_max} (I + (-L)^(2^k)), the product form of the truncated Neumann series (paper Sec. 3.2):
+    equals sum_{i < 2^(k_max+1)} (-L)^i, i.e. (I + L)^{-1} once 2^(k_max+1) >= n.  Powers by explicit repeated
+    multiplication from -L (no squaring of an intermediate that the product also uses)."""
+    L = _strict_lower(L)
+    n = L.shape[0]
+    if k_max is None:
+        k_max = max(int(np.ceil(np.log2(n))) - 1, 0)
+    out = np.eye(n)
+    for k in range(k_max + 1):
+        out = out @ (np.eye(n) + np.linalg.matrix_power(-L, 2 ** k))
+    return out
+
+
+def newton_schulz_closed_form(L, m: int, X0=None):
+    """The m-th Newton-Schulz iterate from its residual recurrence E_{k+1} = E_k^2 (paper Eq. 8):
+    with A = I + L and E_0 = I - A X0,  X_m = A^{-1} (I - E_0^(2^m))."""
+    L = _strict_lower(L)
+    n = L.shape[0]
+    A = np.eye(n) + L
+    X0 = np.eye(n) / n if X0 is None else np.asarray(X0, dtype=np.float64)
+    E = np.eye(n) - A @ X0
+    return np.linalg.solve(A, np.eye(n) - np.linalg.matrix_power(E, 2 ** m))
+
+
+def block_inverse_2x2(L):
+    """(I + L)^{-1} by the 2 x 2 block formula applied recursively (paper Eq. 7 read for a lower-triangular matrix):
+    [[A11, 0], [A21, A22]]^{-1} = [[T11, 0], [-T22 A21 T11, T22]]."""
+    L = _strict_lower(L)
+    n = L.shape[0]
+    if n == 1:
+        return np.ones((1, 1))
+    h = n // 2
+    T11 = block_inverse_2x2(L[:h, :h])
+    T22 = block_inverse_2x2(L[h:, h:])
+    out = np.zeros((n, n))
+    out[:h, :h] = T11
+    out[h:, h:] = T22
+    out[h:, :h] = -T22 @ L[h:, :h] @ T11
+    return out

@@ -236,6 +236,23 @@ def test_paper_algorithms_reach_the_oracle_in_fp64(C):
     assert np.allclose(methods.forward_substitution(L), T, atol=1e-13)
 
 
+@pytest.mark.parametrize("C", [4, 16, 64])
+def test_algorithm_statements_agree_with_their_closed_forms(C):
+    # each iteration, step by step, against the closed form of what it must have reached: the factor product for
+    # Alg. 5 after every iteration, the residual recurrence of Eq. 8 for Alg. 3 after every iteration (also where it
+    # has not converged), the recursive 2 x 2 block formula of Eq. 7 for Alg. 4
+    rng = np.random.default_rng(100 + C)
+    L = np.tril(rng.normal(size=(C, C)) * 0.25, -1)
+    for k in range(int(math.log2(C))):
+        assert np.allclose(methods.mch(L, iters=k), methods.neumann_factor_product(L, k_max=k), atol=1e-11), k
+    assert np.allclose(methods.neumann_factor_product(L), oracle.tri_inv(L[None])[0], atol=1e-11)
+    X0 = np.eye(C) / C + 1e-3 * rng.normal(size=(C, C))
+    for m in range(0, 7):
+        assert np.allclose(methods.ns(L, m=m, X0=X0), methods.newton_schulz_closed_form(L, m, X0=X0), atol=1e-9), m
+    assert np.allclose(methods.mbh(L), methods.block_inverse_2x2(L), atol=1e-12)
+    assert np.allclose(methods.block_inverse_2x2(L), np.linalg.inv(np.eye(C) + L), atol=1e-11)
+
+
 def test_mch_partial_sums():
     # after k iterations of Alg. 5, X = sum_{i < 2^(k+1)} (-L)^i
     rng = np.random.default_rng(5)
