@@ -808,8 +808,9 @@ __global__ __launch_bounds__(64) void k_tri_inv_fwd_shuffle64(const void* __rest
 }
 
 // The same substitution with all of A resident in LDS (tile-packed, 1 KB per lower tile): used at
-// C = 128 when the tiles come out of registers (Gram products), so that the key registers and the
-// tile registers are free before the 128 running values of T take theirs.
+// C >= 64 when the tiles come out of registers (Gram products), so that the key registers and the
+// tile registers are free before the running values of T take theirs (C = 64: 10 KB per wavefront,
+// four wavefronts per SIMD; 140 -> 122 us on the 16 384-matrix workload against the strip-staged form).
 template <int NB> constexpr int fwd_resident_lds_floats() { return NB * (NB + 1) / 2 * 256; }
 
 template <int NB, class ASrc>
@@ -846,7 +847,7 @@ __device__ __forceinline__ void forward_substitution_resident(const ASrc& A, Out
             stream_store(t, Tm, (int64_t)i * C + c);
             // keep the scheduler from hoisting later rows' LDS reads over this row (they do not depend on
             // it, and hoisted by the hundred they would spill the running values of T)
-            if (i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+            if (NB == 8 && i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -873,7 +874,7 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, Out Tm, float*
         return;
     }
     if (METHOD == M_FWD) {
-        if constexpr (NB == 8 && !ASrc::kFromMemory)
+        if constexpr (NB >= 4 && !ASrc::kFromMemory)
             forward_substitution_resident<NB>(src, Tm, lds, ln);
         else
             forward_substitution<NB>(src, Tm, lds, ln);
@@ -903,7 +904,7 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, Out Tm, float*
 template <int NB, int METHOD, bool FUSED = false> constexpr int core_lds_floats()
 {
     static_assert(STORE_LDS_FLOATS >= XPOSE_FLOATS && STORE_LDS_FLOATS >= LEAF_FWD_FLOATS, "the store patch is the largest user");
-    return METHOD != M_FWD ? STORE_LDS_FLOATS : (FUSED && NB == 8) ? fwd_resident_lds_floats<NB>() : fwd_lds_floats<NB>();
+    return METHOD != M_FWD ? STORE_LDS_FLOATS : (FUSED && NB >= 4) ? fwd_resident_lds_floats<NB>() : fwd_lds_floats<NB>();
 }
 
 // The matrix-product kernels may be run in place (A and T the same memory: the composed path of the fused entry points),
