@@ -145,8 +145,8 @@ int tri_inv_ex(const void* A, float* T, int64_t n_mat, int C, int in_dtype, int 
  *   beta are zero, so its matrix still is C x C, with identity rows and columns for the padding;
  *   nothing is read beyond token Tlen - 1 of a sequence.  d_k: a multiple of 32, <= 256.
  *   d_k = 64 and 128 have specialised kernels for every method; other values run a channel loop
- *   with fused kernels for TRIINV_FWD_SUBST, TRIINV_BLOCK_RECURSIVE and TRIINV_BLOCK_DIRECT (and for
- *   every method with the per-channel gate).  A matrix-product method without a fused kernel for the
+ *   with fused kernels for every method at C <= 64 and for TRIINV_FWD_SUBST, TRIINV_BLOCK_RECURSIVE and
+ *   TRIINV_BLOCK_DIRECT at C = 128 (and for every method with the per-channel gate at C <= 64).  A matrix-product method without a fused kernel for the
  *   gate kind / d_k / C asked for runs as two launches on the same stream -- the chunk matrices written
  *   into T as fp32, then inverted in place by the method's tri_inv kernel -- with the same result;
  *   that path needs an fp32 T and does not take TRIINV_FLAG_REFINE1 (TRIINV_ERR_UNSUPPORTED).

@@ -242,12 +242,12 @@ static int kda_method(const GdnArgs& a)
     }
 }
 
-// Head dimensions other than 64 / 128: forward substitution, blocked recursion, blocked recursion from
-// directly solved blocks.
+// Head dimensions other than 64 / 128: every method at C <= 64; forward substitution, blocked recursion and blocked
+// recursion from directly solved blocks at C = 128.
 template <int KD, int METHOD> static int go_any_dk(const GdnArgs& a)
 {
     return launch_kernel(a.dry, k_gdn_any_dk_tri_inv<KD, OP, NB, METHOD>, dim3((unsigned)a.n_mat), dim3(64), 0, a.stream, a.K, a.beta,
-                       a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.out_dt);
+                       a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
 }
 
 template <int KD> static int any_dk_method(const GdnArgs& a)
@@ -260,6 +260,15 @@ template <int KD> static int any_dk_method(const GdnArgs& a)
     case M_BUILD_A: return go_any_dk<KD, M_BUILD_A>(a);
     case M_BLOCK: return go_any_dk<KD, M_BLOCK>(a);
     case M_BLOCK_DIRECT: return go_any_dk<KD, M_BLOCK_DIRECT>(a);
+#if TRIINV_INST_NB <= 4
+    // every tile of A in registers: the whole-matrix methods fit up to C = 64 (C = 128 takes the two-launch path)
+    case M_MIXED: return go_any_dk<KD, M_MIXED>(a);
+#if TRIINV_INST_NB >= 2
+    case M_MIXED32: return go_any_dk<KD, M_MIXED32>(a);
+#endif
+    case M_NEUMANN: return go_any_dk<KD, M_NEUMANN>(a);
+    case M_NEWTON_SCHULZ: return go_any_dk<KD, M_NEWTON_SCHULZ>(a);
+#endif
 #endif
     default: return 1;
     }

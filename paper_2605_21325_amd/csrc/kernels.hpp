@@ -1013,7 +1013,7 @@ __global__ __launch_bounds__(64 * WPB) void k_gdn_tri_inv(const void* __restrict
 template <int KD, int OP, int NB, int METHOD>
 __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restrict__ K, const float* __restrict__ beta,
                                                            const float* __restrict__ g, float* __restrict__ T,
-                                                           int64_t n_chunk, ChunkMap map, int H, int d_k, int out_dt)
+                                                           int64_t n_chunk, ChunkMap map, int H, int d_k, int aux, int out_dt)
 {
     constexpr int C = 16 * NB;
     constexpr int CORE = core_lds_floats<NB, METHOD, true>();
@@ -1030,7 +1030,7 @@ __global__ __launch_bounds__(64) void k_gdn_any_dk_tri_inv(const void* __restric
     build_A_scalar_any_dk<KD, NB, METHOD>(src, static_cast<const char*>(K) + (tok0 * H + h) * (int64_t)d_k * esz,
                                           (int64_t)H * d_k, beta + tok0 * H + h, g ? g + tok0 * H + h : nullptr, H, d_k, lds, ln,
                                           pos.valid);
-    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, out_matrix(T, m, C, out_dt), lds, ln, 0);
+    invert_and_store<OP, NB, METHOD, PreA<NB>, false>(src, out_matrix(T, m, C, out_dt), lds, ln, aux);
 }
 
 // Fused kernel for the per-channel gate: g is [B, Tlen, H, d_k]; the gated keys are rounded to OP.

@@ -259,10 +259,21 @@ def test_other_head_dimensions(C, d_k):
         w = inp["workload"]
         ref = oracle.gdn_chunk_tri_inv(inp["K"], inp["beta"], inp["g"], gate, C)
         g = None if inp["g"] is None else inp["g"].to(DEV)
+        # (C = 64: one fused kernel per method; C = 128: the whole-matrix methods take the two-launch path)
         for method, op in [(tri.BLOCK_RECURSIVE, tri.BF16), (tri.BLOCK_RECURSIVE, tri.F32), (tri.BLOCK_DIRECT, tri.F32),
-                           (tri.BLOCK_DIRECT, tri.F16), (tri.FWD_SUBST, tri.F32)]:
+                           (tri.BLOCK_DIRECT, tri.F16), (tri.FWD_SUBST, tri.F32), (tri.MIXED, tri.BF16), (tri.MIXED_B32, tri.F16),
+                           (tri.NEUMANN, tri.F32), (tri.NEWTON_SCHULZ, tri.BF16), (tri.NEWTON_SCHULZ, tri.F32)]:
             T = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate, method=method, op_dtype=op)
-            check(T, ref, TOL[op], f"d_k={d_k} C={C} {k_dtype} {ids((method, op))}")
+            check(T, ref, TOL[op], f"d_k={d_k} C={C} {k_dtype} {ids((method, op))}", op=op,
+                  method=None if method == tri.NEUMANN else method)
+        if C == 64:     # the fused kernels take a 16-bit result and the mixed recursion's refinement count
+            T16 = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate, method=tri.MIXED, op_dtype=tri.BF16,
+                                           out_dtype=torch.bfloat16)
+            T32 = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate, method=tri.MIXED, op_dtype=tri.BF16)
+            assert torch.equal(T16, T32.bfloat16())
+            T0 = tri.gdn_chunk_tri_inv_ex(inp["K"].to(DEV), inp["beta"].to(DEV), g, C, gate_kind=gate, method=tri.MIXED, op_dtype=tri.BF16,
+                                          flags=tri.flag_mxr_r(0))
+            assert not torch.equal(T0, T32), "the refinement count did not reach the kernel"
 
 
 FP32_KEY_METHODS = [(tri.FWD_SUBST, tri.F32)] + [(m, o) for m in (tri.BLOCK_RECURSIVE, tri.BLOCK_DIRECT, tri.MIXED, tri.MIXED_B32,
@@ -481,12 +492,13 @@ def test_newton_schulz_iteration_count(cases):
 def test_unbuilt_combinations_report_unsupported(cases):
     c = cases[1]
     w, inp = c["w"], c["inp"]
-    # head dimensions other than 64 / 128: the composed path needs an fp32 result and cannot take the refinement flag
-    K96 = torch.zeros(1, 64, 2, 96, dtype=torch.bfloat16, device=DEV)
-    b = torch.zeros(1, 64, 2, device=DEV)
-    for kw in (dict(out_dtype=torch.bfloat16), dict(flags=tri.FLAG_REFINE1)):
+    # head dimensions other than 64 / 128: the refinement flag is not built; at C = 128 the whole-matrix methods take the
+    # composed path, which needs an fp32 result
+    K96 = torch.zeros(1, 128, 2, 96, dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros(1, 128, 2, device=DEV)
+    for C, kw in ((128, dict(out_dtype=torch.bfloat16)), (128, dict(flags=tri.FLAG_REFINE1)), (64, dict(flags=tri.FLAG_REFINE1))):
         with pytest.raises(tri.TriInvError) as e:
-            tri.gdn_chunk_tri_inv_ex(K96, b, b, 64, method=tri.MIXED, **kw)
+            tri.gdn_chunk_tri_inv_ex(K96, b, b, C, method=tri.MIXED, **kw)
         assert e.value.status == -9
     for kw in (dict(method=tri.BLOCK_RECURSIVE, flags=0x80), dict(method=tri.BLOCK_RECURSIVE, flags=8), dict(method=tri.FWD_SUBST, flags=1)):
         with pytest.raises(tri.TriInvError) as e:
