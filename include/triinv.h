@@ -90,8 +90,9 @@ typedef enum {
 #define TRIINV_FLAG_REFINE1 0x1u /* one iterative-refinement step X <- X + (I - X(I+A))X on the whole matrix after the
                                     method (paper Alg. 6, Eq. 9).  Built for every matrix-product method (all but
                                     TRIINV_FWD_SUBST): inside the method's kernel at C <= 64 (tri_inv and every fused
-                                    gate kind); at C = 128 as a second kernel over T, in place, for an fp32 result and
-                                    the scalar / no-gate kinds only.  Anything else returns TRIINV_ERR_UNSUPPORTED */
+                                    gate kind); at C = 128 as a second kernel over T, in place, for an fp32 result
+                                    (head dimensions 64 and 128 for the scalar / no-gate kinds, any supported one for
+                                    the per-channel gate).  Anything else returns TRIINV_ERR_UNSUPPORTED */
 #define TRIINV_FLAG_OUT_F16 0x2u  /* T holds fp16 elements: [n_mat][C][C], 2 bytes each (pass the buffer as float*) */
 #define TRIINV_FLAG_OUT_BF16 0x4u /* T holds bf16 elements.  The fp32 result is rounded to nearest even on the way
                                      out; the diagonal is still exactly 1, the upper triangle exactly 0.  Every

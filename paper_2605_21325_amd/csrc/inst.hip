@@ -7,6 +7,7 @@
 #if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
 #include "c128.hpp"
 #include "c128_kda.hpp"
+#include "kda128.hpp"
 #endif
 
 #ifndef TRIINV_INST_NB
@@ -218,6 +219,16 @@ static int kda_method(const GdnArgs& a)
             default: return 1;
             }
         }
+#if TRIINV_INST_NB == 8 && !TRIINV_INST_FWD
+        // C = 128: the method as usual, then the refinement step as a second pass over T, in place (fp32 result only)
+        if (a.out_dt == OP_F32) {
+            GdnArgs first = a;
+            first.refine = false;
+            if (const int rc = kda_method(first)) return rc;
+            return launch_kernel(a.dry, k_kda_tri_inv_refine128<OP>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K, a.beta, a.g, a.T,
+                                 a.n_chunk, a.map, a.H, a.d_k, a.k_dt);
+        }
+#endif
         return 1;
     }
     switch (a.method) {
@@ -233,9 +244,15 @@ static int kda_method(const GdnArgs& a)
     case M_BLOCK_DIRECT: return go_kda<M_BLOCK_DIRECT>(a);
 #if TRIINV_INST_NB <= 4
     case M_NEWTON_SCHULZ: return go_kda<M_NEWTON_SCHULZ>(a);
-#endif
-#if TRIINV_INST_NB <= 4
     case M_NEUMANN: return go_kda<M_NEUMANN>(a);
+#else
+    // C = 128: one matrix per workgroup of four wavefronts that build A together (kda128.hpp)
+    case M_NEWTON_SCHULZ:
+        return launch_kernel(a.dry, k_kda_tri_inv_ns128<OP>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K, a.beta, a.g, a.T, a.n_chunk,
+                             a.map, a.H, a.d_k, a.k_dt, a.iters, a.out_dt);
+    case M_NEUMANN:
+        return launch_kernel(a.dry, k_kda_tri_inv_neumann128<OP>, dim3((unsigned)a.n_mat), dim3(256), 0, a.stream, a.K, a.beta, a.g, a.T,
+                             a.n_chunk, a.map, a.H, a.d_k, a.k_dt, a.out_dt);
 #endif
 #endif
     default: return 1;

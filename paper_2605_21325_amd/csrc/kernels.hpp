@@ -1350,6 +1350,12 @@ __device__ __forceinline__ void neumann128_run(v4f (&Xt)[9], Opnd<OP> (&yt)[9], 
 //   R^T(i,j) = [i==j] I - Y^T(i,j) - sum_k A(k,j)^T Y(i,k)^T,     X^T(i,j) = Y^T(i,j) + sum_k Y(k,j)^T R(i,k)^T.
 // A wave reads and writes only its own rows of T in global memory, so the pass is safe in place.
 // ---------------------------------------------------------------------------------------------
+// Tile (k, j) of A as a left factor (N orientation, packed): formed on the spot by the sources that hold keys or read memory.
+template <int OP, class ASrc> __device__ __forceinline__ Opnd<OP> left_operand(const ASrc& A, int k, int j)
+{
+    return pack<OP>(A.template get<false>(k, j));
+}
+
 template <int OP, int W, class ASrc>
 __device__ __forceinline__ void refine128_run(const ASrc& A, float* Tm, float* Y, Lane ln, int w)
 {
@@ -1377,7 +1383,7 @@ __device__ __forceinline__ void refine128_run(const ASrc& A, float* Tm, float* Y
 #pragma unroll
             for (int k = 0; k < N128_NB; ++k) {
                 if (k < j || k > i) continue;
-                acc = tn<OP>(pack<OP>(A.template get<false>(k, j)), yo[k], acc);
+                acc = tn<OP>(left_operand<OP>(A, k, j), yo[k], acc);
             }
             v4f r;
 #pragma unroll

@@ -504,21 +504,51 @@ def test_unbuilt_combinations_report_unsupported(cases):
         with pytest.raises(tri.TriInvError) as e:
             tri.tri_inv_ex(torch.zeros(2, 64, 64, device=DEV), op_dtype=tri.F32, **kw)
         assert e.value.status == -9
-    with pytest.raises(tri.TriInvError) as e:   # Newton-Schulz with the per-channel gate at C = 128 is composed: fp32 result only
-        tri.gdn_chunk_tri_inv_ex(torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV), torch.zeros(1, 128, 2, device=DEV),
-                                 torch.zeros(1, 128, 2, 128, device=DEV), 128, gate_kind=tri.GATE_PER_CHANNEL,
-                                 method=tri.NEWTON_SCHULZ, out_dtype=torch.float16)
-    assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:   # refinement at C = 128 is a second pass over an fp32 result
         tri.tri_inv_ex(torch.zeros(2, 128, 128, device=DEV), method=tri.MIXED, op_dtype=tri.F32, flags=1, out_dtype=torch.bfloat16)
     assert e.value.status == -9
-    # per-channel gate + refinement step at C = 128 is not built (the second pass needs A and T side by side)
+    # per-channel gate + refinement step at C = 128: a second pass over an fp32 result as well
     K = torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device=DEV)
     g4 = torch.zeros(1, 128, 2, 128, device=DEV)
     with pytest.raises(tri.TriInvError) as e:
         tri.gdn_chunk_tri_inv_ex(K, torch.zeros(1, 128, 2, device=DEV), g4, 128, gate_kind=tri.GATE_PER_CHANNEL, method=tri.MIXED,
-                                 flags=tri.FLAG_REFINE1)
+                                 flags=tri.FLAG_REFINE1, out_dtype=torch.bfloat16)
     assert e.value.status == -9
+
+
+@pytest.mark.parametrize("k_dtype,d_k", [("bf16", 128), ("f32", 64), ("f16", 96)])
+def test_per_channel_gate_c128_on_four_wavefronts(k_dtype, d_k):
+    """Per-channel gate at C = 128 with the methods that run one matrix per workgroup of four wavefronts (the waves gate and
+    exchange the keys 32 channels at a time): Newton-Schulz, the Neumann product, and the refinement pass behind any method.
+    Short last chunk included; every operand type; a 16-bit result where the method writes it itself."""
+    C = 128
+    inp = si.make_inputs(si.workload(3, B=1, Tlen=2 * C + 41, H=3, C=C, d_k=d_k, k_dtype="f32" if k_dtype == "f16" else k_dtype))
+    if k_dtype == "f16":
+        inp["K"] = inp["K"].to(torch.float16)
+    T_ref = oracle.gdn_chunk_tri_inv_ragged(inp["K"], inp["beta"], inp["g"], 1, C)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    n_mat = T_ref.shape[0]
+    for op in _OPS:
+        ka = None if op == tri.F32 else key_abs_term(inp, 1, C)
+        for method in (tri.NEWTON_SCHULZ, tri.NEUMANN):
+            guard = torch.full((n_mat + 1, C, C), 7.0, device=DEV)
+            tri.gdn_chunk_tri_inv_ex(K, beta, g, C, T=guard[:n_mat], gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op)
+            check(guard[:n_mat], T_ref, TOL[op], f"per-channel C=128 {k_dtype} d_k={d_k} {ids((method, op))}", op=op, key_abs=ka,
+                  method=method if method == tri.NEWTON_SCHULZ else None)
+            assert bool((guard[n_mat] == 7.0).all()), "wrote past the last matrix"
+        T16 = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=tri.NEWTON_SCHULZ, op_dtype=op,
+                                       out_dtype=torch.bfloat16)
+        T32 = tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=tri.NEWTON_SCHULZ, op_dtype=op)
+        assert torch.equal(T16, T32.bfloat16())
+        floor = {tri.F32: 1e-6, tri.F16: 3e-4, tri.BF16: 2e-3}[op]
+        for method in (tri.BLOCK_RECURSIVE, tri.MIXED, tri.NEWTON_SCHULZ, tri.NEUMANN):
+            what = f"per-channel C=128 {k_dtype} d_k={d_k} {ids((method, op))}"
+            e0 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op), T_ref, TOL[op],
+                       what, op=op, key_abs=ka, method=method if method != tri.NEUMANN else None)
+            e1 = check(tri.gdn_chunk_tri_inv_ex(K, beta, g, C, gate_kind=tri.GATE_PER_CHANNEL, method=method, op_dtype=op,
+                                                flags=tri.FLAG_REFINE1), T_ref, TOL[op], what + " + refine", op=op, key_abs=ka,
+                       method=method if method != tri.NEUMANN else None)
+            assert e1 <= max(1.5 * e0, floor), (what, e0, e1)
 
 
 # ------------------------------------------------------------------ full-size workloads, sampled
