@@ -234,9 +234,9 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
  *              not overlap X.  Caller-owned.
  *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
  *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R).  C <= 64 takes every gate kind
- *              and every supported d_k.  C = 128 takes the scalar / no-gate kinds with d_k = 64 or 128 (not
- *              fp32 keys with d_k = 128) and the per-channel gate with any supported d_k; there H * d_x *
- *              128 elements of X must stay below 2^31 bytes.
+ *              and every supported d_k.  C = 128 takes the scalar / no-gate kinds with d_k = 64 or 128 and the
+ *              per-channel gate with any supported d_k; there H * d_x * 128 elements of X must stay below
+ *              2^31 bytes.
  *              Anything else returns TRIINV_ERR_UNSUPPORTED.
  *   flags      TRIINV_FLAG_MXR_R only.
  * Accuracy: that of the method's inverse (see tri_inv_ex) plus one rounding of the scaled inverse

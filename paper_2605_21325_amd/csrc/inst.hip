@@ -301,9 +301,22 @@ int CAT(launch_gdn_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP, SUFFIX)(const GdnArg
         if (a.d_k == 64) return gdn_method<OP_F32, 4>(a);
 #if TRIINV_INST_NB <= 4
         if (a.d_k == 128) return gdn_method<OP_F32, 8>(a);
+#elif !TRIINV_INST_FWD
+        // C = 128 with 128 fp32 channels: on one wavefront the chunk's keys alone would take 256 registers per lane.  The
+        // two-wavefront recursions (16-bit operands) hold half of them each; everything else runs the channel loop below
+        // (keys consumed 32 channels at a time) like the other head dimensions
+        if constexpr (OP != OP_F32) {
+            if (a.d_k == 128 && !a.refine) {
+                switch (a.method) {
+                case M_BLOCK: return go_gdn<OP_F32, M_BLOCK, 8>(a);
+                case M_MIXED: return go_gdn<OP_F32, M_MIXED, 8>(a);
+                case M_MIXED32: return go_gdn<OP_F32, M_MIXED32, 8>(a);
+                case M_BLOCK_DIRECT: return go_gdn<OP_F32, M_BLOCK_DIRECT, 8>(a);
+                default: break;
+                }
+            }
+        }
 #endif
-        // C = 128 with 128 fp32 channels: the chunk's keys alone would take 256 registers per lane, so that
-        // combination runs the channel loop below (keys consumed 32 channels at a time) like the other head dimensions
     } else if (a.k_dt == OP_BF16) {
         if (a.d_k == 64) return gdn_method<OP_BF16, 2>(a);
         if (a.d_k == 128) return gdn_method<OP_BF16, 4>(a);

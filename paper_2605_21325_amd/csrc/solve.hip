@@ -51,7 +51,8 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     // faster than the 128-byte pieces of the column split (data movers with the two access patterns: 142 against 176 us
     // on the stress workload; the kernels: 165 against 179 us).  16-bit keys of d_k = 64 take the two-wavefront kernel for a
     // single right-hand side as well (the one-wavefront build of that case does not fit the register file without spilling).
-    constexpr bool SINGLE_ON_TWO_WAVES = KD != OP_F32 && DKS == 2;
+    // fp32 keys of d_k = 128 (DKS = 8) exist on two wavefronts only: one wavefront cannot hold a chunk's 256 registers of keys.
+    constexpr bool SINGLE_ON_TWO_WAVES = (KD != OP_F32 && DKS == 2) || (KD == OP_F32 && DKS == 8);
     if (a.n_rhs == 2 || SINGLE_ON_TWO_WAVES) {
         if (!rows_fit_32_bits(a)) return 1;
         if constexpr (SINGLE_ON_TWO_WAVES)
@@ -151,7 +152,7 @@ int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a
 #if TRIINV_INST_NB <= 4
         if (f.d_k == 128) return gdn_method<OP_F32, 8>(a);
 #else
-        if (f.d_k == 128) return 1;  // 128 fp32 channels x 128 rows of keys beside the right-hand sides do not fit the register file
+        if (f.d_k == 128) return gdn_method<OP_F32, 8>(a);  // (two wavefronts per chunk, see go_gdn)
 #endif
     } else if (f.k_dt == OP_BF16) {
         if (f.d_k == 64) return gdn_method<OP_BF16, 2>(a);

@@ -1298,6 +1298,28 @@ def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
                     SOLVE_TOL[op], "rhs 1", C=w.C)
 
 
+@pytest.mark.parametrize("op", [tri.F32, tri.F16, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+def test_solve_fp32_keys_with_128_channels_at_c128(op):
+    """Keys stored in fp32 at d_k = 128, C = 128: a chunk's keys are 256 registers per lane on one wavefront, so this
+    combination exists on two wavefronts per chunk only (each holds half the keys); one and two right-hand sides."""
+    w = si.workload(1, B=1, Tlen=2 * 128 + 37, H=3, C=128, d_k=128, k_dtype="f32")
+    inp = si.make_inputs(w)
+    r1, r2 = si.make_rhs(w, 128, XDT[op]), si.make_rhs(w, 72, XDT[op], seed_offset=1)
+    K, beta, g = inp["K"].to(DEV), inp["beta"].to(DEV), inp["g"].to(DEV)
+    for method in (tri.BLOCK_RECURSIVE, tri.MIXED):
+        W = torch.full(r1["X"].shape, float("nan"), dtype=XDT[op], device=DEV)
+        tri.gdn_chunk_tri_solve(K, beta, g, r1["X"].to(DEV), 128, row_scale=r1["row_scale"].to(DEV), W=W, method=method)
+        check_solve(W, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], r1["row_scale"], w.gate_kind, 128), SOLVE_TOL[op],
+                    f"fp32 keys d_k=128 C=128 {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}", C=128,
+                    ctx=dict(inp=inp, rhs=r1, gate_kind=w.gate_kind, op=op))
+        if op != tri.F32:
+            W1, W2 = tri.gdn_chunk_tri_solve_multi(K, beta, g, [r1["X"].to(DEV), r2["X"].to(DEV)], 128,
+                                                   row_scales=[r1["row_scale"].to(DEV), None], method=method)
+            assert torch.equal(W1, W)
+            check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], None, w.gate_kind, 128), SOLVE_TOL[op],
+                        "rhs 1", C=128)
+
+
 def test_solve_multi_limits():
     w, inp, rhs = solve_case(4, 64, tri.BF16, Tlen=256, H=2)
     K, beta, X = inp["K"].to(DEV), inp["beta"].to(DEV), rhs["X"].to(DEV)
