@@ -596,16 +596,24 @@ __device__ __forceinline__ void stream_store(v4f v, __amdgpu_buffer_rsrc_t out, 
     stream_store(__builtin_bit_cast(v4u, v), out, lane_offset, uniform_offset);
 }
 __device__ __forceinline__ void stream_store(float v, float* p) { __builtin_nontemporal_store(v, p); }
-// element idx of a result matrix: fp32, or rounded to nearest even into the 16-bit type the caller asked for
-__device__ __forceinline__ void stream_store(float v, Out Tm, int64_t idx)
+// Element idx of a result matrix whose element size ESZ is known at compile time (so that the row part of the address
+// folds into the store's immediate offset): fp32, or rounded to nearest even into the 16-bit type the caller asked for.
+// ESZ = 0: the element size is read at run time, one address for both widths.
+template <int ESZ> __device__ __forceinline__ void stream_store(float v, Out Tm, int64_t idx)
 {
-    // one address for both widths (two address streams cost the resident variant its last registers)
-    const int sh = Tm.dt == OP_F32 ? 2 : 1;
-    char* const p = static_cast<char*>(Tm.base) + (idx << sh);
-    if (sh == 2)
-        __builtin_nontemporal_store(v, reinterpret_cast<float*>(p));
-    else
-        __builtin_nontemporal_store((uint16_t)(Tm.dt == OP_F16 ? pack2_f16(v, 0.f) : pack2_bf16(v, 0.f)), reinterpret_cast<uint16_t*>(p));
+    if constexpr (ESZ == 4) {
+        __builtin_nontemporal_store(v, static_cast<float*>(Tm.base) + idx);
+    } else if constexpr (ESZ == 2) {
+        __builtin_nontemporal_store((uint16_t)(Tm.dt == OP_F16 ? pack2_f16(v, 0.f) : pack2_bf16(v, 0.f)),
+                                    static_cast<uint16_t*>(Tm.base) + idx);
+    } else {
+        const int sh = Tm.dt == OP_F32 ? 2 : 1;
+        char* const p = static_cast<char*>(Tm.base) + (idx << sh);
+        if (sh == 2)
+            __builtin_nontemporal_store(v, reinterpret_cast<float*>(p));
+        else
+            __builtin_nontemporal_store((uint16_t)(Tm.dt == OP_F16 ? pack2_f16(v, 0.f) : pack2_bf16(v, 0.f)), reinterpret_cast<uint16_t*>(p));
+    }
 }
 
 constexpr int STORE_LD = 16 * 8 + 4;                  // row stride of the patch (fits C = 128), floats
@@ -713,7 +721,7 @@ __device__ __forceinline__ void store_result(Out Tm, const v4f (&Tt)[NB * (NB + 
 // ---------------------------------------------------------------------------------------------
 template <int NB> constexpr int fwd_lds_floats() { return 2 * 16 * (16 * NB + 4); }
 
-template <int NB, class ASrc>
+template <int NB, int ESZ, class ASrc>
 __device__ __forceinline__ void forward_substitution(const ASrc& A, Out Tm, float* lds, Lane ln)
 {
     constexpr int C = 16 * NB;
@@ -728,7 +736,7 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, Out Tm, floa
         if (p > 0) {
             // rows above this pass's diagonal block: columns >= 64p are zero there
 #pragma unroll 8
-            for (int i = 0; i < 64 * p; ++i) stream_store(0.f, Tm, (int64_t)i * C + c);
+            for (int i = 0; i < 64 * p; ++i) stream_store<ESZ>(0.f, Tm, (int64_t)i * C + c);
         }
         v4f stage[NB];  // tiles (s, 4p..s) of the strip being staged, T orientation = row-major pieces
         stage[4 * p] = A.template get<true>(4 * p, 4 * p);
@@ -755,7 +763,7 @@ __device__ __forceinline__ void forward_substitution(const ASrc& A, Out Tm, floa
                 }
                 const float t = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
                 Tc[i - 64 * p] = t;
-                if (mine) stream_store(t, Tm, (int64_t)i * C + c);
+                if (mine) stream_store<ESZ>(t, Tm, (int64_t)i * C + c);
             }
         }
     }
@@ -813,7 +821,7 @@ __global__ __launch_bounds__(64) void k_tri_inv_fwd_shuffle64(const void* __rest
 // four wavefronts per SIMD; 140 -> 122 us on the 16 384-matrix workload against the strip-staged form).
 template <int NB> constexpr int fwd_resident_lds_floats() { return NB * (NB + 1) / 2 * 256; }
 
-template <int NB, class ASrc>
+template <int NB, int ESZ, class ASrc>
 __device__ __forceinline__ void forward_substitution_resident(const ASrc& A, Out Tm, float* lds, Lane ln)
 {
     constexpr int C = 16 * NB;
@@ -830,7 +838,7 @@ __device__ __forceinline__ void forward_substitution_resident(const ASrc& A, Out
         float Tc[C];
         if (p > 0) {
 #pragma unroll 8
-            for (int i = 0; i < 64 * p; ++i) stream_store(0.f, Tm, (int64_t)i * C + c);
+            for (int i = 0; i < 64 * p; ++i) stream_store<ESZ>(0.f, Tm, (int64_t)i * C + c);
         }
 #pragma unroll
         for (int i = 64 * p; i < C; ++i) {
@@ -844,10 +852,10 @@ __device__ __forceinline__ void forward_substitution_resident(const ASrc& A, Out
             }
             const float t = (c < i) ? -acc : ((c == i) ? 1.f : 0.f);
             Tc[i - 64 * p] = t;
-            stream_store(t, Tm, (int64_t)i * C + c);
+            stream_store<ESZ>(t, Tm, (int64_t)i * C + c);
             // keep the scheduler from hoisting later rows' LDS reads over this row (they do not depend on
             // it, and hoisted by the hundred they would spill the running values of T)
-            if (NB == 8 && i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+            if (i % 4 == 3) __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -874,10 +882,18 @@ __device__ __forceinline__ void invert_and_store(const ASrc& src, Out Tm, float*
         return;
     }
     if (METHOD == M_FWD) {
-        if constexpr (NB >= 4 && !ASrc::kFromMemory)
-            forward_substitution_resident<NB>(src, Tm, lds, ln);
-        else
-            forward_substitution<NB>(src, Tm, lds, ln);
+        // The strip-staged form (standalone entry point, small C) gets one copy per element size of the result: the
+        // wave-uniform branch costs nothing, a run-time element size costs every store its immediate offset (107 against
+        // 116 us on 16 384 matrices of C = 64).  The fused, LDS-resident form keeps one copy with a run-time size: two
+        // copies behind the Gram prologue nearly double its registers (100 -> 193 at C = 64: 122 -> 136 us).
+        if constexpr (NB >= 4 && !ASrc::kFromMemory) {
+            forward_substitution_resident<NB, 0>(src, Tm, lds, ln);
+        } else {
+            if (Tm.dt == OP_F32)
+                forward_substitution<NB, 4>(src, Tm, lds, ln);
+            else
+                forward_substitution<NB, 2>(src, Tm, lds, ln);
+        }
     } else if (METHOD == M_NEWTON_SCHULZ) {
         v4f Xt[NT];
         newton_schulz<OP, NB>(src, Xt, aux, ln);  // aux = number of iterations
