@@ -359,7 +359,8 @@ template <bool K16> __device__ __forceinline__ void widen_key8(const RawKey8<K16
 // J <= I, the left factor k_i exp(g_i - a_I) has an exponent within the decay of 16 tokens and <= 0, the
 // right factor k_j exp(a_I - g_j) an exponent <= 0 for J < I and within the decay of 16 tokens for J = I
 // (log-decays only fall along a chunk), so neither factor can overflow however strong the decay over the
-// whole chunk is; the price is a right factor per (I, J) instead of per J (1.75x the exponentials at C = 64).
+// whole chunk is; the price is a right factor per (I, J) instead of per J, which costs one multiplication by a
+// channel-only factor each (see below), not an exponential.
 // C = 128 (no registers for that): a single anchor, row C/2, both factors within exp(+-half the chunk's decay).
 // The gated keys are rounded to OPG and contracted on the matrix cores, 32 channels per step,
 // accumulating every tile the method needs; nothing but K, G, beta is read, nothing stored.
@@ -372,7 +373,7 @@ template <bool K16> __device__ __forceinline__ void widen_key8(const RawKey8<K16
 // exact products) and gc is not read -- the any-d_k path of the scalar / no-gate kinds.
 template <int OPG, int NB, int METHOD, bool K16, bool GATED = true>
 __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void* Kc, bool is_f16, const float* gc,
-                                                      int64_t row_stride, int d_k, Lane ln, int valid)
+                                                      int64_t row_stride, int d_k, Lane ln, int valid, float* tab = nullptr)
 {
     constexpr int C = 16 * NB;
     constexpr float LOG2E = 1.44269504088896340736f;
@@ -411,35 +412,69 @@ __device__ __forceinline__ void accumulate_gated_gram(PreA<NB>& out, const void*
                     An[i][0] = *reinterpret_cast<const v4f*>(gc + (int64_t)ar * row_stride + ch);
                     An[i][1] = *reinterpret_cast<const v4f*>(gc + (int64_t)ar * row_stride + ch + 4);
                 }
-                float kv[NB][8];
+                // With e_i = (g_i - a_I) log2 e (row i, its tile row's anchor a_I), u_i = k_i 2^(e_i) is the left factor of every
+                // tile in tile row I and v_j = k_j 2^(-e_j) the right factor of the diagonal tile (J, J).  The right factor of
+                // tile (I, J), J < I, differs from v_j by 2^((a_I - a_J) log2 e), which depends on the channel only, not on the
+                // row: those NB (NB - 1) / 2 x 32 factors are computed once per k-step by the whole wave (through LDS: the 16
+                // lanes of a row group hold the same anchors; one writes them, each computes a share of the table) instead
+                // of once per row: 67 exponentials per lane and k-step at C = 64 instead of 112, and no subtraction or scaling
+                // of the exponent per pair either.
+                constexpr int NP = NB * (NB - 1) / 2, NE = 8 * NP;
+                float* anc = tab + ln.q * (8 * NB + NE);  // [NB][8] anchors, then [NP][8] factors, per row group
+                float* fac = anc + 8 * NB;
+                if constexpr (NP > 0) {
+                    if (ln.n == 0) {
 #pragma unroll
-                for (int i = 0; i < NB; ++i) {
-                    widen_key8<K16>(raw[t][i], is_f16, kv[i]);
+                        for (int i = 0; i < NB; ++i) {
+                            *reinterpret_cast<v4f*>(&anc[8 * i]) = An[i][0];
+                            *reinterpret_cast<v4f*>(&anc[8 * i + 4]) = An[i][1];
+                        }
+                    }
+                    wave_lds_sync();
 #pragma unroll
-                    for (int r = 0; r < 8; ++r) kv[i][r] *= keep[i];
+                    for (int k = 0; k < (NE + 15) / 16; ++k) {
+                        const int e = ln.n + 16 * k, p = e >> 3, r = e & 7;
+                        if (e < NE) {  // pair p = (hi, lo), hi > lo, in the order (1,0) (2,0) (2,1) (3,0) (3,1) (3,2)
+                            const int hi = p >= 3 ? 3 : (p >= 1 ? 2 : 1), lo = p - hi * (hi - 1) / 2;
+                            fac[e] = __builtin_amdgcn_exp2f((anc[8 * hi + r] - anc[8 * lo + r]) * LOG2E);
+                        }
+                    }
+                    wave_lds_sync();
                 }
+                GOp<OPG> ppi[NB];
+                float v[NB][8];
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
-                    float up[8];
+                    float kv[8], u[8];
+                    widen_key8<K16>(raw[t][i], is_f16, kv);
 #pragma unroll
                     for (int r = 0; r < 8; ++r) {
-                        const float d = (G[i][r / 4][r % 4] - An[i][r / 4][r % 4]) * LOG2E;
-                        up[r] = kv[i][r] * __builtin_amdgcn_exp2f(d);
+                        const float kk = kv[r] * keep[i];
+                        const float e = (G[i][r / 4][r % 4] - An[i][r / 4][r % 4]) * LOG2E;
+                        u[r] = kk * __builtin_amdgcn_exp2f(e);
+                        v[i][r] = kk * __builtin_amdgcn_exp2f(-e);
                     }
-                    const GOp<OPG> ppi = gpack<OPG>(up);
+                    ppi[i] = gpack<OPG>(u);
+                }
+#pragma unroll
+                for (int i = 0; i < NB; ++i)
 #pragma unroll
                     for (int j = 0; j <= i; ++j) {
                         float dn[8];
+                        if (i == j) {
 #pragma unroll
-                        for (int r = 0; r < 8; ++r) {
-                            const float d = (An[i][r / 4][r % 4] - G[j][r / 4][r % 4]) * LOG2E;
-                            dn[r] = kv[j][r] * __builtin_amdgcn_exp2f(d);
+                            for (int r = 0; r < 8; ++r) dn[r] = v[j][r];
+                        } else {
+                            const int p = i * (i - 1) / 2 + j;
+                            const v4f f0 = *reinterpret_cast<const v4f*>(&fac[8 * p]), f1 = *reinterpret_cast<const v4f*>(&fac[8 * p + 4]);
+#pragma unroll
+                            for (int r = 0; r < 8; ++r) dn[r] = v[j][r] * (r < 4 ? f0[r] : f1[r - 4]);
                         }
                         const GOp<OPG> pmj = gpack<OPG>(dn);
-                        if (need_tile<NB, METHOD>(i, j, false)) out.n[tix(i, j)] = gstep<OPG>(ppi, pmj, out.n[tix(i, j)]);
-                        if (need_tile<NB, METHOD>(i, j, true)) out.t[tix(i, j)] = gstep<OPG>(pmj, ppi, out.t[tix(i, j)]);
+                        if (need_tile<NB, METHOD>(i, j, false)) out.n[tix(i, j)] = gstep<OPG>(ppi[i], pmj, out.n[tix(i, j)]);
+                        if (need_tile<NB, METHOD>(i, j, true)) out.t[tix(i, j)] = gstep<OPG>(pmj, ppi[i], out.t[tix(i, j)]);
                     }
-                }
+                if constexpr (NP > 0) wave_lds_sync();  // (the table is rewritten by the next k-step)
                 continue;
             }
             GOp<OPG> pp[NB], pm[NB];
@@ -498,9 +533,9 @@ __device__ __forceinline__ void build_A_per_channel(PreA<NB>& out, const void* K
             out.t[tix(i, j)] = zero4();
         }
     if (kd == OP_F32)
-        accumulate_gated_gram<OPG, NB, METHOD, false>(out, Kc, false, gc, row_stride, d_k, ln, valid);
+        accumulate_gated_gram<OPG, NB, METHOD, false>(out, Kc, false, gc, row_stride, d_k, ln, valid, lds);
     else
-        accumulate_gated_gram<OPG, NB, METHOD, true>(out, Kc, kd == OP_F16, gc, row_stride, d_k, ln, valid);
+        accumulate_gated_gram<OPG, NB, METHOD, true>(out, Kc, kd == OP_F16, gc, row_stride, d_k, ln, valid, lds);
     // beta_i row scaling and the strictly-lower mask
     const int l = 16 * ln.q + ln.n;
 #pragma unroll
