@@ -252,8 +252,7 @@ int gdn_chunk_tri_solve(const void* K, const float* beta, const float* g,
  * gdn_chunk_tri_solve_multi: gdn_chunk_tri_solve for one or two right-hand sides that share the inverse,
  *     W_k = (I + A)^{-1} diag(s_k) X_k,   k = 0 .. n_rhs - 1,
  * with A built and inverted once per chunk (e.g. the key-side and the value-side product of a layer in one pass).
- *   n_rhs       1 or 2 (TRIINV_ERR_BAD_SHAPE otherwise); 2 at C = 128 for op_dtype fp16 / bf16 only
- *               (TRIINV_ERR_UNSUPPORTED for fp32).
+ *   n_rhs       1 or 2 (TRIINV_ERR_BAD_SHAPE otherwise).
  *   X, row_scale, W, d_x   HOST arrays of n_rhs entries: device pointers (row_scale[k] may be NULL) and column
  *               counts, each as in gdn_chunk_tri_solve; read during the call only.  No W_k may overlap any
  *               input, scale or other result.

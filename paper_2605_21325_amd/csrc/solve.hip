@@ -59,10 +59,9 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
             if (a.n_rhs == 1)
                 return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 1>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
                                      f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
-        if constexpr (OP != OP_F32)  // two sets of fp32 tiles do not fit the LDS budget of three workgroups per compute unit
-            return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K,
-                                 f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
-        return 1;
+        // (fp32 operands: the two sets of fp32 tiles take 93 KB of LDS, one workgroup per compute unit)
+        return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K,
+                             f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
     }
     if constexpr (!SINGLE_ON_TWO_WAVES)
 #endif
@@ -97,10 +96,8 @@ template <int METHOD> static int go_kda(const SolveArgs& a)
     if (a.n_rhs == 1)
         return launch_kernel(f.dry, k_kda_tri_solve_c128<OP, METHOD, 1>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K, f.beta, f.g,
                              rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.k_dt, f.iters);
-    if constexpr (OP != OP_F32)  // two sets of fp32 tiles do not fit the LDS budget of three workgroups per compute unit
-        return launch_kernel(f.dry, k_kda_tri_solve_c128<OP, METHOD, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K, f.beta, f.g,
-                             rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.k_dt, f.iters);
-    return 1;
+    return launch_kernel(f.dry, k_kda_tri_solve_c128<OP, METHOD, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K, f.beta, f.g,
+                         rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.k_dt, f.iters);
 #else
     const dim3 grid((unsigned)((f.n_mat + WPB - 1) / WPB)), block(64 * WPB);
     if (a.n_rhs == 1) {

@@ -1170,12 +1170,6 @@ def test_solve_rejects_what_it_does_not_build():
         with pytest.raises(tri.TriInvError) as e:
             tri.gdn_chunk_tri_solve(K, beta, g, X, 64, **kwargs)
         assert e.value.status == -9
-    w3, inp3, rhs3 = solve_case(3, 128, tri.F32, B=1, Tlen=128, H=2)
-    X3 = rhs3["X"].to(DEV)
-    with pytest.raises(tri.TriInvError) as e:                                           # two fp32 right-hand sides at C = 128
-        tri.gdn_chunk_tri_solve_multi(inp3["K"].to(DEV), inp3["beta"].to(DEV), inp3["g"].to(DEV), [X3, X3.clone()], 128,
-                                      gate_kind=tri.GATE_PER_CHANNEL)
-    assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:                                           # in place
         tri.gdn_chunk_tri_solve(K, beta, g, X, 64, W=X)
     assert e.value.status == -7
@@ -1278,8 +1272,6 @@ def test_solve_two_right_hand_sides_share_one_inversion(idx, kw, op):
     # two right-hand sides of different widths and scales in one launch: each result is what a launch of its own gives
     # (bit for bit at C <= 64: the same kernels' arithmetic), and matches the oracle
     w = si.workload(idx, **kw)
-    if w.C == 128 and op == tri.F32:
-        pytest.skip("two right-hand sides at C = 128 are built for 16-bit operands (two sets of fp32 tiles do not fit the LDS)")
     inp = si.make_inputs(w)
     r1, r2 = si.make_rhs(w, 128, XDT[op]), si.make_rhs(w, 72, XDT[op], seed_offset=1)
     K, beta = inp["K"].to(DEV), inp["beta"].to(DEV)
@@ -1312,20 +1304,16 @@ def test_solve_fp32_keys_with_128_channels_at_c128(op):
         check_solve(W, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r1["X"], r1["row_scale"], w.gate_kind, 128), SOLVE_TOL[op],
                     f"fp32 keys d_k=128 C=128 {tri.METHOD_NAMES[method]} {tri.DTYPE_NAMES[op]}", C=128,
                     ctx=dict(inp=inp, rhs=r1, gate_kind=w.gate_kind, op=op))
-        if op != tri.F32:
-            W1, W2 = tri.gdn_chunk_tri_solve_multi(K, beta, g, [r1["X"].to(DEV), r2["X"].to(DEV)], 128,
-                                                   row_scales=[r1["row_scale"].to(DEV), None], method=method)
-            assert torch.equal(W1, W)
-            check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], None, w.gate_kind, 128), SOLVE_TOL[op],
-                        "rhs 1", C=128)
+        W1, W2 = tri.gdn_chunk_tri_solve_multi(K, beta, g, [r1["X"].to(DEV), r2["X"].to(DEV)], 128,
+                                               row_scales=[r1["row_scale"].to(DEV), None], method=method)
+        assert torch.equal(W1, W)
+        check_solve(W2, oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], r2["X"], None, w.gate_kind, 128), SOLVE_TOL[op],
+                    "rhs 1", C=128)
 
 
 def test_solve_multi_limits():
     w, inp, rhs = solve_case(4, 64, tri.BF16, Tlen=256, H=2)
     K, beta, X = inp["K"].to(DEV), inp["beta"].to(DEV), rhs["X"].to(DEV)
-    with pytest.raises(tri.TriInvError) as e:                                 # two right-hand sides at C = 128, fp32 operands
-        tri.gdn_chunk_tri_solve_multi(K, beta, None, [X.float(), X.float()], 128, gate_kind=tri.GATE_NONE)
-    assert e.value.status == -9
     with pytest.raises(tri.TriInvError) as e:                                 # three
         tri.gdn_chunk_tri_solve_multi(K, beta, None, [X, X.clone(), X.clone()], 64, gate_kind=tri.GATE_NONE)
     assert e.value.status == -5
