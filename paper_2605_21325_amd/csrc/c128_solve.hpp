@@ -20,15 +20,6 @@ template <> struct XHalf<OP_F32> { v2f f; };
 template <> struct XHalf<OP_F16> { v2u u; };
 template <> struct XHalf<OP_BF16> { v2u u; };
 
-template <int OP> __device__ __forceinline__ XHalf<OP> load_xh(const char* p)
-{
-    if constexpr (OP == OP_F32) {
-        return {*reinterpret_cast<const v2f*>(p)};
-    } else {
-        return {*reinterpret_cast<const v2u*>(p)};
-    }
-}
-
 // Column tile c of a 16-row tile row of X as a matrix-core operand: rows 4q + r of this lane's column VEC n + c.
 template <int OP> __device__ __forceinline__ Opnd<OP> xh_operand(const XHalf<OP> (&row)[4], int c)
 {

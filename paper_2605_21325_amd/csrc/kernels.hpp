@@ -226,10 +226,6 @@ template <int KD, int NB, int DKS> struct GramA {
         }
     }
 
-    __device__ __forceinline__ void load_gate(const float* bc, const float* gc, int64_t tok_stride, float* lds, int valid = C)
-    {
-        gate.load(bc, gc, tok_stride, lds, ln, valid);
-    }
     __device__ __forceinline__ void issue_gate(const float* bc, const float* gc, int64_t tok_stride, int valid = C)
     {
         gate.issue(bc, gc, tok_stride, ln, valid);
