@@ -10,7 +10,10 @@ namespace triinv {
 template <int OP, int METHOD, int NRHS> struct C128KdaSolveLds {
     typedef C128KdaLds<OP, METHOD> INV;
     static constexpr int TILES = 0;  // after the recursion, in place of everything it kept: one set of 36 tiles per right-hand side
-    static constexpr int SCALE = INV::BYTES > NRHS * TileLds<OP>::BYTES ? INV::BYTES : NRHS * TileLds<OP>::BYTES;  // 128 floats per wave
+    static constexpr bool BY_ROWS = NRHS == 1;  // one right-hand side: split by rows (c128_apply_rows)
+    static constexpr int XTOP = TileLds<OP>::BYTES;
+    static constexpr int APPLY = BY_ROWS ? XTOP + 16 * 64 * 16 : NRHS * TileLds<OP>::BYTES;
+    static constexpr int SCALE = INV::BYTES > APPLY ? INV::BYTES : APPLY;  // 128 floats per wave
     static constexpr int BYTES = SCALE + 2 * 128 * 4;
 };
 
@@ -26,10 +29,17 @@ __device__ __forceinline__ void c128_kda_invert_and_apply(char* lds, const void*
     c128_kda_invert<OP, METHOD, W>(lds, Kc, kd, gc, row_stride, bc, tok_stride, d_k, valid, aux, ln, D, Wc);
     float raw_s[NRHS][2];
     c128_load_scales<NRHS>(raw_s, rhs, tok0, h, H, valid, 16 * ln.q + ln.n);
-    RhsHalf<OP> x;
-    x.init(rhs.r[0], tok0, h, H, valid, ln);
-    if (W < x.n_group()) x.issue(W);
-    c128_apply<OP, W, NRHS>(lds + LY::TILES, lds + LY::SCALE, D, Wc, raw_s, x, rhs, tok0, h, H, valid, ln);
+    if constexpr (LY::BY_ROWS) {
+        RhsRows<OP> x;
+        x.init(rhs.r[0], tok0, h, H, valid, ln);
+        x.template issue<W>(0);
+        c128_apply_rows<OP, W>(lds + LY::TILES, lds + LY::XTOP, lds + LY::SCALE, D, Wc, raw_s[0], x, ln);
+    } else {
+        RhsHalf<OP> x;
+        x.init(rhs.r[0], tok0, h, H, valid, ln);
+        if (W < x.n_group()) x.issue(W);
+        c128_apply<OP, W, NRHS>(lds + LY::TILES, lds + LY::SCALE, D, Wc, raw_s, x, rhs, tok0, h, H, valid, ln);
+    }
 }
 
 // Fused kernel, per-channel gate, C = 128, any d_k (multiple of 32): blocked or mixed recursion, then the inverse applied

@@ -46,23 +46,26 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
 {
     const GdnArgs& f = a.f;
 #if TRIINV_INST_NB == 8
-    // C = 128, two right-hand sides: one chunk per workgroup of two wavefronts with the right-hand sides split by columns
-    // (c128_solve.hpp).  A single right-hand side keeps the one-wavefront kernel below: its 256-byte row pieces stream
-    // faster than the 128-byte pieces of the column split (data movers with the two access patterns: 142 against 176 us
-    // on the stress workload; the kernels: 165 against 179 us).  16-bit keys of d_k = 64 take the two-wavefront kernel for a
-    // single right-hand side as well (the one-wavefront build of that case does not fit the register file without spilling).
-    // fp32 keys of d_k = 128 (DKS = 8) exist on two wavefronts only: one wavefront cannot hold a chunk's 256 registers of keys.
+    // C = 128 on two wavefronts per chunk (c128_solve.hpp).  Two right-hand sides: split by columns, the inverse's tiles
+    // published once per side.  One right-hand side: split by rows (whole 256-byte row pieces on both waves) where that
+    // kernel is the fastest or the only one -- the blocked recursion with 16-bit operands (166 against 170 us on the
+    // stress workload for the one-wavefront kernel below, 245 against 255 us at d_x = 256), 16-bit keys of d_k = 64 (the
+    // one-wavefront build of that case does not fit the register file without spilling) and fp32 keys of d_k = 128 (one
+    // wavefront cannot hold a chunk's 256 registers of keys).  The mixed recursion and fp32 operands keep the
+    // one-wavefront kernel (164 against 166 us, 363 against 444 us).
     constexpr bool SINGLE_ON_TWO_WAVES = (KD != OP_F32 && DKS == 2) || (KD == OP_F32 && DKS == 8);
+    constexpr bool SINGLE_BY_ROWS = SINGLE_ON_TWO_WAVES || (OP != OP_F32 && METHOD == M_BLOCK);
     if (a.n_rhs == 2 || SINGLE_ON_TWO_WAVES) {
         if (!rows_fit_32_bits(a)) return 1;
-        if constexpr (SINGLE_ON_TWO_WAVES)
-            if (a.n_rhs == 1)
-                return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 1>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
-                                     f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
-        // (fp32 operands: the two sets of fp32 tiles take 93 KB of LDS, one workgroup per compute unit)
+    }
+    if constexpr (SINGLE_BY_ROWS)
+        if (a.n_rhs == 1 && rows_fit_32_bits(a))
+            return launch_kernel(f.dry, k_gdn_tri_solve_c128_rows<KD, OP, METHOD, DKS>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
+                                 f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+    // (fp32 operands: the two sets of fp32 tiles take 93 KB of LDS, one workgroup per compute unit)
+    if (a.n_rhs == 2)
         return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K,
                              f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
-    }
     if constexpr (!SINGLE_ON_TWO_WAVES)
 #endif
     {
