@@ -29,14 +29,9 @@ template <int OP> __device__ __forceinline__ Opnd<OP> xh_operand(const XHalf<OP>
         return {v4f{row[0].f[c], row[1].f[c], row[2].f[c], row[3].f[c]}};
     } else {
         const int d = c >> 1;
-        uint32_t lo, hi;
-        if (c & 1) {
-            lo = (row[0].u[d] >> 16) | (row[1].u[d] & 0xffff0000u);
-            hi = (row[2].u[d] >> 16) | (row[3].u[d] & 0xffff0000u);
-        } else {
-            lo = (row[0].u[d] & 0xffffu) | (row[1].u[d] << 16);
-            hi = (row[2].u[d] & 0xffffu) | (row[3].u[d] << 16);
-        }
+        const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;  // the lower / upper halves of two rows' dwords
+        const uint32_t lo = __builtin_amdgcn_perm(row[1].u[d], row[0].u[d], sel);
+        const uint32_t hi = __builtin_amdgcn_perm(row[3].u[d], row[2].u[d], sel);
         Opnd<OP> o;
         o.x = __builtin_bit_cast(decltype(o.x), v2u{lo, hi});
         return o;
@@ -123,6 +118,22 @@ template <int OP> struct RhsHalf {
         }
     }
 };
+
+// Column tile c of a 16-row tile row of X held as 16-byte row pieces (solve.hpp's XRow), as a matrix-core operand: one
+// byte-permute per register takes the lower (c even) or upper (c odd) halves of two rows' dwords.
+template <int OP> __device__ __forceinline__ Opnd<OP> xrow_operand(const XRow<OP> (&row)[4], int c)
+{
+    if constexpr (OP == OP_F32) {
+        return {v4f{row[0].f[c], row[1].f[c], row[2].f[c], row[3].f[c]}};
+    } else {
+        const int d = c >> 1;
+        const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+        Opnd<OP> o;
+        o.x = __builtin_bit_cast(decltype(o.x), v2u{__builtin_amdgcn_perm(row[1].u[d], row[0].u[d], sel),
+                                                    __builtin_amdgcn_perm(row[3].u[d], row[2].u[d], sel)});
+        return o;
+    }
+}
 
 // One right-hand side split by ROWS: wave W owns rows 64 W .. 64 W + 63 of X and of the result, in whole 256-byte row
 // pieces (a lane owns the 16 bytes one load brings, 16 lanes one row piece, four rows per instruction: the layout of the
@@ -406,8 +417,8 @@ __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc,
     c128_apply<OP, W, NRHS>(lds + LY::TILES, lds + LY::SCALE, D, Wc, raw_s, x, rhs, tok0, h, H, valid, ln);
 }
 
-// LDS of the row-split form: one set of tiles and the top 64 rows of one column group of X as loaded (16 bytes per lane
-// and row: [tile row][r][lane]), both in place of what the recursion kept there.
+// LDS of the row-split form: one set of tiles and the top 64 rows of one column group of X as operand tiles
+// ([tile row][column tile][lane]), both in place of what the recursion kept there.
 template <int KD, int OP, int DKS, int METHOD> struct C128SolveRowsLds {
     typedef C128Lds<KD, OP, DKS, METHOD> INV;
     static constexpr int TILES = 0;
@@ -415,13 +426,14 @@ template <int KD, int OP, int DKS, int METHOD> struct C128SolveRowsLds {
     static constexpr int END = XTOP + 16 * 64 * 16;
     static constexpr int SCALE = INV::BYTES > END ? INV::BYTES : END;  // 128 floats per wave
     static constexpr int BYTES = SCALE + 2 * 128 * 4;
-    static_assert(XTOP % 16 == 0, "16-byte rows");
+    static_assert(XTOP % 16 == 0, "16-byte accesses");
 };
 
 // One right-hand side split by rows: wave 0 computes the top 64 rows of W from its own rows of X; wave 1 the bottom 64
-// from the top rows of X, which wave 0 hands over through LDS as loaded, and its own.  One tile row of W (VEC
-// accumulators) at a time, the operand tiles of X rebuilt from the loaded rows for each (two instructions per operand
-// register).  Both waves read and write whole 256-byte row pieces.  x: its first column group requested.
+// from the top rows of X, which wave 0 hands over through LDS, and its own.  Each wave turns the rows it loaded into
+// operand tiles once (a byte-permute per register) and wave 0 publishes its tiles as they are; one tile row of W (VEC
+// accumulators) is formed at a time.  Both waves read and write whole 256-byte row pieces.
+// x: its first column group requested.
 template <int OP, int W>
 __device__ __forceinline__ void c128_apply_rows(char* tiles_lds, char* xtop_lds, char* scale_lds, v4f (&D)[10], v4f (&Wc)[2][4],
                                                 const float (&raw_s)[2], RhsRows<OP> x, Lane ln)
@@ -431,7 +443,7 @@ __device__ __forceinline__ void c128_apply_rows(char* tiles_lds, char* xtop_lds,
     constexpr int VEC = RhsRows<OP>::VEC;
     c128_unit_diagonal<W>(D, ln);
     elem* tiles = reinterpret_cast<elem*>(tiles_lds);
-    XRow<OP>* xtop = reinterpret_cast<XRow<OP>*>(xtop_lds) + (16 * ln.q + ln.n);
+    Opnd<OP>* xtop = reinterpret_cast<Opnd<OP>*>(xtop_lds) + (16 * ln.q + ln.n);  // tile (j, c) at [(VEC j + c) * 64]
     __syncthreads();  // nobody reads what the recursion kept where the tiles and the rows go
     {
         float s_n[8];
@@ -442,12 +454,14 @@ __device__ __forceinline__ void c128_apply_rows(char* tiles_lds, char* xtop_lds,
     const int n_group = x.n_group();
 #pragma unroll 1
     for (int gi = 0; gi < n_group; ++gi) {
-        if (W == 0) {
+        Opnd<OP> xo[4][VEC];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) xtop[(4 * j + r) * 64] = x.raw[j][r];
-        }
+            for (int c = 0; c < VEC; ++c) {
+                xo[j][c] = xrow_operand<OP>(x.raw[j], c);
+                if (W == 0) xtop[(VEC * j + c) * 64] = xo[j][c];
+            }
         __syncthreads();  // the tiles (first group) and the top rows are in LDS
         int hide = 0;
         asm volatile("" : "+v"(hide));  // keeps the tile reads inside the loop (an offset: the pointer stays an LDS pointer)
@@ -461,22 +475,19 @@ __device__ __forceinline__ void c128_apply_rows(char* tiles_lds, char* xtop_lds,
             if (W == 1) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    XRow<OP> top[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) top[r] = xtop[(4 * j + r) * 64];
                     const Opnd<OP> t = TL::read_t(set + tix(I, j) * TL::TILE_ELEMS, ln);
 #pragma unroll
-                    for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(t, x_operand<OP>(top, c), acc[c]);
+                    for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(t, xtop[(VEC * j + c) * 64 + hide], acc[c]);
                 }
             }
 #pragma unroll
             for (int j = 0; j <= i; ++j) {
                 const Opnd<OP> t = TL::read_t(set + tix(I, 4 * W + j) * TL::TILE_ELEMS, ln);
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(t, x_operand<OP>(x.raw[j], c), acc[c]);
+                for (int c = 0; c < VEC; ++c) acc[c] = tn<OP>(t, xo[j][c], acc[c]);
             }
             x.store(gi, I, acc);
-            __builtin_amdgcn_sched_barrier(0);  // one tile row's reads and operands at a time
+            __builtin_amdgcn_sched_barrier(0);  // one tile row's reads at a time
         }
         if (gi + 1 < n_group) {  // (d_x beyond one group only)
             __syncthreads();     // wave 1 is done with the top rows
