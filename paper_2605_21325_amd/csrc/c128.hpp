@@ -47,27 +47,32 @@ template <int KD, int DKS> struct HalfKeys {
     }
 };
 
-// LDS of one workgroup (three workgroups = six wavefronts per compute unit with 16-bit operands: the kernel alternates
-// between memory phases and arithmetic, and other resident wavefronts keep the memory system busy meanwhile; measured
-// best at three): the bottom half's keys and tile rows 1..3 of the top half's (operand layout: [tile row][k-step][lane],
-// 16 bytes each), the packed tiles of T22 (all ten, T orientation: left factors) and of T11 that the other wave needs
-// (N orientation: right factors), the mail area (wave 0's private area while it inverts its diagonal block -- gate
-// staging, tile transposes, leaf staging -- and later its tiles of W on their way to wave 1) and wave 1's private area.
-// The two store strips take the place of the keys, which are dead by then.
-template <int KD, int OP, int DKS, int METHOD> struct C128Lds {
+// LDS of one workgroup: the bottom half's keys and tile rows 1..3 of the top half's (operand layout:
+// [tile row][k-step][lane], 16 bytes each), the packed tiles of T22 (all ten, T orientation: left factors) and of T11
+// that the other wave needs (N orientation: right factors), wave 0's private area (gate staging, tile transposes, leaf
+// staging) and wave 1's.  The two store strips take the place of the keys, which are dead by then.
+// WITH_MAIL (the storing kernel): wave 0's private area is 8 KB and later carries its tiles of W to wave 1.  With 16-bit
+// keys of d_k = 128 that makes 45 KB, three workgroups = six wavefronts per compute unit, which the storing kernel
+// measured best at (140.5 us on the stress workload against 142.6 us at four: the kernel alternates between memory
+// phases and arithmetic, and other resident wavefronts keep the memory system busy meanwhile).  Without the mail (the
+// applied-inverse kernels, which publish their tiles elsewhere) the same case takes 38 KB and four workgroups fit,
+// which those kernels measured best at (154 against 163 us).
+template <int KD, int OP, int DKS, int METHOD, bool WITH_MAIL = true> struct C128Lds {
     static constexpr int KEY_TILE_ROW = DKS * 64 * 16;                     // bytes of one 16-row tile row of keys
     static constexpr int KEYS_BOT = 0;                                     // 4 tile rows
     static constexpr int KEYS_TOP = KEYS_BOT + 4 * KEY_TILE_ROW;           // tile rows 1..3
     static constexpr int STRIPS = 0;                                       // one store strip per wave (alias the keys)
-    static constexpr int KEYS_END = (KEYS_TOP + 3 * KEY_TILE_ROW) > 2 * STORE_LDS_FLOATS * 4 ? (KEYS_TOP + 3 * KEY_TILE_ROW) : 2 * STORE_LDS_FLOATS * 4;
+    static constexpr int KEYS_END = (KEYS_TOP + 3 * KEY_TILE_ROW) > 2 * STORE_LDS_FLOATS * 4 || !WITH_MAIL ? (KEYS_TOP + 3 * KEY_TILE_ROW) : 2 * STORE_LDS_FLOATS * 4;
     static constexpr int OPND = (int)sizeof(Opnd<OP>);
     static constexpr int T22 = KEYS_END;                                   // 10 tiles
     static constexpr int T11 = T22 + 10 * 64 * OPND;                       // tiles (1,1) (2,1) (3,1) (2,2) (3,2)
-    static constexpr int MAIL = T11 + 5 * 64 * OPND;                       // 8 fp32 tiles; before that wave 0's private area
-    static constexpr int PRIVATE1 = MAIL + 8 * 1024;                       // wave 1's private area
-    static constexpr int PRIVATE1_FLOATS = METHOD == M_BLOCK_DIRECT ? LEAF_FWD_FLOATS : XPOSE_FLOATS;
-    static constexpr int BYTES = PRIVATE1 + PRIVATE1_FLOATS * 4;
+    static constexpr int PRIVATE_FLOATS = METHOD == M_BLOCK_DIRECT ? LEAF_FWD_FLOATS : XPOSE_FLOATS;
+    static constexpr int PRIVATE0 = T11 + 5 * 64 * OPND;                   // wave 0's private area
+    static constexpr int MAIL = PRIVATE0;                                  // (WITH_MAIL) 8 fp32 tiles, after wave 0's private use of the same bytes
+    static constexpr int PRIVATE1 = PRIVATE0 + (WITH_MAIL ? 8 * 1024 : PRIVATE_FLOATS * 4);  // wave 1's private area
+    static constexpr int BYTES = PRIVATE1 + PRIVATE_FLOATS * 4;
     static_assert(XPOSE_FLOATS >= 2 * 128 && 2048 >= LEAF_FWD_FLOATS, "the private areas fit their users");
+    static_assert(PRIVATE0 % 16 == 0 && PRIVATE1 % 16 == 0, "16-byte accesses");
 };
 
 // Slot of tile (d, c) of T11 in the LDS copy (only the five tiles wave 1 reads are there).
@@ -137,15 +142,15 @@ __device__ __forceinline__ void c128_diagonal_block(const DiagSrc& diag, v4f (&D
 // wave's block D is final (a place to send it on its way while the off-diagonal block is formed).
 // keys_done(): called in the second phase once this wave's tiles of A21 exist: the keys' registers and the gate's are
 // free from there on, and 40 tile products follow (a place to start loads whose data is needed after them).
-template <int KD, int OP, int METHOD, int DKS, int W, class Hook, class Hook2, class Hook3 = NoHook>
+template <int KD, int OP, int METHOD, int DKS, int W, bool WITH_MAIL = true, class Hook, class Hook2, class Hook3 = NoHook>
 __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
                                             int64_t tok_stride, int valid, int aux, Lane ln, v4f (&D)[10], v4f (&Wc)[2][4],
                                             Hook keys_loaded, Hook2 block_done, Hook3 keys_done = Hook3())
 {
     typedef typename KeyVec<KD>::type kvec;
-    typedef C128Lds<KD, OP, DKS, METHOD> LY;
+    typedef C128Lds<KD, OP, DKS, METHOD, WITH_MAIL> LY;
     const int lane = 16 * ln.q + ln.n;
-    float* small = reinterpret_cast<float*>(lds + (W == 0 ? LY::MAIL : LY::PRIVATE1));
+    float* small = reinterpret_cast<float*>(lds + (W == 0 ? LY::PRIVATE0 : LY::PRIVATE1));
     kvec* keys_bot = reinterpret_cast<kvec*>(lds + LY::KEYS_BOT);   // [tile row 0..3][k-step][lane]
     kvec* keys_top = reinterpret_cast<kvec*>(lds + LY::KEYS_TOP);   // [tile row 1..3][k-step][lane]
     Opnd<OP>* t22_lds = reinterpret_cast<Opnd<OP>*>(lds + LY::T22);

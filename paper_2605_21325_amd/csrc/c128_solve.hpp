@@ -257,7 +257,7 @@ template <int OP> struct TileLds {
 };
 
 template <int KD, int OP, int DKS, int METHOD, int NRHS> struct C128SolveLds {
-    typedef C128Lds<KD, OP, DKS, METHOD> INV;
+    typedef C128Lds<KD, OP, DKS, METHOD, false> INV;
     static constexpr int TILES = 0;  // after the recursion, in place of the keys: one set of 36 tiles per right-hand side
     static constexpr int SCALE = INV::BYTES > NRHS * TileLds<OP>::BYTES ? INV::BYTES : NRHS * TileLds<OP>::BYTES;  // 128 floats per wave
     static constexpr int BYTES = SCALE + 2 * 128 * 4;
@@ -407,7 +407,7 @@ __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc,
     v4f D[10], Wc[2][4];
     RhsHalf<OP> x;
     x.init(rhs.r[0], tok0, h, H, valid, ln);
-    c128_invert<KD, OP, METHOD, DKS, W>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
+    c128_invert<KD, OP, METHOD, DKS, W, false>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
         // X's first column group: requested as soon as the keys' registers are free, in flight during the last 40 tile
         // products of the recursion and while the inverse's tiles are published
         __builtin_amdgcn_sched_barrier(0);
@@ -420,7 +420,7 @@ __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc,
 // LDS of the row-split form: one set of tiles and the top 64 rows of one column group of X as operand tiles
 // ([tile row][column tile][lane]), both in place of what the recursion kept there.
 template <int KD, int OP, int DKS, int METHOD> struct C128SolveRowsLds {
-    typedef C128Lds<KD, OP, DKS, METHOD> INV;
+    typedef C128Lds<KD, OP, DKS, METHOD, false> INV;
     static constexpr int TILES = 0;
     static constexpr int XTOP = TileLds<OP>::BYTES;
     static constexpr int END = XTOP + 16 * 64 * 16;
@@ -507,7 +507,7 @@ __device__ __forceinline__ void c128_invert_and_apply_rows(char* lds, const void
     v4f D[10], Wc[2][4];
     RhsRows<OP> x;
     x.init(rhs.r[0], tok0, h, H, valid, ln);
-    c128_invert<KD, OP, METHOD, DKS, W>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
+    c128_invert<KD, OP, METHOD, DKS, W, false>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
         // this wave's rows of X: requested as soon as the keys' registers are free
         __builtin_amdgcn_sched_barrier(0);
         x.template issue<W>(0);

@@ -47,14 +47,14 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     const GdnArgs& f = a.f;
 #if TRIINV_INST_NB == 8
     // C = 128 on two wavefronts per chunk (c128_solve.hpp).  Two right-hand sides: split by columns, the inverse's tiles
-    // published once per side.  One right-hand side: split by rows (whole 256-byte row pieces on both waves) where that
-    // kernel is the fastest or the only one -- the blocked recursion with 16-bit operands (166 against 170 us on the
-    // stress workload for the one-wavefront kernel below, 245 against 255 us at d_x = 256), 16-bit keys of d_k = 64 (the
-    // one-wavefront build of that case does not fit the register file without spilling) and fp32 keys of d_k = 128 (one
-    // wavefront cannot hold a chunk's 256 registers of keys).  The mixed recursion and fp32 operands keep the
-    // one-wavefront kernel (164 against 166 us, 363 against 444 us).
+    // published once per side.  One right-hand side: split by rows (whole 256-byte row pieces on both waves, four
+    // workgroups per compute unit) with 16-bit operands (154 against 170 us on the stress workload for the one-wavefront
+    // kernel below, 156 against 164 us with the mixed recursion, 249 against 255 us at d_x = 256), and where it is the
+    // only kernel: 16-bit keys of d_k = 64 (the one-wavefront build of that case does not fit the register file without
+    // spilling) and fp32 keys of d_k = 128 (one wavefront cannot hold a chunk's 256 registers of keys).  fp32 operands
+    // keep the one-wavefront kernel otherwise (363 against 444 us).
     constexpr bool SINGLE_ON_TWO_WAVES = (KD != OP_F32 && DKS == 2) || (KD == OP_F32 && DKS == 8);
-    constexpr bool SINGLE_BY_ROWS = SINGLE_ON_TWO_WAVES || (OP != OP_F32 && METHOD == M_BLOCK);
+    constexpr bool SINGLE_BY_ROWS = SINGLE_ON_TWO_WAVES || OP != OP_F32;
     if (a.n_rhs == 2 || SINGLE_ON_TWO_WAVES) {
         if (!rows_fit_32_bits(a)) return 1;
     }
