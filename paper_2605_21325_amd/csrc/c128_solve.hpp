@@ -221,10 +221,12 @@ template <int OP> struct RhsRows {
     }
 };
 
-// Published tiles: element type = operand type, 16 rows of TILE_LD elements.
+// Published tiles: element type = operand type, 16 rows of TILE_LD elements.  16-bit tiles go without padding (a set is
+// 18 KB, two sets and the recursion fit four workgroups per compute unit): the 8-byte row pieces read_t / write_t move
+// stay conflict-free, the 2-byte column writes of write_n become two-way conflicts.  fp32 tiles keep a stride of 20.
 template <int OP> struct TileLds {
     typedef typename std::conditional<OP == OP_F32, float, uint16_t>::type elem;
-    static constexpr int TILE_LD = 20;
+    static constexpr int TILE_LD = OP == OP_F32 ? 20 : 16;
     static constexpr int TILE_ELEMS = 16 * TILE_LD;
     static constexpr int BYTES = 36 * TILE_ELEMS * (int)sizeof(elem);
 
