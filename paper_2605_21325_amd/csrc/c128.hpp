@@ -80,10 +80,10 @@ __host__ __device__ constexpr int c128_t11_slot(int d, int c) { return c == 1 ? 
 
 // Tile source of a wave's own 64 x 64 diagonal block: Gram products of its own keys, the scalar gate of the whole
 // chunk (tile rows / columns 4 W .. 4 W + 3).
-template <int KD, int DKS, int W> struct DiagA {
+template <int KD, int DKS, int W, bool NOGATE> struct DiagA {
     static constexpr bool kFromMemory = false;
     const HalfKeys<KD, DKS>& hk;
-    const GateVec<8>& gate;
+    const GateVec<8, NOGATE>& gate;
     Lane ln;
     template <bool TR> __device__ __forceinline__ v4f get(int i, int j) const
     {
@@ -142,7 +142,7 @@ __device__ __forceinline__ void c128_diagonal_block(const DiagSrc& diag, v4f (&D
 // wave's block D is final (a place to send it on its way while the off-diagonal block is formed).
 // keys_done(): called in the second phase once this wave's tiles of A21 exist: the keys' registers and the gate's are
 // free from there on, and 40 tile products follow (a place to start loads whose data is needed after them).
-template <int KD, int OP, int METHOD, int DKS, int W, bool WITH_MAIL = true, class Hook, class Hook2, class Hook3 = NoHook>
+template <int KD, int OP, int METHOD, int DKS, int W, bool WITH_MAIL = true, bool NOGATE = false, class Hook, class Hook2, class Hook3 = NoHook>
 __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
                                             int64_t tok_stride, int valid, int aux, Lane ln, v4f (&D)[10], v4f (&Wc)[2][4],
                                             Hook keys_loaded, Hook2 block_done, Hook3 keys_done = Hook3())
@@ -155,7 +155,7 @@ __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t r
     kvec* keys_top = reinterpret_cast<kvec*>(lds + LY::KEYS_TOP);   // [tile row 1..3][k-step][lane]
     Opnd<OP>* t22_lds = reinterpret_cast<Opnd<OP>*>(lds + LY::T22);
     Opnd<OP>* t11_lds = reinterpret_cast<Opnd<OP>*>(lds + LY::T11);
-    GateVec<8> gate;
+    GateVec<8, NOGATE> gate;
     gate.issue(bc, gc, tok_stride, ln, valid);
     HalfKeys<KD, DKS> hk;
     hk.load(Kc, row_stride, valid, 64 * W, ln);
@@ -171,7 +171,7 @@ __device__ __forceinline__ void c128_invert(char* lds, const void* Kc, int64_t r
                 keys_top[((i - 1) * DKS + s) * 64 + lane] = hk.k[i][s];
         }
 
-    const DiagA<KD, DKS, W> diag{hk, gate, ln};
+    const DiagA<KD, DKS, W, NOGATE> diag{hk, gate, ln};
     c128_diagonal_block<OP, METHOD, W>(diag, D, small, t11_lds, t22_lds, aux, ln);
     __syncthreads();  // the keys and the diagonal-block inverses the other wave needs are in LDS
     block_done();
@@ -263,13 +263,13 @@ __device__ __forceinline__ void c128_merge(const Opnd<OP> (&a21)[4][4], const v4
 template <int W>
 __device__ __forceinline__ void c128_store_result(v4f* mail, float* strip, Out Tm, const v4f (&D)[10], const v4f (&Wc)[2][4], Lane ln);
 
-template <int KD, int OP, int METHOD, int DKS, int W>
+template <int KD, int OP, int METHOD, int DKS, int W, bool NOGATE>
 __device__ __forceinline__ void c128_invert_and_store(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
                                                       int64_t tok_stride, int valid, int aux, Out Tm, Lane ln)
 {
     typedef C128Lds<KD, OP, DKS, METHOD> LY;
     v4f D[10], Wc[2][4];
-    c128_invert<KD, OP, METHOD, DKS, W>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook());
+    c128_invert<KD, OP, METHOD, DKS, W, true, NOGATE>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook());
     c128_store_result<W>(reinterpret_cast<v4f*>(lds + LY::MAIL), reinterpret_cast<float*>(lds + LY::STRIPS) + W * STORE_LDS_FLOATS, Tm, D,
                          Wc, ln);
 }
@@ -310,7 +310,7 @@ __device__ __forceinline__ void c128_store_result(v4f* mail, float* strip, Out T
 // Fused kernel, scalar / no-gate kinds, C = 128, d_k = 64 or 128 (DKS k-steps): blocked, mixed (b0 = 16, 32) and
 // direct-leaf recursion.  One workgroup of two wavefronts per matrix; workgroups of the H heads of one (batch, chunk)
 // run back to back on one XCD (head_group_swizzle).
-template <int KD, int OP, int METHOD, int DKS>
+template <int KD, int OP, int METHOD, int DKS, bool NOGATE>
 __global__ __launch_bounds__(128) void k_gdn_tri_inv_c128(const void* __restrict__ K, const float* __restrict__ beta,
                                                           const float* __restrict__ g, float* __restrict__ T, int64_t n_chunk,
                                                           ChunkMap map, int H, int d_k, int aux, int out_dt)
@@ -330,9 +330,9 @@ __global__ __launch_bounds__(128) void k_gdn_tri_inv_c128(const void* __restrict
     const float* gcp = g ? g + tok0 * H + h : nullptr;
     const Out Tm = out_matrix(T, m, C, out_dt);
     if (w == 0)
-        c128_invert_and_store<KD, OP, METHOD, DKS, 0>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, pos.valid, aux, Tm, ln);
+        c128_invert_and_store<KD, OP, METHOD, DKS, 0, NOGATE>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, pos.valid, aux, Tm, ln);
     else
-        c128_invert_and_store<KD, OP, METHOD, DKS, 1>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, pos.valid, aux, Tm, ln);
+        c128_invert_and_store<KD, OP, METHOD, DKS, 1, NOGATE>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, pos.valid, aux, Tm, ln);
 }
 
 }  // namespace triinv

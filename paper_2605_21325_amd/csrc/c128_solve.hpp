@@ -398,7 +398,7 @@ __device__ __forceinline__ void c128_apply(char* tiles_lds, char* scale_lds, v4f
     }
 }
 
-template <int KD, int OP, int METHOD, int DKS, int W, int NRHS>
+template <int KD, int OP, int METHOD, int DKS, int W, int NRHS, bool NOGATE>
 __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
                                                       int64_t tok_stride, const RhsList& rhs, int64_t tok0, int h, int H, int valid,
                                                       int aux, Lane ln)
@@ -409,7 +409,7 @@ __device__ __forceinline__ void c128_invert_and_apply(char* lds, const void* Kc,
     v4f D[10], Wc[2][4];
     RhsHalf<OP> x;
     x.init(rhs.r[0], tok0, h, H, valid, ln);
-    c128_invert<KD, OP, METHOD, DKS, W, false>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
+    c128_invert<KD, OP, METHOD, DKS, W, false, NOGATE>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
         // X's first column group: requested as soon as the keys' registers are free, in flight during the last 40 tile
         // products of the recursion and while the inverse's tiles are published
         __builtin_amdgcn_sched_barrier(0);
@@ -498,7 +498,7 @@ __device__ __forceinline__ void c128_apply_rows(char* tiles_lds, char* xtop_lds,
     }
 }
 
-template <int KD, int OP, int METHOD, int DKS, int W>
+template <int KD, int OP, int METHOD, int DKS, int W, bool NOGATE>
 __device__ __forceinline__ void c128_invert_and_apply_rows(char* lds, const void* Kc, int64_t row_stride, const float* bc, const float* gc,
                                                            int64_t tok_stride, const RhsList& rhs, int64_t tok0, int h, int H, int valid,
                                                            int aux, Lane ln)
@@ -509,7 +509,7 @@ __device__ __forceinline__ void c128_invert_and_apply_rows(char* lds, const void
     v4f D[10], Wc[2][4];
     RhsRows<OP> x;
     x.init(rhs.r[0], tok0, h, H, valid, ln);
-    c128_invert<KD, OP, METHOD, DKS, W, false>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
+    c128_invert<KD, OP, METHOD, DKS, W, false, NOGATE>(lds, Kc, row_stride, bc, gc, tok_stride, valid, aux, ln, D, Wc, NoHook(), NoHook(), [&]() {
         // this wave's rows of X: requested as soon as the keys' registers are free
         __builtin_amdgcn_sched_barrier(0);
         x.template issue<W>(0);
@@ -520,7 +520,7 @@ __device__ __forceinline__ void c128_invert_and_apply_rows(char* lds, const void
 
 // Fused kernel, scalar / no-gate kinds, C = 128: blocked or mixed recursion, then the inverse applied to one right-hand side
 // split by rows (c128_apply_rows).  One workgroup of two wavefronts per chunk matrix.
-template <int KD, int OP, int METHOD, int DKS>
+template <int KD, int OP, int METHOD, int DKS, bool NOGATE>
 __global__ __launch_bounds__(128) void k_gdn_tri_solve_c128_rows(const void* __restrict__ K, const float* __restrict__ beta,
                                                                  const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
                                                                  int H, int d_k, int aux)
@@ -539,14 +539,14 @@ __global__ __launch_bounds__(128) void k_gdn_tri_solve_c128_rows(const void* __r
     const float* bcp = beta + tok0 * H + h;
     const float* gcp = g ? g + tok0 * H + h : nullptr;
     if (w == 0)
-        c128_invert_and_apply_rows<KD, OP, METHOD, DKS, 0>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
+        c128_invert_and_apply_rows<KD, OP, METHOD, DKS, 0, NOGATE>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
     else
-        c128_invert_and_apply_rows<KD, OP, METHOD, DKS, 1>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
+        c128_invert_and_apply_rows<KD, OP, METHOD, DKS, 1, NOGATE>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
 }
 
 // Fused kernel, scalar / no-gate kinds, C = 128, d_k = 64 or 128: blocked or mixed recursion, then the inverse applied to
 // one or two right-hand sides.  One workgroup of two wavefronts per chunk matrix.
-template <int KD, int OP, int METHOD, int DKS, int NRHS>
+template <int KD, int OP, int METHOD, int DKS, int NRHS, bool NOGATE>
 __global__ __launch_bounds__(128) void k_gdn_tri_solve_c128(const void* __restrict__ K, const float* __restrict__ beta,
                                                             const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
                                                             int H, int d_k, int aux)
@@ -565,9 +565,9 @@ __global__ __launch_bounds__(128) void k_gdn_tri_solve_c128(const void* __restri
     const float* bcp = beta + tok0 * H + h;
     const float* gcp = g ? g + tok0 * H + h : nullptr;
     if (w == 0)
-        c128_invert_and_apply<KD, OP, METHOD, DKS, 0, NRHS>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
+        c128_invert_and_apply<KD, OP, METHOD, DKS, 0, NRHS, NOGATE>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
     else
-        c128_invert_and_apply<KD, OP, METHOD, DKS, 1, NRHS>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
+        c128_invert_and_apply<KD, OP, METHOD, DKS, 1, NRHS, NOGATE>(lds, Kc, (int64_t)H * d_k, bcp, gcp, H, rhs, tok0, h, H, pos.valid, aux, ln);
 }
 
 }  // namespace triinv

@@ -123,8 +123,10 @@ template <int KD, int METHOD, int DKS, bool REFINE = false> static int go_gdn(co
     // keep one wavefront per matrix: their four-instruction tile products make the kernel matrix-core bound, and the
     // exchange of fp32 tiles through LDS costs more than the second wavefront returns (250 against 226 us on the stress workload).
     if constexpr (!REFINE && OP != OP_F32 && (METHOD == M_BLOCK || METHOD == M_MIXED || METHOD == M_MIXED32 || METHOD == M_BLOCK_DIRECT))
-        return launch_kernel(a.dry, k_gdn_tri_inv_c128<KD, OP, METHOD, DKS>, dim3((unsigned)a.n_mat), dim3(128), 0, a.stream, a.K, a.beta,
-                             a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
+        return a.g ? launch_kernel(a.dry, k_gdn_tri_inv_c128<KD, OP, METHOD, DKS, false>, dim3((unsigned)a.n_mat), dim3(128), 0, a.stream, a.K,
+                                   a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt)
+                   : launch_kernel(a.dry, k_gdn_tri_inv_c128<KD, OP, METHOD, DKS, true>, dim3((unsigned)a.n_mat), dim3(128), 0, a.stream, a.K,
+                                   a.beta, a.g, a.T, a.n_chunk, a.map, a.H, a.d_k, a.iters, a.out_dt);
     else
 #endif
         return launch_kernel(a.dry, k_gdn_tri_inv<KD, OP, NB, METHOD, DKS, REFINE, WPB>, dim3((unsigned)((a.n_mat + WPB - 1) / WPB)),

@@ -109,7 +109,8 @@ template <> __device__ __forceinline__ v4f gram_step<OP_BF16>(v8bf a, v8bf b, v4
 //   A_ij = beta_i exp(g_i - g_j) S_ij for i > j, else 0      (paper Table 1, GDN / DeltaNet rows).
 // g is kept multiplied by log2(e) (done once per token when the values are staged), so that the gate of an element is
 // one subtraction and one exp2; without a gate g = 0 and exp2(0) = 1 exactly, so that kind needs no code of its own.
-template <int NB> struct GateVec {
+// NOGATE: the launch is known to have no gate (gc null): the factor exp(g_i - g_j) is 1 and its exponentials are left out.
+template <int NB, bool NOGATE = false> struct GateVec {
     static constexpr int C = 16 * NB;
     float beta_n[NB], g_n[NB];   // g_*: g log2(e)
     v4f beta_q[NB], g_q[NB];
@@ -181,7 +182,7 @@ template <int NB> struct GateVec {
             // N: element (row 16i + 4q + r, col 16j + n);  T: element (row 16i + n, col 16j + 4q + r)
             const float b = TR ? beta_n[i] : beta_q[i][r];
             const float d = TR ? (g_n[i] - g_q[j][r]) : (g_q[i][r] - g_n[j]);  // (g_i - g_j) log2 e
-            const float w = b * __builtin_amdgcn_exp2f(d);                      // beta_i exp(g_i - g_j)
+            const float w = NOGATE ? b : b * __builtin_amdgcn_exp2f(d);        // beta_i exp(g_i - g_j)
             const bool low = (i != j) || (TR ? (ln.n > 4 * ln.q + r) : (4 * ln.q + r > ln.n));
             a[r] = low ? w * s[r] : 0.f;
         }

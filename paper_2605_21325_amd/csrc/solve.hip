@@ -60,12 +60,16 @@ template <int KD, int METHOD, int DKS> static int go_gdn(const SolveArgs& a)
     }
     if constexpr (SINGLE_BY_ROWS)
         if (a.n_rhs == 1 && rows_fit_32_bits(a))
-            return launch_kernel(f.dry, k_gdn_tri_solve_c128_rows<KD, OP, METHOD, DKS>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
-                                 f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+            return f.g ? launch_kernel(f.dry, k_gdn_tri_solve_c128_rows<KD, OP, METHOD, DKS, false>, dim3((unsigned)f.n_mat), dim3(128), 0,
+                                       f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters)
+                       : launch_kernel(f.dry, k_gdn_tri_solve_c128_rows<KD, OP, METHOD, DKS, true>, dim3((unsigned)f.n_mat), dim3(128), 0,
+                                       f.stream, f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
     // (fp32 operands: the two sets of fp32 tiles take 93 KB of LDS, one workgroup per compute unit)
     if (a.n_rhs == 2)
-        return launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream, f.K,
-                             f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
+        return f.g ? launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2, false>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
+                                   f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters)
+                   : launch_kernel(f.dry, k_gdn_tri_solve_c128<KD, OP, METHOD, DKS, 2, true>, dim3((unsigned)f.n_mat), dim3(128), 0, f.stream,
+                                   f.K, f.beta, f.g, rhs_of(a), f.n_chunk, f.map, f.H, f.d_k, f.iters);
     if constexpr (!SINGLE_ON_TWO_WAVES)
 #endif
     {
