@@ -1132,6 +1132,22 @@ def test_solve_column_counts(d_x, op):
                 ctx=dict(inp=inp, rhs=rhs, gate_kind=w.gate_kind, op=op, scale=False))
 
 
+@pytest.mark.parametrize("d_x", [8, 72, 128, 200, 256, 512])
+@pytest.mark.parametrize("op", [tri.F32, tri.BF16], ids=lambda o: tri.DTYPE_NAMES[o])
+@pytest.mark.parametrize("idx,kw", [(1, {}), (3, dict(B=1)), (4, {}), (1, dict(k_dtype="f32"))], ids=["scalar", "channel", "nogate", "f32keys"])
+def test_solve_column_counts_c128(idx, kw, d_x, op):
+    # C = 128 on two wavefronts: part of a column group, exactly one, several (the waves meet again between groups), a
+    # last group that is not full; the last chunk is short (300 = 2 * 128 + 44 tokens: a tile row cut in the middle)
+    w, inp, rhs = solve_case(idx, d_x, op, Tlen=300, H=3, C=128, d_k=128, **kw)
+    W_ref = oracle.gdn_chunk_tri_solve(inp["K"], inp["beta"], inp["g"], rhs["X"], rhs["row_scale"], w.gate_kind, w.C)
+    g = None if inp["g"] is None else inp["g"].to(DEV)
+    W = torch.full(rhs["X"].shape, float("nan"), dtype=XDT[op], device=DEV)
+    tri.gdn_chunk_tri_solve(inp["K"].to(DEV), inp["beta"].to(DEV), g, rhs["X"].to(DEV), w.C, row_scale=rhs["row_scale"].to(DEV), W=W,
+                            gate_kind=w.gate_kind)
+    check_solve(W, W_ref, SOLVE_TOL[op], f"C=128 cfg{idx} {kw} d_x={d_x}", C=w.C,   # every element written (no NaN left)
+                ctx=dict(inp=inp, rhs=rhs, gate_kind=w.gate_kind, op=op))
+
+
 @pytest.mark.parametrize("C", [16, 32, 64, 128])
 @pytest.mark.parametrize("Tlen", [1, 50, 64, 150])
 @pytest.mark.parametrize("gate_kind", [tri.GATE_SCALAR, tri.GATE_PER_CHANNEL, tri.GATE_NONE])
