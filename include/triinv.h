@@ -235,8 +235,8 @@ int gdn_chunk_tri_inv_varlen(const void* K, const float* beta, const float* g, f
  *   K, beta, g, B, Tlen, H, d_k, C, k_dtype, gate_kind, hip_stream: as in gdn_chunk_tri_inv_ex.
  *   method     TRIINV_BLOCK_RECURSIVE or TRIINV_MIXED (with TRIINV_FLAG_MXR_R).  C <= 64 takes every gate kind
  *              and every supported d_k.  C = 128 takes the scalar / no-gate kinds with d_k = 64 or 128 and the
- *              per-channel gate with any supported d_k; there H * d_x * 128 elements of X must stay below
- *              2^31 bytes.
+ *              per-channel gate with any supported d_k.  The rows of X one chunk covers (H * d_x * C elements)
+ *              must stay below 2^31 bytes: the kernels address them with 32-bit offsets.
  *              Anything else returns TRIINV_ERR_UNSUPPORTED.
  *   flags      TRIINV_FLAG_MXR_R only.
  * Accuracy: that of the method's inverse (see tri_inv_ex) plus one rounding of the scaled inverse

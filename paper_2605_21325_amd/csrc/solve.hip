@@ -31,11 +31,12 @@ static RhsList rhs_of(const SolveArgs& a)
     return l;
 }
 
-// The two-wavefront kernels address a right-hand side with 32-bit row offsets: 128 rows of H * d_x elements.
+// The two-wavefront kernels at C = 128 and every kernel at C <= 64 address a right-hand side with 32-bit row offsets: C
+// rows of H * d_x elements.
 [[maybe_unused]] static bool rows_fit_32_bits(const SolveArgs& a)
 {
     for (int k = 0; k < a.n_rhs; ++k)
-        if ((int64_t)a.f.H * a.d_x[k] * (OP == OP_F32 ? 4 : 2) * 128 >= (1LL << 31)) return false;
+        if ((int64_t)a.f.H * a.d_x[k] * (OP == OP_F32 ? 4 : 2) * (16 * NB) >= (1LL << 31)) return false;
     return true;
 }
 
@@ -146,6 +147,7 @@ int CAT(launch_solve_nb, TRIINV_INST_NB, _op, TRIINV_INST_OP)(const SolveArgs& a
     const GdnArgs& f = a.f;
     if (f.refine) return 1;
     if (a.n_rhs < 1 || a.n_rhs > MAX_RHS) return 1;
+    if (NB <= 4 && !rows_fit_32_bits(a)) return 1;  // (H * d_x beyond 8 million elements)
     if (f.gate == G_CHANNEL) {
         if (f.method == M_BLOCK) return go_kda<M_BLOCK>(a);
         if (f.method == M_MIXED) return go_kda<M_MIXED>(a);

@@ -98,6 +98,15 @@ template <int OP, int NB> struct RhsX {
     static constexpr int ESZ = OP == OP_F32 ? 4 : 2;
     static constexpr int VEC = 16 / ESZ;  // columns per lane
     static constexpr int GW = 16 * VEC;   // columns per group
+    // C <= 64: X and W are addressed through buffer descriptors based at the chunk's first row of this head, with one 32-bit
+    // byte offset per row that loads and stores share (64 rows of H * d_x elements stay below 2^31 bytes; the launcher
+    // checks).  With 64-bit pointers every row's load address and store address is a register pair of its own: 64
+    // registers at C = 64, which cost the kernels with two right-hand sides their second wavefront per SIMD (299
+    // registers against 236).
+    // C = 128 (one wavefront per chunk: the fallback for tensors too wide for 32-bit offsets) keeps the pointers.
+    static constexpr bool BUF = NB <= 4;
+    static constexpr int CACHE_NT = 2;
+    __amdgpu_buffer_rsrc_t xb, wb;
     const char* xc;      // element (chunk row 0, this head, column 0) of X
     char* wc;            // the same element of W
     int64_t row_bytes;   // H * d_x * ESZ
@@ -116,6 +125,11 @@ template <int OP, int NB> struct RhsX {
         const int64_t e0 = (tok0 * H + h) * (int64_t)d_x * ESZ;
         xc = static_cast<const char*>(a.X) + e0;
         wc = static_cast<char*>(a.W) + e0;
+        if constexpr (BUF) {
+            const int span = (valid - 1) * (int)row_bytes + d_x * ESZ;  // the chunk's real rows: nothing beyond is read or written
+            xb = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(xc), 0, span, 0x00020000);
+            wb = __builtin_amdgcn_make_buffer_rsrc(wc, 0, span, 0x00020000);
+        }
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
@@ -141,7 +155,10 @@ template <int OP, int NB> struct RhsX {
                 if (j < j0 || j >= j1) continue;
                 const int row = 16 * j + 4 * ln.q + r;
                 const int rc = row < valid ? row : valid - 1;
-                raw[j][r] = load_x<OP>(xc + rc * row_bytes + col * ESZ);
+                if constexpr (BUF)
+                    raw[j][r] = __builtin_bit_cast(XRow<OP>, __builtin_amdgcn_raw_buffer_load_b128(xb, rc * (int)row_bytes + col * ESZ, 0, 0));
+                else
+                    raw[j][r] = load_x<OP>(xc + rc * row_bytes + col * ESZ);
             }
     }
 
@@ -154,6 +171,21 @@ template <int OP, int NB> struct RhsX {
         for (int r = 0; r < 4; ++r) {
             const int row = 16 * i + 4 * ln.q + r;
             if (row >= valid) continue;
+            if constexpr (BUF) {
+                // (the whole offset in the per-lane part of the address: a 16-byte buffer store with a register as its
+                // uniform offset is not followed by the wait state its data registers need before they are written again)
+                v4u v;
+                if constexpr (OP == OP_F32)
+                    v = __builtin_bit_cast(v4u, v4f{acc[0][r], acc[1][r], acc[2][r], acc[3][r]});
+                else if constexpr (OP == OP_F16)
+                    v = v4u{pack2_f16(acc[0][r], acc[1][r]), pack2_f16(acc[2][r], acc[3][r]), pack2_f16(acc[4][r], acc[5][r]),
+                            pack2_f16(acc[6][r], acc[7][r])};
+                else
+                    v = v4u{pack2_bf16(acc[0][r], acc[1][r]), pack2_bf16(acc[2][r], acc[3][r]), pack2_bf16(acc[4][r], acc[5][r]),
+                            pack2_bf16(acc[6][r], acc[7][r])};
+                __builtin_amdgcn_raw_buffer_store_b128(v, wb, row * (int)row_bytes + col * ESZ, 0, CACHE_NT);
+                continue;
+            }
             char* p = wc + row * row_bytes + col * ESZ;
             if constexpr (OP == OP_F32) {
                 __builtin_nontemporal_store(v4f{acc[0][r], acc[1][r], acc[2][r], acc[3][r]}, reinterpret_cast<v4f*>(p));
