@@ -277,8 +277,10 @@ __device__ __forceinline__ void invert_and_apply(const ASrc& src, RhsX<OP, NB>& 
 // tile of A is formed first, so the keys' registers are free); 2: after the recursion; 3: as many tile rows as fit beside
 // the keys before the recursion, the rest inside its last merge or after it (see invert_and_apply).
 // spread: see fused_matrix_index.
+// (C = 64: at most two wavefronts per SIMD -- like the storing kernels, these run slower with more resident: 146 against
+// 138 us at three on the batched workload, 122 against 120 us with d_k = 64, whose build would otherwise fit three)
 template <int KD, int OP, int NB, int METHOD, int DKS, int WPB, int XPOS, int NRHS>
-__global__ __launch_bounds__(64 * WPB) void k_gdn_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
+__global__ __launch_bounds__(64 * WPB) __attribute__((amdgpu_waves_per_eu(1, NB == 4 ? 2 : 8))) void k_gdn_tri_solve(const void* __restrict__ K, const float* __restrict__ beta,
                                                             const float* __restrict__ g, RhsList rhs, int64_t n_chunk, ChunkMap map,
                                                             int H, int d_k, int aux, int spread)
 {
